@@ -1,0 +1,153 @@
+/*
+ * railsched - batched LPT rail spraying of MoE all-to-all traffic on one AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of RailS (arXiv 2510.19262): router logits -> top-k routing ->
+ * GPU-to-GPU byte matrix D^(1) -> fixed-size chunks -> per-node descending sort ->
+ * greedy least-loaded-rail assignment -> per-NIC send/receive loads, completion time,
+ * lower bound.  The rails are simulated arithmetically; nothing is transmitted.
+ *
+ * Notation (Section 4.1, System Model): M domains (nodes); N GPUs = NICs = rails per domain;
+ * G = M*N GPUs; GPU id g = d*N + n, 0-based; C = chunk bytes; R2 = rate of one rail.
+ * "batch" is the number of independent traffic matrices (e.g. MoE layers) processed in one call;
+ * an *instance* is one (matrix b, source node k) pair, numbered b*M + k.  Instances are scheduled
+ * independently: each node decides from local information only (Sections 1 and 3.2).
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name starts with h_.  The caller owns every
+ *     buffer (inputs, outputs, workspace); the library allocates nothing, keeps no state between
+ *     calls (LoadState is reset for every all-to-all round, Section 5.2) and never frees anything.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is enqueued
+ *     asynchronously on it; no call synchronises the host with the device.
+ *   - Every function returns 0 (RAILSCHED_OK) or a negative railsched_status.  Arguments are
+ *     validated on the host before anything is launched; on an error nothing has been enqueued.
+ *   - All outputs are integers and are defined bit-exactly.
+ *   - Limits: 1 <= N <= 64, 1 <= M, G <= 16384, N*G <= 16384 for chunk_sort, 1 <= k <= E <= 1024,
+ *     1 <= C < 2^32, every instance holds fewer than 2^32 chunks and fewer than 2^56 bytes.
+ */
+#ifndef RAILSCHED_H
+#define RAILSCHED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum railsched_status {
+    RAILSCHED_OK = 0,
+    RAILSCHED_ERR_INVALID_ARG = -1, /* a size or count is out of its documented range           */
+    RAILSCHED_ERR_NULL_PTR    = -2, /* a required pointer is NULL                               */
+    RAILSCHED_ERR_UNSUPPORTED = -3, /* valid in the paper's model but beyond this build's limits */
+    RAILSCHED_ERR_CAPACITY    = -4, /* reserved: record arrays smaller than the chunk count      */
+    RAILSCHED_ERR_WORKSPACE   = -5, /* workspace missing or smaller than *_workspace_bytes()     */
+    RAILSCHED_ERR_HIP         = -6  /* the HIP runtime refused a launch                          */
+} railsched_status;
+
+/* Topology and chunking of the Rail fabric (Section 4.1; chunk size: Section 5.1, "Flow Splitting
+ * and Atomicity").  Plain data, passed by HOST pointer. */
+typedef struct railsched_topo {
+    int32_t nodes;              /* M                                                             */
+    int32_t rails;              /* N                                                             */
+    int64_t chunk_bytes;        /* C                                                             */
+    int64_t rail_bw_Bps;        /* R2 in bytes/s; only used by callers to turn bytes into time   */
+    int32_t include_intra_node; /* 0: traffic inside a node is not inter-domain and is skipped   */
+    int32_t reserved;           /* must be 0                                                     */
+} railsched_topo_t;
+
+const char *railsched_version(void);
+const char *railsched_strerror(int status);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 1 - gating decision (Algorithm 1 step 1; Top-K expert selection of Section 6.3).
+ * For every token row the indices of the k largest logits, largest first; equal logits (IEEE
+ * comparison, so -0 == +0) are ordered by ascending expert index.  Logits must be finite.
+ *   logits   [rows][E] fp32, row-major            (in)
+ *   topk_idx [rows][k] int32                      (out)
+ * rows may be 0.  Errors: NULL_PTR, INVALID_ARG (rows < 0, E < 1, k < 1, k > E), UNSUPPORTED (E > 1024).
+ * ------------------------------------------------------------------------------------------- */
+int railsched_route_topk(const float *logits, int64_t rows, int32_t E, int32_t k,
+                         int32_t *topk_idx, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 2 - GPU-to-GPU traffic matrix D^(1) (Section 4.1; Algorithm 1 step 2, selection of input
+ * slices by gate and expert assignment).  Row r of matrix b belongs to source GPU
+ * s = r / tokens_per_gpu; its slot j goes to GPU expert_gpu[topk_idx[r][j]][t mod R] with
+ * t = r mod tokens_per_gpu (R replicas of every expert; R = 1 puts an expert on a single GPU);
+ * every (token, slot) adds payload_bytes to D1[b][s][d].  A token whose slots hit the same GPU
+ * counts once per slot.
+ *   topk_idx   [batch*G*tokens_per_gpu][k] int32, values in [0,E)  (in; out-of-range values are ignored)
+ *   expert_gpu [E][R] int32, values in [0,G)                        (in; same rule)
+ *   D1         [batch][G][G] int64                                  (out, fully overwritten)
+ * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (G > 16384).
+ * ------------------------------------------------------------------------------------------- */
+int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, int64_t tokens_per_gpu, int32_t k,
+                             const int32_t *expert_gpu, int32_t E, int32_t R, int64_t payload_bytes,
+                             const railsched_topo_t *h_topo, int64_t *D1, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 3 - flow splitting and LPT sorting (Section 5.1 "Flow Splitting and Atomicity";
+ * Algorithm 2 steps 1-2).  For instance (b,k) the flows of node k's N GPUs are taken in canonical
+ * order (local GPU n ascending, destination GPU ascending; destinations inside node k skipped
+ * unless include_intra_node); a flow of B bytes yields floor(B/C) chunks of C bytes and one of
+ * B mod C bytes if that is non-zero.  The instance's chunks are then ordered by descending weight,
+ * ties by source GPU, destination GPU and position in the flow (a stable sort of the canonical list).
+ *   D1         [batch][G][G] int64, entries >= 0                     (in)
+ *   chunk_off  [batch*M + 1] int64: exclusive scan of instance sizes (out)
+ *   chunk_w    [capacity] uint32: chunk weight in bytes              (out, nullable)
+ *   chunk_flow [capacity] uint32: n*G + destination GPU              (out)
+ *   perm       [capacity] uint32: canonical position inside the instance of the chunk now at this
+ *              sorted position                                      (out, nullable)
+ * With chunk_w == NULL only chunk_off is produced (a count query: read chunk_off[batch*M] to size
+ * the record arrays).  If the total chunk count exceeds `capacity` the record arrays are left
+ * untouched and chunk_off is still complete: compare chunk_off[batch*M] with capacity after the
+ * stream has drained.
+ * Workspace: railsched_chunk_sort_workspace_bytes(batch, topo) bytes, 256-byte aligned.
+ * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (N*G > 16384, C >= 2^32), WORKSPACE.
+ * ------------------------------------------------------------------------------------------- */
+size_t railsched_chunk_sort_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo);
+int railsched_chunk_sort(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo,
+                         int64_t *chunk_off, uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm,
+                         int64_t capacity, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 4 - LPT iterative allocation (Algorithm 2, initialisation and step 3).  Per instance:
+ * LoadState[0..N) = 0; for every chunk in stored order j* = the lowest-numbered rail of minimum
+ * LoadState; rail[i] = j*; LoadState[j*] += w_i.  The final LoadState is the send load S[b][k][.]
+ * (Section 4.1, load matrix S).  Weights need not come from stage 3: any sequence is scheduled in
+ * the order given (the guarantees of Theorem 4 need it non-increasing).
+ *   chunk_off [batch*M + 1] int64   (in)
+ *   chunk_w   [chunk_off[batch*M]]  (in)
+ *   rail      [chunk_off[batch*M]] uint8, values in [0,N)  (out)
+ *   S         [batch][M][N] int64                          (out)
+ * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (N > 64).
+ * ------------------------------------------------------------------------------------------- */
+int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
+                        const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 5 - load evaluation (Section 4.1 load matrices S and R; Theorem 2; Theorem 3).
+ * Rail n of a source node ends on NIC n of the destination node, so a chunk whose destination GPU
+ * lies in node f and that was put on rail n adds its weight to R[b][f][n].
+ *   R     [batch][M][N] int64                                   (out)
+ *   stats [batch][8] int64                                      (out)
+ *     [0] makespan = max over all entries of S[b] and R[b]  (Theorem 2: T = makespan / R2)
+ *     [1] max send load   [2] max receive load
+ *     [3] lower bound max( max_k ceil(sum_n S[b][k][n] / N), max_f ceil(sum_n R[b][f][n] / N), w_max )
+ *         (uniform split of Theorem 3; one chunk is indivisible, Theorem 4 proof)
+ *     [4] total bytes scheduled  [5] w_max  [6] chunk count
+ *     [7] max over nodes k of (max_n S[b][k][n] - min_n S[b][k][n])
+ * S is read as produced by stage 4.  No global atomics are used: every workgroup writes its
+ * partial receive loads to the workspace and a second kernel adds them in a fixed order.
+ * Workspace: railsched_eval_workspace_bytes(batch, topo) bytes, 256-byte aligned.
+ * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED, WORKSPACE.
+ * ------------------------------------------------------------------------------------------- */
+size_t railsched_eval_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo);
+int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w, const uint32_t *chunk_flow,
+                   const uint8_t *rail, const int64_t *S, int32_t batch, const railsched_topo_t *h_topo,
+                   int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAILSCHED_H */

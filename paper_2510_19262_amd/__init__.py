@@ -1,0 +1,10 @@
+"""railsched: batched LPT rail spraying of MoE all-to-all traffic on one MI355X.
+
+Thin ctypes binding over librailsched.so (hand-written HIP kernels for gfx950).
+Every step of the path runs in those kernels; this package only marshals arguments.
+"""
+from .binding import (  # noqa: F401
+    Topo, RailschedError, lib_path, load, version, strerror,
+    route_topk, traffic_matrix, chunk_sort, chunk_count, lpt_spray, eval, evaluate,
+    chunk_sort_workspace_bytes, eval_workspace_bytes, Plan,
+)

@@ -1,0 +1,282 @@
+"""ctypes marshalling for the railsched C ABI (include/railsched.h).
+
+PyTorch is used for device memory and streams only: tensors are allocated with
+torch, their data pointers and the current HIP stream are handed to the library.
+There is no fallback: if librailsched.so cannot be loaded, importing a symbol
+works but the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "librailsched.so")
+_lib = None
+
+EXPORTS = (
+    "railsched_version", "railsched_strerror", "railsched_route_topk", "railsched_traffic_matrix",
+    "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray",
+    "railsched_eval_workspace_bytes", "railsched_eval",
+)
+
+
+class RailschedError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class _TopoStruct(C.Structure):
+    _fields_ = [("nodes", C.c_int32), ("rails", C.c_int32), ("chunk_bytes", C.c_int64),
+                ("rail_bw_Bps", C.c_int64), ("include_intra_node", C.c_int32), ("reserved", C.c_int32)]
+
+
+@dataclass(frozen=True)
+class Topo:
+    """M nodes x N rails, chunk size C, rail rate R2 (Section 4.1 of the paper)."""
+    nodes: int
+    rails: int
+    chunk_bytes: int
+    rail_bw_Bps: int = 50_000_000_000
+    include_intra_node: int = 0
+
+    @property
+    def G(self) -> int:
+        return self.nodes * self.rails
+
+    def c(self) -> _TopoStruct:
+        return _TopoStruct(self.nodes, self.rails, self.chunk_bytes, self.rail_bw_Bps, self.include_intra_node, 0)
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load librailsched.so (building it first only if it is absent)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build(force=True)
+    lib = C.CDLL(_LIB_PATH)           # torch is imported above, so its HIP runtime is the one resolved
+    lib.railsched_version.restype = C.c_char_p
+    lib.railsched_strerror.restype = C.c_char_p
+    lib.railsched_strerror.argtypes = [C.c_int]
+    P, I32, I64, SZ = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    TP = C.POINTER(_TopoStruct)
+    lib.railsched_route_topk.argtypes = [P, I64, I32, I32, P, P]
+    lib.railsched_traffic_matrix.argtypes = [P, I32, I64, I32, P, I32, I32, I64, TP, P, P]
+    lib.railsched_chunk_sort_workspace_bytes.argtypes = [I32, TP]
+    lib.railsched_chunk_sort_workspace_bytes.restype = SZ
+    lib.railsched_chunk_sort.argtypes = [P, I32, TP, P, P, P, P, I64, P, SZ, P]
+    lib.railsched_lpt_spray.argtypes = [P, P, I32, TP, P, P, P]
+    lib.railsched_eval_workspace_bytes.argtypes = [I32, TP]
+    lib.railsched_eval_workspace_bytes.restype = SZ
+    lib.railsched_eval.argtypes = [P, P, P, P, P, I32, TP, P, P, P, SZ, P]
+    for fn in ("railsched_route_topk", "railsched_traffic_matrix", "railsched_chunk_sort", "railsched_lpt_spray",
+               "railsched_eval"):
+        getattr(lib, fn).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def version() -> str:
+    return load().railsched_version().decode()
+
+
+def strerror(status: int) -> str:
+    return load().railsched_strerror(int(status)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise RailschedError(status, where)
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# ---------------------------------------------------------------------------------- stage 1
+def route_topk(logits: torch.Tensor, k: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """[rows][E] fp32 -> [rows][k] int32 indices of the k largest logits, lowest index on ties."""
+    _dev(logits, torch.float32, "logits")
+    rows, E = logits.shape
+    if out is None:
+        out = torch.empty((rows, k), dtype=torch.int32, device=logits.device)
+    _dev(out, torch.int32, "out")
+    _check(load().railsched_route_topk(_ptr(logits), rows, E, k, _ptr(out), _stream()), "railsched_route_topk")
+    return out
+
+
+# ---------------------------------------------------------------------------------- stage 2
+def traffic_matrix(topk_idx: torch.Tensor, batch: int, tokens_per_gpu: int, expert_gpu: torch.Tensor,
+                   payload_bytes: int, topo: Topo, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """top-k indices + expert placement -> D1 [batch][G][G] int64 bytes."""
+    _dev(topk_idx, torch.int32, "topk_idx")
+    _dev(expert_gpu, torch.int32, "expert_gpu")
+    k = topk_idx.shape[1]
+    E, R = expert_gpu.shape
+    G = topo.G
+    if topk_idx.shape[0] != batch * G * tokens_per_gpu:
+        raise ValueError("topk_idx must hold batch*G*tokens_per_gpu rows")
+    if out is None:
+        out = torch.empty((batch, G, G), dtype=torch.int64, device=topk_idx.device)
+    _dev(out, torch.int64, "out")
+    t = topo.c()
+    _check(load().railsched_traffic_matrix(_ptr(topk_idx), batch, tokens_per_gpu, k, _ptr(expert_gpu), E, R,
+                                           payload_bytes, C.byref(t), _ptr(out), _stream()), "railsched_traffic_matrix")
+    return out
+
+
+# ---------------------------------------------------------------------------------- stage 3
+def chunk_sort_workspace_bytes(batch: int, topo: Topo) -> int:
+    t = topo.c()
+    return int(load().railsched_chunk_sort_workspace_bytes(batch, C.byref(t)))
+
+
+def eval_workspace_bytes(batch: int, topo: Topo) -> int:
+    t = topo.c()
+    return int(load().railsched_eval_workspace_bytes(batch, C.byref(t)))
+
+
+def chunk_count(D1: torch.Tensor, topo: Topo, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Count query: chunk_off [batch*M+1] int64 only."""
+    _dev(D1, torch.int64, "D1")
+    batch = D1.shape[0]
+    off = torch.empty(batch * topo.nodes + 1, dtype=torch.int64, device=D1.device)
+    if ws is None:
+        ws = _ws(chunk_sort_workspace_bytes(batch, topo), D1.device)
+    t = topo.c()
+    _check(load().railsched_chunk_sort(_ptr(D1), batch, C.byref(t), _ptr(off), None, None, None, 0,
+                                       _ptr(ws), ws.numel(), _stream()), "railsched_chunk_sort(count)")
+    return off
+
+
+def chunk_sort(D1: torch.Tensor, topo: Topo, want_perm: bool = True, capacity: Optional[int] = None,
+               out=None, ws: Optional[torch.Tensor] = None):
+    """D1 -> (chunk_off, chunk_w, chunk_flow, perm|None), every instance sorted by descending weight.
+
+    Without `capacity` a count query runs first and the host waits for the total (one
+    synchronisation) to size the record arrays.  With `capacity` (and optionally preallocated
+    `out` = (chunk_off, chunk_w, chunk_flow, perm)) the call is fully asynchronous; the record
+    arrays are left untouched if the total exceeds the capacity.
+    """
+    _dev(D1, torch.int64, "D1")
+    batch = D1.shape[0]
+    dev = D1.device
+    if ws is None:
+        ws = _ws(chunk_sort_workspace_bytes(batch, topo), dev)
+    if capacity is None:
+        capacity = int(chunk_count(D1, topo, ws)[-1].item())
+    if out is None:
+        off = torch.empty(batch * topo.nodes + 1, dtype=torch.int64, device=dev)
+        w = torch.empty(max(capacity, 1), dtype=torch.int32, device=dev)
+        flow = torch.empty(max(capacity, 1), dtype=torch.int32, device=dev)
+        perm = torch.empty(max(capacity, 1), dtype=torch.int32, device=dev) if want_perm else None
+    else:
+        off, w, flow, perm = out
+    t = topo.c()
+    _check(load().railsched_chunk_sort(_ptr(D1), batch, C.byref(t), _ptr(off), _ptr(w), _ptr(flow), _ptr(perm),
+                                       capacity, _ptr(ws), ws.numel(), _stream()), "railsched_chunk_sort")
+    return off, w, flow, perm
+
+
+# ---------------------------------------------------------------------------------- stage 4
+def lpt_spray(chunk_off: torch.Tensor, chunk_w: torch.Tensor, batch: int, topo: Topo, out=None):
+    """Greedy least-loaded-rail assignment per instance -> (rail uint8 [chunks], S int64 [batch][M][N])."""
+    _dev(chunk_off, torch.int64, "chunk_off")
+    if chunk_w.dtype not in (torch.int32, torch.uint32):
+        raise ValueError("chunk_w must be a 32-bit integer tensor")
+    if out is None:
+        rail = torch.empty(max(chunk_w.numel(), 1), dtype=torch.uint8, device=chunk_off.device)
+        S = torch.empty((batch, topo.nodes, topo.rails), dtype=torch.int64, device=chunk_off.device)
+    else:
+        rail, S = out
+    t = topo.c()
+    _check(load().railsched_lpt_spray(_ptr(chunk_off), _ptr(chunk_w), batch, C.byref(t), _ptr(rail), _ptr(S),
+                                      _stream()), "railsched_lpt_spray")
+    return rail, S
+
+
+# ---------------------------------------------------------------------------------- stage 5
+def eval(chunk_off, chunk_w, chunk_flow, rail, S, batch: int, topo: Topo, out=None,  # noqa: A001
+         ws: Optional[torch.Tensor] = None):
+    """Receive loads R [batch][M][N] and stats [batch][8] (see include/railsched.h)."""
+    dev = chunk_off.device
+    if out is None:
+        R = torch.empty((batch, topo.nodes, topo.rails), dtype=torch.int64, device=dev)
+        stats = torch.empty((batch, 8), dtype=torch.int64, device=dev)
+    else:
+        R, stats = out
+    if ws is None:
+        ws = _ws(eval_workspace_bytes(batch, topo), dev)
+    t = topo.c()
+    _check(load().railsched_eval(_ptr(chunk_off), _ptr(chunk_w), _ptr(chunk_flow), _ptr(rail), _ptr(S), batch,
+                                 C.byref(t), _ptr(R), _ptr(stats), _ptr(ws), ws.numel(), _stream()), "railsched_eval")
+    return R, stats
+
+
+evaluate = eval
+
+
+# ---------------------------------------------------------------------------------- whole path
+class Plan:
+    """Preallocated buffers for repeated passes of the whole path over same-shaped batches
+    (no allocation and no host synchronisation inside step())."""
+
+    def __init__(self, topo: Topo, batch: int, capacity: int, device, rows: int = 0, k: int = 0, want_perm: bool = True):
+        self.topo, self.batch, self.capacity = topo, batch, capacity
+        M, N, G = topo.nodes, topo.rails, topo.G
+        i32, i64 = torch.int32, torch.int64
+        self.topk_idx = torch.empty((rows, k), dtype=i32, device=device) if rows else None
+        self.D1 = torch.empty((batch, G, G), dtype=i64, device=device)
+        self.chunk_off = torch.empty(batch * M + 1, dtype=i64, device=device)
+        self.chunk_w = torch.empty(max(capacity, 1), dtype=i32, device=device)
+        self.chunk_flow = torch.empty(max(capacity, 1), dtype=i32, device=device)
+        self.perm = torch.empty(max(capacity, 1), dtype=i32, device=device) if want_perm else None
+        self.rail = torch.empty(max(capacity, 1), dtype=torch.uint8, device=device)
+        self.S = torch.empty((batch, M, N), dtype=i64, device=device)
+        self.R = torch.empty((batch, M, N), dtype=i64, device=device)
+        self.stats = torch.empty((batch, 8), dtype=i64, device=device)
+        self.ws_sort = _ws(chunk_sort_workspace_bytes(batch, topo), device)
+        self.ws_eval = _ws(eval_workspace_bytes(batch, topo), device)
+
+    def route(self, logits, tokens_per_gpu, expert_gpu, payload_bytes):
+        route_topk(logits, self.topk_idx.shape[1], out=self.topk_idx)
+        traffic_matrix(self.topk_idx, self.batch, tokens_per_gpu, expert_gpu, payload_bytes, self.topo, out=self.D1)
+        return self.D1
+
+    def schedule(self, D1=None):
+        D1 = self.D1 if D1 is None else D1
+        chunk_sort(D1, self.topo, capacity=self.capacity,
+                   out=(self.chunk_off, self.chunk_w, self.chunk_flow, self.perm), ws=self.ws_sort)
+        lpt_spray(self.chunk_off, self.chunk_w, self.batch, self.topo, out=(self.rail, self.S))
+        eval(self.chunk_off, self.chunk_w, self.chunk_flow, self.rail, self.S, self.batch, self.topo,
+             out=(self.R, self.stats), ws=self.ws_eval)
+        return self.stats

@@ -1,0 +1,336 @@
+// Stage 3: flow splitting into fixed-size chunks and the per-node descending sort
+// (Section 5.1 "Flow Splitting and Atomicity"; Algorithm 2 steps 1-2).
+//
+// The sorted order has structure the kernels use instead of sorting every chunk: a flow of B bytes
+// gives floor(B/C) chunks of exactly C bytes and at most one tail of B mod C < C bytes.  Under
+// "weight descending, ties in canonical order" all full chunks therefore come first, in canonical
+// order (their positions follow from an exclusive scan of floor(B/C) over the instance's flows), and
+// only the tails - at most one per flow, N*G per instance - need a real sort.  The tails of one
+// instance are sorted by one wavefront with a stable LSD radix sort held in LDS (8-bit digits,
+// ranks inside a 64-element batch from ballot matching).  Every chunk record is written to HBM
+// exactly once.
+//
+// An instance (matrix b, node k) owns the N consecutive rows k*N..k*N+N-1 of D1[b]; read as one
+// array of N*G entries its index is exactly the canonical flow id n*G + dst.
+#include "common.h"
+
+namespace rs {
+
+constexpr int kTile = 16384;        // full-chunk positions per fill tile
+constexpr int kFillThreads = 256;
+constexpr int kFillStage = 4096;    // flow boundaries staged in LDS per tile
+constexpr int kFillBlocks = 2048;
+
+struct CsArgs {
+    const int64_t *D1;
+    int64_t *chunk_off;
+    uint32_t *chunk_w, *chunk_flow, *perm;
+    int64_t capacity;
+    int64_t *cnt_all, *cnt_full, *tile_off;
+    uint32_t *full_start, *canon_start;
+    int64_t C;
+    int32_t cshift;      // >= 0 when C is a power of two
+    int32_t M, N, G, NF, intra;
+    int32_t n_inst, n_pass;
+};
+
+__device__ __forceinline__ void split_bytes(const CsArgs &a, int64_t B, uint32_t &q, uint32_t &r)
+{
+    if (B < 0) B = 0;
+    if (a.cshift >= 0) {
+        q = (uint32_t)(B >> a.cshift);
+        r = (uint32_t)(B & (a.C - 1));
+    } else {
+        const uint64_t qq = (uint64_t)B / (uint64_t)a.C;
+        q = (uint32_t)qq;
+        r = (uint32_t)((uint64_t)B - qq * (uint64_t)a.C);
+    }
+}
+
+// bytes of flow f of instance (b, k); 0 for destinations inside node k unless intra-node traffic is kept
+__device__ __forceinline__ int64_t flow_bytes(const CsArgs &a, const int64_t *rows, int k, int f)
+{
+    const int dst = f % a.G;
+    if (!a.intra && dst / a.N == k) return 0;
+    return rows[f];
+}
+
+__device__ __forceinline__ unsigned wave_exscan(unsigned v, unsigned &total)
+{
+    const int lane = threadIdx.x & 63;
+    unsigned inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned o = __shfl_up(inc, d);
+        if (lane >= d) inc += o;
+    }
+    total = __shfl(inc, 63);
+    return inc - v;
+}
+
+// ---- A: per-instance chunk counts and the two exclusive scans over its flows -----------------
+__global__ __launch_bounds__(64) void cs_count_kernel(CsArgs a)
+{
+    const int inst = blockIdx.x;
+    const int b = inst / a.M, k = inst % a.M;
+    const int lane = threadIdx.x;
+    const int64_t *rows = a.D1 + ((int64_t)b * a.G + (int64_t)k * a.N) * a.G;
+    uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
+    uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
+    unsigned carry_full = 0, carry_all = 0;
+    int64_t n_full = 0, n_all = 0;
+    for (int f0 = 0; f0 < a.NF; f0 += 64) {
+        const int f = f0 + lane;
+        uint32_t q = 0, r = 0;
+        if (f < a.NF) split_bytes(a, flow_bytes(a, rows, k, f), q, r);
+        const unsigned c = q + (r ? 1u : 0u);
+        unsigned tq, tc;
+        const unsigned eq = wave_exscan(q, tq);
+        const unsigned ec = wave_exscan(c, tc);
+        if (f < a.NF) { fs[f] = carry_full + eq; cs[f] = carry_all + ec; }
+        carry_full += tq; carry_all += tc;
+        n_full += q; n_all += c;
+    }
+    // exact 64-bit totals
+    for (int d = 32; d >= 1; d >>= 1) { n_full += __shfl_xor(n_full, d); n_all += __shfl_xor(n_all, d); }
+    if (lane == 0) { a.cnt_all[inst] = n_all; a.cnt_full[inst] = n_full; }
+}
+
+// ---- B: chunk_off = exclusive scan of instance sizes; tile_off = exclusive scan of fill tiles --
+__global__ __launch_bounds__(1024) void cs_scan_kernel(CsArgs a)
+{
+    __shared__ int64_t sh_a[1024], sh_t[1024];
+    __shared__ int64_t carry_a, carry_t;
+    const int tid = threadIdx.x;
+    if (tid == 0) { carry_a = 0; carry_t = 0; }
+    __syncthreads();
+    for (int base = 0; base < a.n_inst; base += 1024) {
+        const int i = base + tid;
+        const int64_t va = i < a.n_inst ? a.cnt_all[i] : 0;
+        const int64_t vt = i < a.n_inst ? (a.cnt_full[i] + kTile - 1) / kTile : 0;
+        sh_a[tid] = va; sh_t[tid] = vt;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {
+            const int64_t xa = tid >= d ? sh_a[tid - d] : 0;
+            const int64_t xt = tid >= d ? sh_t[tid - d] : 0;
+            __syncthreads();
+            sh_a[tid] += xa; sh_t[tid] += xt;
+            __syncthreads();
+        }
+        if (i < a.n_inst) {
+            a.chunk_off[i] = carry_a + sh_a[tid] - va;
+            a.tile_off[i] = carry_t + sh_t[tid] - vt;
+        }
+        __syncthreads();
+        if (tid == 1023) { carry_a += sh_a[1023]; carry_t += sh_t[1023]; }
+        __syncthreads();
+    }
+    if (tid == 0) { a.chunk_off[a.n_inst] = carry_a; a.tile_off[a.n_inst] = carry_t; }
+}
+
+// ---- C: tails of one instance: stable descending radix sort in LDS, one wavefront -------------
+__global__ __launch_bounds__(64) void cs_tail_kernel(CsArgs a)
+{
+    extern __shared__ unsigned cs_lds[];
+    unsigned *rem = cs_lds;                                              // [NF] tail bytes per flow
+    unsigned *hist = cs_lds + a.NF;                                      // [256]
+    unsigned short *idx_a = reinterpret_cast<unsigned short *>(hist + 256);   // [NF] flow ids, ping
+    unsigned short *idx_b = idx_a + a.NF;                                      // [NF] pong
+    if (a.chunk_off[a.n_inst] > a.capacity) return;                      // record arrays too small: leave them alone
+
+    const int inst = blockIdx.x;
+    const int b = inst / a.M, k = inst % a.M;
+    const int lane = threadIdx.x;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    const int64_t *rows = a.D1 + ((int64_t)b * a.G + (int64_t)k * a.N) * a.G;
+
+    // tails in canonical order
+    int nt = 0;
+    for (int f0 = 0; f0 < a.NF; f0 += 64) {
+        const int f = f0 + lane;
+        uint32_t q = 0, r = 0;
+        if (f < a.NF) { split_bytes(a, flow_bytes(a, rows, k, f), q, r); rem[f] = r; }
+        const unsigned long long m = __ballot(r != 0);
+        if (r) idx_a[nt + __popcll(m & lt)] = (unsigned short)f;
+        nt += __popcll(m);
+    }
+    __syncthreads();
+
+    for (int pass = 0; pass < a.n_pass; ++pass) {
+        const int shift = 8 * pass;
+        for (int i = lane; i < 256; i += 64) hist[i] = 0;
+        __syncthreads();
+        for (int i = lane; i < nt; i += 64) atomicAdd(&hist[255u - ((rem[idx_a[i]] >> shift) & 255u)], 1u);
+        __syncthreads();
+        {   // exclusive scan of the 256 buckets: four per lane
+            const unsigned h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+            unsigned tot;
+            const unsigned ex = wave_exscan(h0 + h1 + h2 + h3, tot);
+            __syncthreads();
+            hist[4 * lane] = ex; hist[4 * lane + 1] = ex + h0; hist[4 * lane + 2] = ex + h0 + h1; hist[4 * lane + 3] = ex + h0 + h1 + h2;
+        }
+        __syncthreads();
+        for (int i0 = 0; i0 < nt; i0 += 64) {                            // batches in order keep the sort stable
+            const int i = i0 + lane;
+            const bool act = i < nt;
+            const unsigned short f = act ? idx_a[i] : 0;
+            const unsigned d = act ? 255u - ((rem[f] >> shift) & 255u) : 0u;
+            unsigned long long peers = __ballot(act);
+#pragma unroll
+            for (int bit = 0; bit < 8; ++bit) {
+                const bool one = (d >> bit) & 1u;
+                const unsigned long long bm = __ballot(act && one);
+                peers &= one ? bm : ~bm;
+            }
+            const unsigned base = act ? hist[d] : 0u;
+            if (act) idx_b[base + __popcll(peers & lt)] = f;
+            __syncthreads();
+            if (act && (peers >> lane) == 1ull) hist[d] = base + __popcll(peers);   // highest lane of the peer set
+            __syncthreads();
+        }
+        unsigned short *t = idx_a; idx_a = idx_b; idx_b = t;
+    }
+
+    const int64_t out0 = a.chunk_off[inst] + a.cnt_full[inst];
+    const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
+    const uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
+    const uint32_t n_full = (uint32_t)a.cnt_full[inst];
+    for (int i = lane; i < nt; i += 64) {
+        const int f = idx_a[i];
+        a.chunk_w[out0 + i] = rem[f];
+        a.chunk_flow[out0 + i] = (uint32_t)f;
+        if (a.perm) {
+            const uint32_t qf = (f + 1 < a.NF ? fs[f + 1] : n_full) - fs[f];
+            a.perm[out0 + i] = cs[f] + qf;                               // the tail is the flow's last chunk
+        }
+    }
+}
+
+// ---- D: full chunks: tiles of consecutive output positions ------------------------------------
+template <typename T>
+__device__ __forceinline__ int last_le(const T *v, int n, uint32_t x)   // last i in [0,n) with v[i] <= x (v[0] <= x)
+{
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (v[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ int last_le64(const int64_t *v, int n, int64_t x)
+{
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (v[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a)
+{
+    __shared__ uint32_t stage[kFillStage];
+    if (a.chunk_off[a.n_inst] > a.capacity) return;
+    const int64_t n_tiles = a.tile_off[a.n_inst];
+    for (int64_t u = blockIdx.x; u < n_tiles; u += gridDim.x) {
+        const int inst = last_le64(a.tile_off, a.n_inst, u);             // tile_off[inst] <= u < tile_off[inst+1]
+        const uint32_t n_full = (uint32_t)a.cnt_full[inst];
+        const uint32_t p0 = (uint32_t)(u - a.tile_off[inst]) * (uint32_t)kTile;
+        const uint32_t p1 = (n_full - p0 < (uint32_t)kTile) ? n_full : p0 + (uint32_t)kTile;
+        const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
+        const uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
+        const int f_lo = last_le(fs, a.NF, p0);
+        const int f_hi = last_le(fs, a.NF, p1 - 1);
+        const int nf = f_hi - f_lo + 1;
+        const bool staged = nf <= kFillStage;
+        __syncthreads();                                                 // previous tile is done with the stage
+        if (staged)
+            for (int i = threadIdx.x; i < nf; i += kFillThreads) stage[i] = fs[f_lo + i];
+        __syncthreads();
+        const int64_t out0 = a.chunk_off[inst];
+        for (uint32_t p = p0 + threadIdx.x; p < p1; p += kFillThreads) {
+            const int f = f_lo + (staged ? last_le(stage, nf, p) : last_le(fs + f_lo, nf, p));
+            a.chunk_w[out0 + p] = (uint32_t)a.C;
+            a.chunk_flow[out0 + p] = (uint32_t)f;
+            if (a.perm) a.perm[out0 + p] = cs[f] + (p - fs[f]);
+        }
+    }
+}
+
+static void ws_layout(int64_t n_inst, int64_t NF, size_t off[6])
+{
+    size_t o = 0;
+    off[0] = o; o += align_up(sizeof(int64_t) * (size_t)n_inst, 256);          // cnt_all
+    off[1] = o; o += align_up(sizeof(int64_t) * (size_t)n_inst, 256);          // cnt_full
+    off[2] = o; o += align_up(sizeof(int64_t) * (size_t)(n_inst + 1), 256);    // tile_off
+    off[3] = o; o += align_up(sizeof(uint32_t) * (size_t)(n_inst * NF), 256);  // full_start
+    off[4] = o; o += align_up(sizeof(uint32_t) * (size_t)(n_inst * NF), 256);  // canon_start
+    off[5] = o;
+}
+
+}  // namespace rs
+
+extern "C" size_t railsched_chunk_sort_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo)
+{
+    using namespace rs;
+    if (check_topo(h_topo) != RAILSCHED_OK || batch < 0) return 0;
+    const int64_t G = (int64_t)h_topo->nodes * h_topo->rails;
+    size_t off[6];
+    ws_layout((int64_t)batch * h_topo->nodes, (int64_t)h_topo->rails * G, off);
+    return off[5] ? off[5] : 256;
+}
+
+extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo,
+                                    int64_t *chunk_off, uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm,
+                                    int64_t capacity, void *ws, size_t ws_bytes, void *stream)
+{
+    using namespace rs;
+    if (int rc = check_topo(h_topo)) return rc;
+    if (batch < 0 || capacity < 0) return RAILSCHED_ERR_INVALID_ARG;
+    const int64_t M = h_topo->nodes, N = h_topo->rails, G = M * N, NF = N * G;
+    if (NF > kMaxFlows) return RAILSCHED_ERR_UNSUPPORTED;
+    const int64_t n_inst = (int64_t)batch * M;
+    if (n_inst > 0x7FFFFFFFll) return RAILSCHED_ERR_UNSUPPORTED;
+    if (!chunk_off) return RAILSCHED_ERR_NULL_PTR;
+    if (n_inst > 0 && !D1) return RAILSCHED_ERR_NULL_PTR;
+    if (chunk_w && !chunk_flow) return RAILSCHED_ERR_NULL_PTR;
+    size_t off[6];
+    ws_layout(n_inst, NF, off);
+    if (!ws || ws_bytes < off[5] || reinterpret_cast<uintptr_t>(ws) % 256) return RAILSCHED_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    char *w8 = static_cast<char *>(ws);
+    CsArgs a;
+    a.D1 = D1; a.chunk_off = chunk_off; a.chunk_w = chunk_w; a.chunk_flow = chunk_flow; a.perm = perm;
+    a.capacity = capacity;
+    a.cnt_all = reinterpret_cast<int64_t *>(w8 + off[0]);
+    a.cnt_full = reinterpret_cast<int64_t *>(w8 + off[1]);
+    a.tile_off = reinterpret_cast<int64_t *>(w8 + off[2]);
+    a.full_start = reinterpret_cast<uint32_t *>(w8 + off[3]);
+    a.canon_start = reinterpret_cast<uint32_t *>(w8 + off[4]);
+    a.C = h_topo->chunk_bytes;
+    a.cshift = is_pow2(a.C) ? ilog2(a.C) : -1;
+    a.M = (int32_t)M; a.N = (int32_t)N; a.G = (int32_t)G; a.NF = (int32_t)NF; a.intra = h_topo->include_intra_node;
+    a.n_inst = (int32_t)n_inst;
+    a.n_pass = a.C <= 1 ? 0 : (ilog2(a.C - 1) + 1 + 7) / 8;             // tail weights are < C
+
+    if (n_inst > 0) {
+        hipLaunchKernelGGL(cs_count_kernel, dim3((unsigned)n_inst), dim3(64), 0, st, a);
+        if (int rc = launch_status()) return rc;
+    }
+    hipLaunchKernelGGL(cs_scan_kernel, dim3(1), dim3(1024), 0, st, a);
+    if (int rc = launch_status()) return rc;
+    if (!chunk_w || n_inst == 0) return RAILSCHED_OK;
+
+    const size_t lds = sizeof(unsigned) * (size_t)(NF + 256) + 2 * sizeof(unsigned short) * (size_t)NF;
+    if (lds > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(cs_tail_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return RAILSCHED_ERR_HIP;
+    }
+    hipLaunchKernelGGL(cs_tail_kernel, dim3((unsigned)n_inst), dim3(64), lds, st, a);
+    if (int rc = launch_status()) return rc;
+    hipLaunchKernelGGL(cs_fill_kernel, dim3(kFillBlocks), dim3(kFillThreads), 0, st, a);
+    return launch_status();
+}

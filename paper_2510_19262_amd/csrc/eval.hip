@@ -1,0 +1,185 @@
+// Stage 5: send/receive loads, completion time and lower bound
+// (Section 4.1 load matrices S and R; Theorem 2; Theorem 3; Algorithm 2 step 6 uses the same loads).
+//
+// Rail n of a source node ends on NIC n of the destination node (one-to-one rail mapping used in the
+// proof of Theorem 3), so R[b][f][n] is the sum of the weights of all chunks of matrix b whose
+// destination GPU lies in node f and that were assigned to rail n - whatever their source node.
+// Kernel 1: the chunk range of matrix b is cut into `slices` equal parts; one workgroup streams a
+// part (9 bytes per chunk), accumulates the G = M*N receive bins in LDS and writes them, plus the
+// largest weight it saw, to its own slot of the workspace with plain stores.
+// Kernel 2: one workgroup per matrix adds the slots in slice order and derives the statistics from
+// S (as produced by stage 4) and R.  No global atomics anywhere: every result is a fixed-order sum.
+#include "common.h"
+
+namespace rs {
+
+constexpr int kEvThreads = 256;
+
+struct EvArgs {
+    const int64_t *chunk_off;
+    const uint32_t *chunk_w, *chunk_flow;
+    const uint8_t *rail;
+    const int64_t *S;
+    int64_t *R, *stats;
+    int64_t *partial;        // [batch][slices][G + 1]
+    int32_t M, N, G, slices;
+    int32_t nshift, gmask;   // >= 0 when N / G are powers of two
+};
+
+__device__ __forceinline__ int dst_node(const EvArgs &a, uint32_t flow)
+{
+    // flow = n*G + dst  ->  dst / N
+    if (a.gmask >= 0 && a.nshift >= 0) return (int)((flow & (uint32_t)a.gmask) >> a.nshift);
+    return (int)((flow % (uint32_t)a.G) / (uint32_t)a.N);
+}
+
+__global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
+{
+    extern __shared__ unsigned long long ev_bins[];                     // [G]
+    __shared__ unsigned ev_wmax;
+    const int b = blockIdx.y, t = blockIdx.x;
+    for (int i = threadIdx.x; i < a.G; i += kEvThreads) ev_bins[i] = 0;
+    if (threadIdx.x == 0) ev_wmax = 0;
+    __syncthreads();
+
+    const int64_t lo_m = a.chunk_off[(int64_t)b * a.M], hi_m = a.chunk_off[(int64_t)(b + 1) * a.M];
+    const int64_t n = hi_m - lo_m;
+    const int64_t lo = lo_m + n * t / a.slices, hi = lo_m + n * (t + 1) / a.slices;
+    unsigned wmax = 0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kEvThreads) {
+        const uint32_t w = a.chunk_w[i];
+        const int f = dst_node(a, a.chunk_flow[i]);
+        const int r = a.rail[i];
+        if (f < a.M && r < a.N) atomicAdd(&ev_bins[f * a.N + r], (unsigned long long)w);   // LDS, workgroup-private
+        wmax = w > wmax ? w : wmax;
+    }
+    atomicMax(&ev_wmax, wmax);
+    __syncthreads();
+    int64_t *slot = a.partial + ((int64_t)b * a.slices + t) * (a.G + 1);
+    for (int i = threadIdx.x; i < a.G; i += kEvThreads) slot[i] = (int64_t)ev_bins[i];
+    if (threadIdx.x == 0) slot[a.G] = (int64_t)ev_wmax;
+}
+
+__device__ __forceinline__ int64_t block_reduce(int64_t v, bool take_max, int64_t *sh)
+{
+    __syncthreads();
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int d = kEvThreads / 2; d >= 1; d >>= 1) {
+        if ((int)threadIdx.x < d) {
+            const int64_t x = sh[threadIdx.x], y = sh[threadIdx.x + d];
+            sh[threadIdx.x] = take_max ? (x > y ? x : y) : (x + y);
+        }
+        __syncthreads();
+    }
+    return sh[0];
+}
+
+__global__ __launch_bounds__(kEvThreads) void eval_reduce_kernel(EvArgs a)
+{
+    __shared__ int64_t sh[kEvThreads];
+    const int b = blockIdx.x;
+    const int64_t *slots = a.partial + (int64_t)b * a.slices * (a.G + 1);
+    int64_t *Rb = a.R + (int64_t)b * a.G;
+    const int64_t *Sb = a.S + (int64_t)b * a.G;
+
+    for (int i = threadIdx.x; i < a.G; i += kEvThreads) {
+        int64_t acc = 0;
+        for (int t = 0; t < a.slices; ++t) acc += slots[(int64_t)t * (a.G + 1) + i];
+        Rb[i] = acc;
+    }
+    int64_t wmax = 0;
+    for (int t = threadIdx.x; t < a.slices; t += kEvThreads) {
+        const int64_t x = slots[(int64_t)t * (a.G + 1) + a.G];
+        wmax = x > wmax ? x : wmax;
+    }
+    __syncthreads();   // R[b] written by this workgroup is read back below
+
+    int64_t max_s = 0, max_r = 0, lb = 0, total = 0, spread = 0;
+    for (int k = threadIdx.x; k < a.M; k += kEvThreads) {
+        int64_t out = 0, in = 0, smin = INT64_MAX, smax = 0;
+        for (int n = 0; n < a.N; ++n) {
+            const int64_t s = Sb[k * a.N + n], r = Rb[k * a.N + n];
+            out += s; in += r;
+            max_s = s > max_s ? s : max_s;
+            max_r = r > max_r ? r : max_r;
+            smin = s < smin ? s : smin;
+            smax = s > smax ? s : smax;
+        }
+        total += out;
+        const int64_t co = (out + a.N - 1) / a.N, ci = (in + a.N - 1) / a.N;
+        lb = co > lb ? co : lb;
+        lb = ci > lb ? ci : lb;
+        spread = (smax - smin) > spread ? (smax - smin) : spread;
+    }
+    max_s = block_reduce(max_s, true, sh);
+    max_r = block_reduce(max_r, true, sh);
+    lb = block_reduce(lb, true, sh);
+    wmax = block_reduce(wmax, true, sh);
+    spread = block_reduce(spread, true, sh);
+    total = block_reduce(total, false, sh);
+    if (threadIdx.x == 0) {
+        int64_t *st = a.stats + (int64_t)b * 8;
+        st[0] = max_s > max_r ? max_s : max_r;
+        st[1] = max_s;
+        st[2] = max_r;
+        st[3] = lb > wmax ? lb : wmax;
+        st[4] = total;
+        st[5] = wmax;
+        st[6] = a.chunk_off[(int64_t)(b + 1) * a.M] - a.chunk_off[(int64_t)b * a.M];
+        st[7] = spread;
+    }
+}
+
+static int eval_slices(int32_t batch)
+{
+    // about 2048 workgroups in flight whatever the batch; at least one slice per matrix
+    int s = (2048 + batch - 1) / (batch > 0 ? batch : 1);
+    if (s < 1) s = 1;
+    if (s > 2048) s = 2048;
+    return s;
+}
+
+}  // namespace rs
+
+extern "C" size_t railsched_eval_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo)
+{
+    using namespace rs;
+    if (check_topo(h_topo) != RAILSCHED_OK || batch < 0) return 0;
+    const int64_t G = (int64_t)h_topo->nodes * h_topo->rails;
+    const size_t n = sizeof(int64_t) * (size_t)batch * (size_t)eval_slices(batch) * (size_t)(G + 1);
+    return n ? align_up(n, 256) : 256;
+}
+
+extern "C" int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w, const uint32_t *chunk_flow,
+                              const uint8_t *rail, const int64_t *S, int32_t batch, const railsched_topo_t *h_topo,
+                              int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream)
+{
+    using namespace rs;
+    if (int rc = check_topo(h_topo)) return rc;
+    if (batch < 0) return RAILSCHED_ERR_INVALID_ARG;
+    if (batch > 65535) return RAILSCHED_ERR_UNSUPPORTED;
+    if (batch == 0) return RAILSCHED_OK;
+    if (!chunk_off || !S || !R || !stats) return RAILSCHED_ERR_NULL_PTR;
+    if (!ws || ws_bytes < railsched_eval_workspace_bytes(batch, h_topo) || reinterpret_cast<uintptr_t>(ws) % 256)
+        return RAILSCHED_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    EvArgs a;
+    a.chunk_off = chunk_off; a.chunk_w = chunk_w; a.chunk_flow = chunk_flow; a.rail = rail; a.S = S;
+    a.R = R; a.stats = stats; a.partial = static_cast<int64_t *>(ws);
+    a.M = h_topo->nodes; a.N = h_topo->rails; a.G = a.M * a.N; a.slices = eval_slices(batch);
+    a.nshift = is_pow2(a.N) ? ilog2(a.N) : -1;
+    a.gmask = is_pow2(a.G) ? a.G - 1 : -1;
+
+    const size_t lds = sizeof(unsigned long long) * (size_t)a.G;
+    if (lds > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(eval_partial_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return RAILSCHED_ERR_HIP;
+    }
+    hipLaunchKernelGGL(eval_partial_kernel, dim3((unsigned)a.slices, (unsigned)batch), dim3(kEvThreads), lds, st, a);
+    if (int rc = launch_status()) return rc;
+    hipLaunchKernelGGL(eval_reduce_kernel, dim3((unsigned)batch), dim3(kEvThreads), 0, st, a);
+    return launch_status();
+}

@@ -1,0 +1,125 @@
+// Stage 2: GPU-to-GPU traffic matrix D^(1) (Section 4.1; Algorithm 1 step 2).
+//
+// One workgroup owns (a slice of) the tokens of one (matrix b, source GPU s) pair.  It streams the
+// pair's top-k indices with 16-byte loads, maps every (token, slot) to its destination GPU through
+// the expert placement table (staged in LDS) and counts hits in an LDS histogram private to the
+// workgroup: G 32-bit bins.  Counts become bytes (count * payload) only when the histogram is
+// flushed.  HBM traffic is the index stream once plus 8*G bytes per (b, s) pair.
+#include "common.h"
+
+namespace rs {
+
+constexpr int kTmThreads = 256;
+constexpr int kTmTableMax = 8192;   // placement entries staged in LDS (32 KiB)
+
+__global__ void fill_zero_i64(int64_t *p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+struct TmArgs {
+    const int32_t *topk_idx;
+    const int32_t *expert_gpu;
+    int64_t *D1;
+    int64_t slots_per_gpu;   // tokens_per_gpu * k
+    int64_t payload;
+    int32_t k, kshift;       // kshift >= 0 when k is a power of two
+    int32_t E, R, rmask;     // rmask >= 0 when R is a power of two
+    int32_t G, splits;
+    int32_t table_in_lds;
+};
+
+__device__ __forceinline__ void tm_count(const TmArgs &a, const int32_t *table, unsigned *bins, int64_t slot, int32_t e)
+{
+    const int64_t t = a.kshift >= 0 ? (slot >> a.kshift) : (slot / a.k);
+    const int rho = a.rmask >= 0 ? (int)(t & a.rmask) : (int)(t % a.R);
+    if ((unsigned)e < (unsigned)a.E) {
+        const int32_t d = table[e * a.R + rho];
+        if ((unsigned)d < (unsigned)a.G) atomicAdd(&bins[d], 1u);
+    }
+}
+
+__global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
+{
+    extern __shared__ unsigned tm_lds[];
+    unsigned *bins = tm_lds;                                            // [G]
+    int32_t *lds_table = reinterpret_cast<int32_t *>(tm_lds + a.G);     // [E*R] when it fits
+    const int64_t pair = blockIdx.x / a.splits;                         // b*G + s
+    const int part = blockIdx.x % a.splits;
+
+    for (int i = threadIdx.x; i < a.G; i += kTmThreads) bins[i] = 0;
+    if (a.table_in_lds)
+        for (int i = threadIdx.x; i < a.E * a.R; i += kTmThreads) lds_table[i] = a.expert_gpu[i];
+    __syncthreads();
+    const int32_t *table = a.table_in_lds ? lds_table : a.expert_gpu;
+
+    // this workgroup's slice [lo, hi) of the pair's slots, cut at multiples of 4 slots
+    const int64_t quads = (a.slots_per_gpu + 3) / 4;
+    const int64_t qlo = quads * part / a.splits, qhi = quads * (part + 1) / a.splits;
+    const int32_t *src = a.topk_idx + pair * a.slots_per_gpu;
+    const bool aligned = (reinterpret_cast<uintptr_t>(src) % 16) == 0;
+    for (int64_t qd = qlo + threadIdx.x; qd < qhi; qd += kTmThreads) {
+        const int64_t s0 = qd * 4;
+        if (aligned && s0 + 4 <= a.slots_per_gpu) {
+            const int4 e = *reinterpret_cast<const int4 *>(src + s0);
+            tm_count(a, table, bins, s0 + 0, e.x);
+            tm_count(a, table, bins, s0 + 1, e.y);
+            tm_count(a, table, bins, s0 + 2, e.z);
+            tm_count(a, table, bins, s0 + 3, e.w);
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (s0 + j < a.slots_per_gpu) tm_count(a, table, bins, s0 + j, src[s0 + j]);
+        }
+    }
+    __syncthreads();
+
+    int64_t *dst = a.D1 + pair * a.G;
+    for (int i = threadIdx.x; i < a.G; i += kTmThreads) {
+        const int64_t bytes = (int64_t)bins[i] * a.payload;
+        if (a.splits == 1) dst[i] = bytes;                               // sole owner: plain store, zeros included
+        else if (bytes) atomicAdd(reinterpret_cast<unsigned long long *>(dst + i), (unsigned long long)bytes);
+    }
+}
+
+}  // namespace rs
+
+extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, int64_t tokens_per_gpu, int32_t k,
+                                        const int32_t *expert_gpu, int32_t E, int32_t R, int64_t payload_bytes,
+                                        const railsched_topo_t *h_topo, int64_t *D1, void *stream)
+{
+    using namespace rs;
+    if (int rc = check_topo(h_topo)) return rc;
+    if (batch < 0 || tokens_per_gpu < 0 || k < 1 || E < 1 || R < 1 || payload_bytes < 0) return RAILSCHED_ERR_INVALID_ARG;
+    if (E > kMaxExperts) return RAILSCHED_ERR_UNSUPPORTED;
+    const int64_t G = (int64_t)h_topo->nodes * h_topo->rails;
+    if (tokens_per_gpu > (int64_t(1) << 31) / k) return RAILSCHED_ERR_UNSUPPORTED;   // 32-bit bin counters
+    if (batch == 0) return RAILSCHED_OK;
+    if (!D1 || !expert_gpu || (!topk_idx && tokens_per_gpu > 0)) return RAILSCHED_ERR_NULL_PTR;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    TmArgs a;
+    a.topk_idx = topk_idx; a.expert_gpu = expert_gpu; a.D1 = D1;
+    a.slots_per_gpu = tokens_per_gpu * k; a.payload = payload_bytes;
+    a.k = k; a.kshift = is_pow2(k) ? ilog2(k) : -1;
+    a.E = E; a.R = R; a.rmask = is_pow2(R) ? R - 1 : -1;
+    a.G = (int32_t)G;
+    a.table_in_lds = ((int64_t)E * R <= kTmTableMax && 4 * (G + (int64_t)E * R) <= 64 * 1024) ? 1 : 0;
+
+    // enough workgroups to cover the chip, but no slice shorter than 16 Ki slots
+    const int64_t pairs = (int64_t)batch * G;
+    int64_t splits = (2048 + pairs - 1) / pairs;
+    const int64_t max_splits = (a.slots_per_gpu + 16383) / 16384;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    a.splits = (int32_t)splits;
+    if (pairs * splits > 0x7FFFFFFFll) return RAILSCHED_ERR_UNSUPPORTED;
+
+    if (splits > 1) {
+        const int64_t n = pairs * G;
+        hipLaunchKernelGGL(fill_zero_i64, dim3((unsigned)((n + 1023) / 1024 > 4096 ? 4096 : (n + 1023) / 1024)), dim3(256), 0, st, D1, n);
+        if (int rc = launch_status()) return rc;
+    }
+    const size_t lds = sizeof(unsigned) * (size_t)G + (a.table_in_lds ? sizeof(int32_t) * (size_t)E * R : 0);
+    hipLaunchKernelGGL(traffic_matrix_kernel, dim3((unsigned)(pairs * splits)), dim3(kTmThreads), lds, st, a);
+    return launch_status();
+}

@@ -1,0 +1,107 @@
+"""Host-side checks of the C ABI that need no GPU: the shared library loads, exports every
+symbol the header declares, and rejects bad arguments before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2510_19262_amd as rs
+from paper_2510_19262_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "railsched.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(railsched_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_and_library_agree():
+    lib = rs.load()
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert "gfx950" in rs.version()
+    assert rs.strerror(0) == "ok" and "workspace" in rs.strerror(-5)
+
+
+def _topo(M=4, N=4, Cb=4096, intra=0, reserved=0):
+    t = binding._TopoStruct(M, N, Cb, 1, intra, reserved)
+    return t
+
+
+P = C.c_void_p
+FAKE = P(0x1000)      # never dereferenced: validation fails first
+
+
+def test_route_topk_validation():
+    lib = rs.load()
+    assert lib.railsched_route_topk(FAKE, -1, 8, 2, FAKE, None) == -1
+    assert lib.railsched_route_topk(FAKE, 10, 0, 1, FAKE, None) == -1
+    assert lib.railsched_route_topk(FAKE, 10, 8, 9, FAKE, None) == -1
+    assert lib.railsched_route_topk(FAKE, 10, 8, 0, FAKE, None) == -1
+    assert lib.railsched_route_topk(FAKE, 10, 2048, 2, FAKE, None) == -3
+    assert lib.railsched_route_topk(None, 10, 8, 2, FAKE, None) == -2
+    assert lib.railsched_route_topk(FAKE, 10, 8, 2, None, None) == -2
+    assert lib.railsched_route_topk(None, 0, 8, 2, None, None) == 0      # nothing to do
+
+
+def test_topology_validation():
+    lib = rs.load()
+    for t, want in ((_topo(M=0), -1), (_topo(N=0), -1), (_topo(Cb=0), -1), (_topo(reserved=1), -1), (_topo(intra=2), -1),
+                    (_topo(N=65), -3), (_topo(M=4096, N=8), -3), (_topo(Cb=1 << 32), -3)):
+        assert lib.railsched_lpt_spray(FAKE, FAKE, 1, C.byref(t), FAKE, FAKE, None) == want
+        assert lib.railsched_chunk_sort_workspace_bytes(1, C.byref(t)) == 0
+        assert lib.railsched_eval_workspace_bytes(1, C.byref(t)) == 0
+    assert lib.railsched_lpt_spray(FAKE, FAKE, 1, None, FAKE, FAKE, None) == -2
+
+
+def test_traffic_matrix_validation():
+    lib = rs.load()
+    t = _topo()
+    f = lib.railsched_traffic_matrix
+    assert f(FAKE, -1, 10, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, None) == -1
+    assert f(FAKE, 1, 10, 0, FAKE, 8, 2, 1024, C.byref(t), FAKE, None) == -1
+    assert f(FAKE, 1, 10, 2, FAKE, 8, 0, 1024, C.byref(t), FAKE, None) == -1
+    assert f(FAKE, 1, 10, 2, FAKE, 8, 2, -5, C.byref(t), FAKE, None) == -1
+    assert f(FAKE, 1, 1 << 31, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, None) == -3
+    assert f(FAKE, 1, 10, 2, None, 8, 2, 1024, C.byref(t), FAKE, None) == -2
+    assert f(FAKE, 1, 10, 2, FAKE, 8, 2, 1024, C.byref(t), None, None) == -2
+    assert f(FAKE, 0, 10, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, None) == 0
+
+
+def test_chunk_sort_and_eval_validation():
+    lib = rs.load()
+    t = _topo()
+    need = lib.railsched_chunk_sort_workspace_bytes(2, C.byref(t))
+    assert need > 0 and need % 256 == 0
+    cs = lib.railsched_chunk_sort
+    assert cs(FAKE, -1, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, need, None) == -1
+    assert cs(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, -1, FAKE, need, None) == -1
+    assert cs(FAKE, 2, C.byref(t), None, FAKE, FAKE, FAKE, 10, FAKE, need, None) == -2
+    assert cs(None, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, need, None) == -2
+    assert cs(FAKE, 2, C.byref(t), FAKE, FAKE, None, FAKE, 10, FAKE, need, None) == -2
+    assert cs(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, None, need, None) == -5
+    assert cs(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, need - 1, None) == -5
+    assert cs(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, P(0x1001), need, None) == -5
+    big = _topo(M=64, N=32)                                              # N*G = 65536 flows per instance
+    assert cs(FAKE, 1, C.byref(big), FAKE, FAKE, FAKE, FAKE, 10, FAKE, 1 << 40, None) == -3
+    ev = lib.railsched_eval
+    need = lib.railsched_eval_workspace_bytes(2, C.byref(t))
+    assert need > 0
+    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, -1, C.byref(t), FAKE, FAKE, FAKE, need, None) == -1
+    assert ev(FAKE, FAKE, FAKE, FAKE, None, 2, C.byref(t), FAKE, FAKE, FAKE, need, None) == -2
+    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 2, C.byref(t), None, FAKE, FAKE, need, None) == -2
+    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, need - 1, None) == -5
+    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 0, C.byref(t), FAKE, FAKE, FAKE, need, None) == 0
+    assert lib.railsched_lpt_spray(FAKE, FAKE, 0, C.byref(t), FAKE, FAKE, None) == 0
+    assert lib.railsched_lpt_spray(None, FAKE, 1, C.byref(t), FAKE, FAKE, None) == -2
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        rs.route_topk(torch.zeros((4, 8)), 2)

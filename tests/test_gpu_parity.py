@@ -1,0 +1,307 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, bit for bit.
+
+All outputs are integers, so every comparison is exact equality.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+rs = pytest.importorskip("paper_2510_19262_amd")
+DEV = "cuda:0"
+
+
+def _u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def gpu_schedule(D1_np, topo, want_perm=True):
+    """Stages 3-5 on the GPU for a [batch][G][G] matrix stack; everything back as numpy."""
+    D1 = torch.from_numpy(np.ascontiguousarray(D1_np)).to(DEV)
+    batch = D1.shape[0]
+    off, w, flow, perm = rs.chunk_sort(D1, topo, want_perm=want_perm)
+    rail, S = rs.lpt_spray(off, w, batch, topo)
+    R, stats = rs.eval(off, w, flow, rail, S, batch, topo)
+    torch.cuda.synchronize()
+    total = int(off[-1].item())
+    return dict(off=off.cpu().numpy(), w=_u32(w)[:total], flow=_u32(flow)[:total],
+                perm=None if perm is None else _u32(perm)[:total], rail=rail.cpu().numpy()[:total],
+                S=S.cpu().numpy(), R=R.cpu().numpy(), stats=stats.cpu().numpy())
+
+
+def cpu_schedule(D1_np, M, N, C, intra=0):
+    D1_np = np.ascontiguousarray(D1_np, dtype=np.int64)
+    B = D1_np.shape[0]
+    off, w, flow, perm = oracle.chunk_sort_batch(D1_np, M, N, C, intra)
+    rail, S = oracle.lpt_batch(off, w, B, M, N)
+    Ssum, R, stats = oracle.eval_batch(off, w, flow, rail, B, M, N)
+    assert np.array_equal(S, Ssum)
+    return dict(off=off, w=w, flow=flow, perm=perm, rail=rail, S=S, R=R, stats=stats)
+
+
+def assert_same(g, c, what=""):
+    for key in ("off", "w", "flow", "perm", "rail", "S", "R", "stats"):
+        if g[key] is None:
+            continue
+        assert g[key].shape == c[key].shape, f"{what}{key}: shape {g[key].shape} vs {c[key].shape}"
+        if not np.array_equal(g[key], c[key]):
+            bad = np.flatnonzero(g[key].reshape(-1) != c[key].reshape(-1))
+            raise AssertionError(f"{what}{key}: {bad.size} mismatches, first at {bad[:5]}: "
+                                 f"gpu {g[key].reshape(-1)[bad[:5]]} cpu {c[key].reshape(-1)[bad[:5]]}")
+
+
+# ------------------------------------------------------------------------------ stage 1
+@pytest.mark.parametrize("E,k,rows", [(8, 2, 100_003), (8, 1, 777), (8, 8, 513), (4, 2, 1000), (3, 2, 1001), (5, 3, 999),
+                                      (16, 4, 2049), (12, 5, 300), (32, 2, 1025), (64, 6, 700), (100, 7, 333),
+                                      (128, 8, 511), (256, 8, 4099), (250, 9, 130), (512, 4, 129), (1000, 3, 65),
+                                      (1024, 16, 70), (1, 1, 50), (8, 2, 1), (256, 8, 1)])
+def test_topk_matches_oracle(E, k, rows):
+    rng = np.random.default_rng(E * 1000 + k)
+    x = rng.standard_normal((rows, E)).astype(np.float32)
+    x[rows // 2:] = np.round(x[rows // 2:] * 2) / 2          # half the rows: few distinct values, many ties
+    got = rs.route_topk(torch.from_numpy(x).to(DEV), k).cpu().numpy()
+    assert np.array_equal(got, oracle.route_topk(x, k))
+
+
+def test_topk_crafted_ties():
+    rows = [[1.25] * 8, [0, 5, 1, 5, 5, -1, 2, 0], [-1, -0.0, 0.0, -2, 0.0, -0.0, -3, -4], [3, 3, 2, 2, 1, 1, 0, 0],
+            [-5, -5, -5, -5, -5, -5, -5, -4]]
+    x = np.array(rows, dtype=np.float32)
+    for k in (1, 2, 4, 8):
+        got = rs.route_topk(torch.from_numpy(x).to(DEV), k).cpu().numpy()
+        assert np.array_equal(got, oracle.route_topk(x, k))
+    x = np.zeros((130, 256), dtype=np.float32)                 # all equal across 64 lanes: first k indices
+    got = rs.route_topk(torch.from_numpy(x).to(DEV), 8).cpu().numpy()
+    assert np.array_equal(got, np.tile(np.arange(8), (130, 1)))
+
+
+def test_topk_unaligned_rows_and_empty():
+    x = torch.randn(1001 * 8 + 1, device=DEV)[1:].view(1001, 8)   # base pointer off 16-byte alignment
+    assert np.array_equal(rs.route_topk(x.contiguous(), 2).cpu().numpy(), oracle.route_topk(x.cpu().numpy(), 2))
+    empty = torch.empty((0, 8), device=DEV)
+    assert rs.route_topk(empty, 2).shape == (0, 2)
+
+
+def test_logit_generator_is_device_independent():
+    cfg = W.get_config("c2")
+    a = W.gen_logits(cfg, 3, device="cpu", rows=50_000)
+    b = W.gen_logits(cfg, 3, device=DEV, rows=50_000).cpu()
+    assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    c = W.gen_logits(cfg, 3, device=DEV, row_start=1000, rows=10).cpu()
+    assert torch.equal(a[1000:1010].view(torch.int32), c.view(torch.int32))
+
+
+# ------------------------------------------------------------------------------ stage 2
+@pytest.mark.parametrize("M,N,E,k,R,tok,batch", [(4, 4, 8, 2, 2, 2048, 1), (2, 3, 6, 3, 1, 777, 2), (3, 2, 7, 2, 3, 1000, 3),
+                                                 (8, 8, 8, 2, 8, 4096, 2), (1, 1, 4, 1, 1, 10, 1), (2, 2, 4, 4, 2, 70001, 1),
+                                                 (16, 8, 256, 8, 1, 300, 1)])
+def test_traffic_matrix_matches_oracle(M, N, E, k, R, tok, batch):
+    rng = np.random.default_rng(M * 100 + N * 10 + E)
+    G = M * N
+    eg = rng.integers(0, G, size=(E, R)).astype(np.int32)
+    rows = batch * G * tok
+    idx = np.argsort(rng.random((rows, E)), axis=1)[:, :k].astype(np.int32)
+    topo = rs.Topo(M, N, 4096)
+    got = rs.traffic_matrix(torch.from_numpy(idx).to(DEV), batch, tok, torch.from_numpy(eg).to(DEV), 2048, topo)
+    assert np.array_equal(got.cpu().numpy(), oracle.traffic_matrix(idx, batch, tok, eg, 2048, M, N))
+
+
+def test_traffic_matrix_skewed_bins():
+    # every token picks expert 0 first: all hits of a source GPU land in one bin
+    M, N, E, k, tok = 2, 4, 8, 2, 50_000
+    G = M * N
+    eg = np.arange(E, dtype=np.int32).reshape(E, 1)
+    idx = np.tile(np.array([[0, 1]], dtype=np.int32), (G * tok, 1))
+    got = rs.traffic_matrix(torch.from_numpy(idx).to(DEV), 1, tok, torch.from_numpy(eg).to(DEV), 8192, rs.Topo(M, N, 4096))
+    assert np.array_equal(got.cpu().numpy(), oracle.traffic_matrix(idx, 1, tok, eg, 8192, M, N))
+
+
+# ------------------------------------------------------------------------------ stages 3-5
+def _rand_stack(rng, B, G, C, p_zero=0.3, hi=6):
+    m = rng.integers(0, hi * C, size=(B, G, G)).astype(np.int64)
+    m[rng.random((B, G, G)) < p_zero] = 0
+    m[rng.random((B, G, G)) < 0.2] //= C
+    m[rng.random((B, G, G)) < 0.2] = 3 * C
+    return m
+
+
+@pytest.mark.parametrize("M,N,C,B,intra", [(4, 4, 65536, 1, 0), (3, 2, 100, 4, 0), (3, 2, 100, 4, 1), (5, 3, 1000, 3, 0),
+                                           (2, 8, 4096, 5, 0), (8, 8, 262144, 3, 0), (6, 5, 12345, 2, 0), (2, 16, 64, 2, 0),
+                                           (3, 20, 512, 2, 0), (2, 33, 256, 1, 0), (2, 64, 128, 1, 0), (1, 4, 64, 2, 1),
+                                           (7, 1, 64, 3, 0), (4, 4, 1, 1, 0), (40, 8, 4096, 2, 0)])
+def test_schedule_matches_oracle(M, N, C, B, intra):
+    rng = np.random.default_rng(M * 1000 + N * 10 + B)
+    hi = 6 if C > 1 else 40
+    D1 = _rand_stack(rng, B, M * N, C, hi=hi)
+    topo = rs.Topo(M, N, C, include_intra_node=intra)
+    assert_same(gpu_schedule(D1, topo), cpu_schedule(D1, M, N, C, intra))
+
+
+def test_schedule_long_instances_and_empty_ones():
+    # heavy-tailed flows: instances from zero to tens of thousands of chunks, several fill tiles per instance
+    M, N, C, B = 6, 8, 4096, 3
+    rng = np.random.default_rng(42)
+    G = M * N
+    D1 = (np.exp(rng.normal(np.log(40 * C), 2.0, size=(B, G, G))) // 512 * 512).astype(np.int64)
+    D1[rng.random((B, G, G)) < 0.6] = 0
+    D1[0, 8:16, :] = 0                      # node 1 of matrix 0 sends nothing
+    D1[2] = 0                               # a whole empty matrix
+    topo = rs.Topo(M, N, C)
+    g, c = gpu_schedule(D1, topo), cpu_schedule(D1, M, N, C)
+    assert np.diff(c["off"]).max() > 3 * 16384
+    assert_same(g, c)
+
+
+def test_schedule_without_perm_and_all_zero():
+    M, N, C = 3, 4, 1024
+    rng = np.random.default_rng(5)
+    D1 = _rand_stack(rng, 2, M * N, C)
+    g = gpu_schedule(D1, rs.Topo(M, N, C), want_perm=False)
+    assert g["perm"] is None
+    assert_same(g, cpu_schedule(D1, M, N, C))
+    Z = np.zeros((2, M * N, M * N), dtype=np.int64)
+    assert_same(gpu_schedule(Z, rs.Topo(M, N, C)), cpu_schedule(Z, M, N, C))
+
+
+def test_chunk_sort_capacity_guard():
+    M, N, C = 3, 4, 1024
+    rng = np.random.default_rng(6)
+    D1 = torch.from_numpy(_rand_stack(rng, 2, M * N, C)).to(DEV)
+    topo = rs.Topo(M, N, C)
+    total = int(rs.chunk_count(D1, topo)[-1].item())
+    sentinel = 0x5A5A5A5A
+    out = (torch.empty(2 * M + 1, dtype=torch.int64, device=DEV),
+           torch.full((total,), sentinel, dtype=torch.int32, device=DEV),
+           torch.full((total,), sentinel, dtype=torch.int32, device=DEV),
+           torch.full((total,), sentinel, dtype=torch.int32, device=DEV))
+    off, w, flow, perm = rs.chunk_sort(D1, topo, capacity=total - 1, out=out)
+    torch.cuda.synchronize()
+    assert int(off[-1].item()) == total                               # offsets are complete ...
+    assert bool((w == sentinel).all()) and bool((flow == sentinel).all()) and bool((perm == sentinel).all())  # ... records untouched
+    off, w, flow, perm = rs.chunk_sort(D1, topo, capacity=total, out=out)
+    torch.cuda.synchronize()
+    assert not bool((w == sentinel).any())
+
+
+# ------------------------------------------------------------------------------ stage 4 alone
+def _lpt_case(weights_per_inst, M, N, batch=1):
+    """Arbitrary per-instance weight lists straight into stage 4."""
+    lens = [len(w) for w in weights_per_inst]
+    assert len(lens) == batch * M
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    w = np.concatenate([np.asarray(x, dtype=np.uint32) for x in weights_per_inst]) if sum(lens) else np.zeros(0, np.uint32)
+    topo = rs.Topo(M, N, 1 << 20)
+    wt = torch.from_numpy(w.view(np.int32).copy()).to(DEV) if w.size else torch.zeros(1, dtype=torch.int32, device=DEV)
+    rail, S = rs.lpt_spray(torch.from_numpy(off).to(DEV), wt, batch, topo)
+    rail_c, S_c = oracle.lpt_batch(off, w, batch, M, N)
+    assert np.array_equal(rail.cpu().numpy()[:w.size], rail_c)
+    assert np.array_equal(S.cpu().numpy(), S_c)
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 8, 11, 16, 24, 32, 40, 64])
+def test_lpt_random_weights_any_order(N):
+    rng = np.random.default_rng(N)
+    M = 19
+    insts = []
+    for i in range(M):
+        n = int(rng.integers(0, 700))
+        w = rng.integers(0, 1 << 18, size=n)
+        if i % 3 == 0:
+            w = np.sort(w)[::-1]
+        if i % 5 == 0 and n:
+            w[:] = w[0]                                           # one long run of equal weights
+        insts.append(w)
+    _lpt_case(insts, M, N)
+
+
+@pytest.mark.parametrize("N", [2, 8, 16, 64])
+def test_lpt_large_weights_take_the_exact_path(N):
+    rng = np.random.default_rng(100 + N)
+    M = 9
+    insts = []
+    for i in range(M):
+        n = int(rng.integers(1, 300))
+        w = rng.integers(0, 1 << 32, size=n, dtype=np.uint64)
+        if i % 2:                                                 # small weights first, a huge one mid-stream
+            w = rng.integers(0, 1 << 16, size=n, dtype=np.uint64)
+            w[n // 2] = (1 << 32) - 1
+        insts.append(w.astype(np.uint32))
+    _lpt_case(insts, M, N)
+
+
+def test_lpt_weights_at_the_packing_limit():
+    # weights just below / at / above the switch-over, many chunks so the loads pass 2^32
+    for N, lim in ((8, ((0xFFFFFFFF >> 3) // 34) - 1), (64, ((0xFFFFFFFF >> 6) // 66) - 1)):
+        insts = [np.full(400, lim, dtype=np.uint32), np.full(400, lim + 1, dtype=np.uint32),
+                 np.concatenate([np.full(200, lim), np.arange(200, 0, -1)]).astype(np.uint32)]
+        _lpt_case(insts, 3, N)
+
+
+def test_lpt_tight_family_and_small_cases():
+    _lpt_case([[5, 5, 4, 4, 3, 3, 3]], 1, 3)
+    _lpt_case([[9, 7, 3], [], [4]], 3, 5)
+    _lpt_case([[], []], 2, 8)
+    _lpt_case([[7] * 1000], 1, 8)
+
+
+def test_lpt_many_instances():
+    rng = np.random.default_rng(9)
+    M, batch = 37, 11
+    insts = [np.sort(rng.integers(1, 1 << 16, size=int(rng.integers(0, 200))))[::-1] for _ in range(M * batch)]
+    _lpt_case(insts, M, 8, batch)
+
+
+# ------------------------------------------------------------------------------ whole path on the paper-shaped configs
+def _moe_pipeline_gpu(cfg, layers):
+    topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes, cfg.rail_bw_Bps)
+    logits = torch.cat([W.gen_logits(cfg, b, device=DEV) for b in layers])
+    eg = torch.from_numpy(W.expert_gpu_table(cfg)).to(DEV)
+    idx = rs.route_topk(logits, cfg.k)
+    D1 = rs.traffic_matrix(idx, len(layers), cfg.tokens_per_gpu, eg, cfg.payload_bytes, topo)
+    torch.cuda.synchronize()
+    return logits, idx, D1, topo
+
+
+def test_config1_end_to_end():
+    cfg = W.get_config("c1")
+    logits, idx, D1, topo = _moe_pipeline_gpu(cfg, [0])
+    x = logits.cpu().numpy()
+    idx_c = oracle.route_topk(x, cfg.k)
+    assert np.array_equal(idx.cpu().numpy(), idx_c)
+    D1_c = oracle.traffic_matrix(idx_c, 1, cfg.tokens_per_gpu, W.expert_gpu_table(cfg), cfg.payload_bytes, cfg.M, cfg.N)
+    assert np.array_equal(D1.cpu().numpy(), D1_c)
+    g, c = gpu_schedule(D1_c, topo), cpu_schedule(D1_c, cfg.M, cfg.N, cfg.chunk_bytes)
+    assert_same(g, c, "c1 ")
+    assert c["stats"][0, 0] >= c["stats"][0, 3]
+
+
+def test_config2_two_layers_elementwise():
+    cfg = W.get_config("c2")
+    logits, idx, D1, topo = _moe_pipeline_gpu(cfg, [0, 31])
+    idx_c = oracle.route_topk(logits.cpu().numpy(), cfg.k)
+    assert np.array_equal(idx.cpu().numpy(), idx_c)
+    D1_c = oracle.traffic_matrix(idx_c, 2, cfg.tokens_per_gpu, W.expert_gpu_table(cfg), cfg.payload_bytes, cfg.M, cfg.N)
+    assert np.array_equal(D1.cpu().numpy(), D1_c)
+    assert_same(gpu_schedule(D1_c, topo), cpu_schedule(D1_c, cfg.M, cfg.N, cfg.chunk_bytes), "c2 ")
+
+
+def test_config3_shape_small_batch():
+    cfg = W.get_config("c3")
+    D1 = W.gen_flow_matrices(cfg, first=0, count=2)
+    topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes)
+    assert_same(gpu_schedule(D1, topo), cpu_schedule(D1, cfg.M, cfg.N, cfg.chunk_bytes), "c3 ")
+
+
+def test_config4_shape_reduced_tokens():
+    # DeepSeek-V3-shaped routing (E=256, top-8, 512 GPUs, 2 experts/GPU, 4 replicas) with 256 tokens per GPU
+    cfg = W.get_config("c4").scaled(tokens_per_gpu=256)
+    logits, idx, D1, topo = _moe_pipeline_gpu(cfg, [0])
+    idx_c = oracle.route_topk(logits.cpu().numpy(), cfg.k)
+    assert np.array_equal(idx.cpu().numpy(), idx_c)
+    D1_c = oracle.traffic_matrix(idx_c, 1, cfg.tokens_per_gpu, W.expert_gpu_table(cfg), cfg.payload_bytes, cfg.M, cfg.N)
+    assert np.array_equal(D1.cpu().numpy(), D1_c)
+    assert_same(gpu_schedule(D1_c, topo), cpu_schedule(D1_c, cfg.M, cfg.N, cfg.chunk_bytes), "c4 ")
