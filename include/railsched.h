@@ -125,6 +125,14 @@ int railsched_chunk_sort(const int64_t *D1, int32_t batch, const railsched_topo_
 int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
                         const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream);
 
+/* Same function, same arguments, same outputs bit for bit (Algorithm 2 step 3), but every single chunk
+ * goes through the cross-lane argmin; railsched_lpt_spray above additionally assigns whole periods of
+ * equal-weight chunks in closed form when the rail loads are within one weight of each other (the
+ * bound L_max <= L_opt + w_max of the Theorem 4 proof is what makes that state the common one).
+ * Kept as the plain reference kernel for measurements and cross-checks. */
+int railsched_lpt_spray_chunkwise(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
+                                  const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Stage 5 - load evaluation (Section 4.1 load matrices S and R; Theorem 2; Theorem 3).
  * Rail n of a source node ends on NIC n of the destination node, so a chunk whose destination GPU

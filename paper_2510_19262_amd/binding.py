@@ -20,7 +20,7 @@ _lib = None
 
 EXPORTS = (
     "railsched_version", "railsched_strerror", "railsched_route_topk", "railsched_traffic_matrix",
-    "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray",
+    "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray", "railsched_lpt_spray_chunkwise",
     "railsched_eval_workspace_bytes", "railsched_eval",
 )
 
@@ -77,11 +77,12 @@ def load():
     lib.railsched_chunk_sort_workspace_bytes.restype = SZ
     lib.railsched_chunk_sort.argtypes = [P, I32, TP, P, P, P, P, I64, P, SZ, P]
     lib.railsched_lpt_spray.argtypes = [P, P, I32, TP, P, P, P]
+    lib.railsched_lpt_spray_chunkwise.argtypes = [P, P, I32, TP, P, P, P]
     lib.railsched_eval_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_eval_workspace_bytes.restype = SZ
     lib.railsched_eval.argtypes = [P, P, P, P, P, I32, TP, P, P, P, SZ, P]
     for fn in ("railsched_route_topk", "railsched_traffic_matrix", "railsched_chunk_sort", "railsched_lpt_spray",
-               "railsched_eval"):
+               "railsched_lpt_spray_chunkwise", "railsched_eval"):
         getattr(lib, fn).restype = C.c_int
     _lib = lib
     return lib
@@ -208,8 +209,9 @@ def chunk_sort(D1: torch.Tensor, topo: Topo, want_perm: bool = True, capacity: O
 
 
 # ---------------------------------------------------------------------------------- stage 4
-def lpt_spray(chunk_off: torch.Tensor, chunk_w: torch.Tensor, batch: int, topo: Topo, out=None):
-    """Greedy least-loaded-rail assignment per instance -> (rail uint8 [chunks], S int64 [batch][M][N])."""
+def lpt_spray(chunk_off: torch.Tensor, chunk_w: torch.Tensor, batch: int, topo: Topo, out=None, chunkwise: bool = False):
+    """Greedy least-loaded-rail assignment per instance -> (rail uint8 [chunks], S int64 [batch][M][N]).
+    chunkwise=True calls railsched_lpt_spray_chunkwise (same result, no closed-form periods)."""
     _dev(chunk_off, torch.int64, "chunk_off")
     if chunk_w.dtype not in (torch.int32, torch.uint32):
         raise ValueError("chunk_w must be a 32-bit integer tensor")
@@ -219,8 +221,8 @@ def lpt_spray(chunk_off: torch.Tensor, chunk_w: torch.Tensor, batch: int, topo: 
     else:
         rail, S = out
     t = topo.c()
-    _check(load().railsched_lpt_spray(_ptr(chunk_off), _ptr(chunk_w), batch, C.byref(t), _ptr(rail), _ptr(S),
-                                      _stream()), "railsched_lpt_spray")
+    fn = load().railsched_lpt_spray_chunkwise if chunkwise else load().railsched_lpt_spray
+    _check(fn(_ptr(chunk_off), _ptr(chunk_w), batch, C.byref(t), _ptr(rail), _ptr(S), _stream()), "railsched_lpt_spray")
     return rail, S
 
 

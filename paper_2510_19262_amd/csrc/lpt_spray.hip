@@ -2,25 +2,35 @@
 //
 // The loop is serial inside one (matrix, node) instance - every decision depends on all earlier
 // ones - and independent across instances.  LoadState lives in lanes: a group of GW = 2^S lanes
-// (GW >= N) holds one instance, lane q holds rail q, and 64/GW instances share a wavefront, so one
-// instruction stream advances 64/GW schedulers.  Per chunk the group needs
+// (GW >= N) holds the N rail loads, lane q holds rail q.  Per chunk the group needs
 //   j* = lowest-numbered rail of minimum load,   LoadState[j*] += w.
 //
-// Fast path.  Greedy assignment keeps max(LoadState) - min(LoadState) <= the largest weight seen so
+// Packed keys.  Greedy assignment keeps max(LoadState) - min(LoadState) <= the largest weight seen so
 // far (the fullest rail was the emptiest one just before its last chunk).  Loads are therefore kept
 // as a 64-bit base shared by the group plus a small per-lane delta, and the lane packs
 // key = (delta << S) | q into 32 bits: one unsigned min over the group, done with DPP exchanges,
 // yields both the minimum and the lowest rail index that attains it, and key equality marks the
-// winner.  The base is advanced every kBatch chunks so deltas stay small.
-// Exact path.  As soon as a weight above the packing limit shows up, the instance group's wave
-// switches for good to plain 64-bit loads with an explicit (load, rail) lexicographic reduction.
-// Both paths compute the same function; the loads that leave the kernel are exact 64-bit sums.
+// winner.  The base is advanced after every period so deltas stay small.
+// Exact path.  As soon as a weight above the packing limit shows up, the wave switches for good to
+// plain 64-bit loads with an explicit (load, rail) lexicographic reduction.  Both compute the same
+// function; the loads that leave the kernel are exact 64-bit sums.
+// Runs.  Chunk lists are dominated by long runs of one weight (every full chunk weighs C).  A period
+// of equal weights that starts from loads within one weight of each other needs no chain at all (see
+// closed_period below).  railsched_lpt_spray uses that shortcut, railsched_lpt_spray_chunkwise never
+// does; their outputs are identical.
+//
+// Two launch shapes.  "Packed": 64/GW instances share a wavefront, one per lane group, so one
+// instruction stream advances several schedulers - the shape for tens of thousands of instances,
+// where issue slots are the limit.  "Wide": one instance per wavefront, its state replicated in
+// every lane group, all 64 lanes streaming weights and writing rails - the shape for few instances,
+// where the latency of the chain and of HBM is the limit and more wavefronts hide more of it.
 #include "common.h"
 
 namespace rs {
 
-constexpr int kBatch = 32;          // chunks per normalisation period and instance (64 when a group is a whole wave)
+constexpr int kBatch = 32;          // packed shape: chunks per period and instance (64 when a group is a whole wave)
 constexpr int kLptWaves = 4;        // wavefronts per workgroup
+constexpr int kWideDepth = 4;       // wide shape: periods of 64 chunks in flight per wavefront
 
 template <int GW> struct GroupBits;
 template <> struct GroupBits<4> { static constexpr int S = 2; };
@@ -29,15 +39,46 @@ template <> struct GroupBits<16> { static constexpr int S = 4; };
 template <> struct GroupBits<32> { static constexpr int S = 5; };
 template <> struct GroupBits<64> { static constexpr int S = 6; };
 
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_mov(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+
+// min(v, v of the partner lane).  The partner value is fetched with "old" = UINT_MAX, the identity
+// of unsigned min, which lets the compiler fold the lane exchange into one v_min_u32 with a DPP operand.
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_min(unsigned v)
+{
+    return min(v, (unsigned)__builtin_amdgcn_update_dpp((int)0xFFFFFFFF, (int)v, CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_max(unsigned v)
+{
+    return max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false));
+}
+
 template <int GW>
 __device__ __forceinline__ unsigned group_min_u32(unsigned v)
 {
-    v = min(v, xlane<1>(v));
-    v = min(v, xlane<2>(v));
-    if constexpr (GW >= 8) v = min(v, xlane<4>(v));
-    if constexpr (GW >= 16) v = min(v, xlane<8>(v));
+    v = dpp_min<0xB1>(v);                           // quad_perm [1,0,3,2]
+    v = dpp_min<0x4E>(v);                           // quad_perm [2,3,0,1]
+    if constexpr (GW >= 8) v = dpp_min<0x141>(v);   // row_half_mirror
+    if constexpr (GW >= 16) v = dpp_min<0x140>(v);  // row_mirror
     if constexpr (GW >= 32) v = min(v, xlane<16>(v));
     if constexpr (GW >= 64) v = min(v, xlane<32>(v));
+    return v;
+}
+
+template <int GW>
+__device__ __forceinline__ unsigned group_max_u32(unsigned v)
+{
+    v = dpp_max<0xB1>(v);
+    v = dpp_max<0x4E>(v);
+    if constexpr (GW >= 8) v = dpp_max<0x141>(v);
+    if constexpr (GW >= 16) v = dpp_max<0x140>(v);
+    if constexpr (GW >= 32) v = max(v, xlane<16>(v));
+    if constexpr (GW >= 64) v = max(v, xlane<32>(v));
     return v;
 }
 
@@ -63,6 +104,61 @@ __device__ __forceinline__ unsigned group_argmin_u64(unsigned long long load, un
     return q;
 }
 
+// f(value held by the lane whose in-group index is q ^ mask, mask) for every mask in 1..GW-1
+template <int GW, int T, typename F>
+__device__ __forceinline__ void partners_shfl(unsigned v, F &f)
+{
+    if constexpr (T < GW) { f((unsigned)__shfl_xor((int)v, T, GW), (unsigned)T); partners_shfl<GW, T + 1>(v, f); }
+}
+template <typename F>
+__device__ __forceinline__ void partners_quad(unsigned x, unsigned mask, F &f)
+{
+    if (mask != 0) f(x, mask);
+    f(dpp_mov<0xB1>(x), mask ^ 1u);                 // quad_perm [1,0,3,2]
+    f(dpp_mov<0x4E>(x), mask ^ 2u);                 // quad_perm [2,3,0,1]
+    f(dpp_mov<0x1B>(x), mask ^ 3u);                 // quad_perm [3,2,1,0]
+}
+template <int GW, typename F>
+__device__ __forceinline__ void for_each_partner(unsigned v, F f)
+{
+    if constexpr (GW <= 16) {
+        partners_quad(v, 0u, f);
+        if constexpr (GW >= 8) partners_quad(dpp_mov<0x141>(v), 7u, f);            // row_half_mirror: q ^ 7
+        if constexpr (GW >= 16) {
+            const unsigned r = dpp_mov<0x140>(v);                                 // row_mirror: q ^ 15
+            partners_quad(r, 15u, f);
+            partners_quad(dpp_mov<0x141>(r), 8u, f);
+        }
+    } else {
+        partners_shfl<GW, 1>(v, f);
+    }
+}
+
+// Closed form for a period of P chunks of one weight w > 0 entered with max - min load < w: with every
+// rail within w of the emptiest one, greedy assignment of equal weights visits the rails round after
+// round in the fixed order "ascending (load, rail)" - each pick lifts the emptiest rail above all
+// others by less than w.  So chunk i of the period goes to the rail of rank i mod N, and the rail of
+// rank s receives floor(P/N) + (s < P mod N) chunks.  Returns this lane's rank; adds its share to key.
+template <int GW>
+__device__ __forceinline__ unsigned closed_period(unsigned &key, bool has_rail, unsigned w, unsigned per_rank, unsigned extra)
+{
+    unsigned rank = 0;
+    const unsigned mine = key;
+    for_each_partner<GW>(mine, [&](unsigned other, unsigned) { rank += other < mine ? 1u : 0u; });
+    if (has_rail) key += (w * (per_rank + (rank < extra ? 1u : 0u))) << GroupBits<GW>::S;
+    return rank;
+}
+
+// in-group index of the lane whose rank equals `want` (ranks of rail lanes are a permutation of 0..N-1)
+template <int GW>
+__device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsigned want)
+{
+    unsigned res = q;
+    for_each_partner<GW>(rank, [&](unsigned other, unsigned mask) { res = (other == want) ? (q ^ mask) : res; });
+    return res;
+}
+
+// ================================================================================ packed shape
 // value held by lane T of the caller's GW-lane group
 template <int GW, int T>
 __device__ __forceinline__ unsigned group_bcast(unsigned v)
@@ -71,17 +167,27 @@ __device__ __forceinline__ unsigned group_bcast(unsigned v)
     else return (unsigned)__builtin_amdgcn_ds_swizzle((int)v, ((0x1F & ~(GW - 1)) | (T << 5)));   // lane = (lane & ~(GW-1)) | T
 }
 
+// Broadcast every weight of a period to its whole group, already shifted into key position, before the
+// chain starts, so that the exchange latency is paid once per period and not once per chunk.
 template <int GW, int STEP, int T>
-__device__ __forceinline__ void fast_steps(unsigned &key, const unsigned (&wv)[STEP / GW], unsigned (&won)[STEP / GW], unsigned q)
+__device__ __forceinline__ void bcast_steps(const unsigned (&wv)[STEP / GW], unsigned (&bc)[STEP])
 {
-    // chunk T of the period: its weight sits in lane T % GW of register T / GW
     if constexpr (T < STEP) {
-        constexpr int S = GroupBits<GW>::S;
-        const unsigned wS = group_bcast<GW, T % GW>(wv[T / GW]) << S;
+        bc[T] = group_bcast<GW, T % GW>(wv[T / GW]) << GroupBits<GW>::S;
+        bcast_steps<GW, STEP, T + 1>(wv, bc);
+    }
+}
+
+template <int GW, int STEP, int T>
+__device__ __forceinline__ void fast_steps(unsigned &key, const unsigned (&bc)[STEP], unsigned (&won)[STEP / GW], unsigned q)
+{
+    // chunk T of the period; the serial chain is: group min (log2 GW exchanges), compare, select
+    if constexpr (T < STEP) {
+        const unsigned bumped = key + bc[T];        // off the chain: does not need the minimum
         const unsigned m = group_min_u32<GW>(key);
-        key += (key == m) ? wS : 0u;
         won[T / GW] = (q == (unsigned)(T % GW)) ? m : won[T / GW];
-        fast_steps<GW, STEP, T + 1>(key, wv, won, q);
+        key = (key == m) ? bumped : key;
+        fast_steps<GW, STEP, T + 1>(key, bc, won, q);
     }
 }
 
@@ -98,14 +204,14 @@ __device__ __forceinline__ void exact_steps(unsigned long long &load, const unsi
     }
 }
 
-template <int GW>
-__global__ __launch_bounds__(64 * kLptWaves) void lpt_spray_kernel(const int64_t *__restrict__ chunk_off,
-                                                                   const uint32_t *__restrict__ chunk_w, int n_inst, int N,
-                                                                   uint8_t *__restrict__ rail, int64_t *__restrict__ S_out)
+template <int GW, bool RUNS>
+__global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_t *__restrict__ chunk_off,
+                                                                    const uint32_t *__restrict__ chunk_w, int n_inst, int N,
+                                                                    uint8_t *__restrict__ rail, int64_t *__restrict__ S_out)
 {
     constexpr int S = GroupBits<GW>::S;
     constexpr int IPW = 64 / GW;                    // instances per wavefront
-    constexpr int STEP = kBatch > GW ? kBatch : GW; // chunks per instance and normalisation period
+    constexpr int STEP = kBatch > GW ? kBatch : GW; // chunks per instance and period
     constexpr int REGS = STEP / GW;
     // packing limit: inside a period no delta exceeds (STEP + 2) maximal weights, and the largest
     // packed key must stay below the all-ones key of lanes that hold no rail
@@ -128,61 +234,194 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_spray_kernel(const int64_t
     unsigned long long base = 0, load = has_rail ? 0ull : ~0ull;
     bool exact = false;                             // wave-uniform
 
-    for (int64_t i0 = 0; i0 < max_len; i0 += STEP) {
-        unsigned wv[REGS], won[REGS];
+    const unsigned per_rank = (unsigned)(STEP / N), extra = (unsigned)(STEP % N);
+    unsigned want[REGS];                            // rank that owns each of this lane's chunks of a period
+#pragma unroll
+    for (int r = 0; r < REGS; ++r) want[r] = (unsigned)(r * GW + q) % (unsigned)N;
+
+    // weights of period p: lane q of a group holds chunks p*STEP + r*GW + q; past the end weight 0 (changes nothing)
+    auto fetch = [&](int64_t i0, unsigned (&wv)[REGS]) {
 #pragma unroll
         for (int r = 0; r < REGS; ++r) {
             const int64_t i = i0 + r * GW + q;
-            wv[r] = (i < len) ? chunk_w[beg + i] : 0u;   // past the end: weight 0 changes nothing
-            won[r] = 0;
+            wv[r] = (i < len) ? chunk_w[beg + i] : 0u;
         }
+    };
+    unsigned wv_cur[REGS], wv_nxt[REGS];
+    fetch(0, wv_cur);
+    fetch(STEP, wv_nxt);
+
+    for (int64_t i0 = 0; i0 < max_len; i0 += STEP) {
+        unsigned wv_far[REGS], won[REGS];
+        fetch(i0 + 2 * STEP, wv_far);               // two periods ahead: HBM/L2 latency
+#pragma unroll
+        for (int r = 0; r < REGS; ++r) won[r] = 0;
         if (!exact) {
             unsigned big = 0;
 #pragma unroll
-            for (int r = 0; r < REGS; ++r) big |= (wv[r] > W_LIMIT) ? 1u : 0u;
+            for (int r = 0; r < REGS; ++r) big |= (wv_cur[r] > W_LIMIT) ? 1u : 0u;
             if (__ballot(big != 0) != 0ull) {       // leave the packed representation for good
                 exact = true;
                 if (has_rail) load = base + (unsigned long long)(key >> S);
             }
         }
-        if (!exact) {
-            fast_steps<GW, STEP, 0>(key, wv, won, q);
-            // advance the base to the current minimum so deltas stay below the packing limit
-            const unsigned m = group_min_u32<GW>(key);
-            const unsigned adv = (m >> S);
-            if (has_rail) { key -= adv << S; base += adv; }
+        bool closed = false;                        // wave-uniform
+        unsigned w0 = 0;
+        if (RUNS && !exact) {
+            const bool done = i0 >= len;            // this group's instance is already finished
+            w0 = group_bcast<GW, 0>(wv_cur[0]);
+            bool same = true;
+#pragma unroll
+            for (int r = 0; r < REGS; ++r) same = same && (wv_cur[r] == w0);
+            const unsigned dmin = group_min_u32<GW>(key) >> S;
+            const unsigned dmax = group_max_u32<GW>(has_rail ? (key >> S) : 0u);
+            const bool ok = done || (same && w0 != 0u && (i0 + STEP <= len) && (dmax - dmin) < w0);
+            closed = __ballot(!ok) == 0ull;
+            if (done) w0 = 0;
+        }
+        if (closed) {
+            const unsigned rank = closed_period<GW>(key, has_rail, w0, per_rank, extra);
+#pragma unroll
+            for (int r = 0; r < REGS; ++r) won[r] = rail_of_rank<GW>(rank, q, want[r]);
+        } else if (!exact) {
+            unsigned bc[STEP];
+            bcast_steps<GW, STEP, 0>(wv_cur, bc);
+            fast_steps<GW, STEP, 0>(key, bc, won, q);
 #pragma unroll
             for (int r = 0; r < REGS; ++r) won[r] &= (unsigned)(GW - 1);
         } else {
-            exact_steps<GW, STEP, 0>(load, wv, won, q);
+            exact_steps<GW, STEP, 0>(load, wv_cur, won, q);
+        }
+        if (!exact) {
+            // advance the base to the current minimum so deltas stay below the packing limit
+            const unsigned adv = group_min_u32<GW>(key) >> S;
+            if (has_rail) { key -= adv << S; base += adv; }
         }
 #pragma unroll
         for (int r = 0; r < REGS; ++r) {
             const int64_t i = i0 + r * GW + q;
             if (i < len) rail[beg + i] = (uint8_t)won[r];
         }
+#pragma unroll
+        for (int r = 0; r < REGS; ++r) { wv_cur[r] = wv_nxt[r]; wv_nxt[r] = wv_far[r]; }
     }
     if (has_rail) S_out[(int64_t)inst * N + q] = (int64_t)(exact ? load : base + (unsigned long long)(key >> S));
 }
 
-template <int GW>
+// ================================================================================ wide shape
+// One instance per wavefront.  Every GW-lane group carries a copy of the N rail loads and runs the
+// same reduction, so all 64 lanes know each decision; lane t keeps the decision for chunk t of the
+// 64-chunk period, and weights reach the chain through v_readlane (a scalar broadcast).
+template <int GW, bool RUNS>
+__global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t *__restrict__ chunk_off,
+                                                                  const uint32_t *__restrict__ chunk_w, int n_inst, int N,
+                                                                  uint8_t *__restrict__ rail, int64_t *__restrict__ S_out)
+{
+    constexpr int S = GroupBits<GW>::S;
+    constexpr int P = 64;                           // chunks per period: one per lane
+    constexpr unsigned W_LIMIT = (unsigned)((0xFFFFFFFFu >> S) / (unsigned)(P + 2)) - 1u;
+
+    const int lane = threadIdx.x & 63;
+    const unsigned q = (unsigned)(lane % GW);
+    const int inst = (int)((blockIdx.x * (unsigned)kLptWaves) + (threadIdx.x >> 6));
+    if (inst >= n_inst) return;                     // whole wavefront leaves; nothing below synchronises across waves
+    const bool has_rail = (int)q < N;
+    const int64_t beg = chunk_off[inst];
+    const int64_t len = chunk_off[inst + 1] - beg;
+
+    unsigned key = has_rail ? q : 0xFFFFFFFFu;
+    unsigned long long base = 0, load = has_rail ? 0ull : ~0ull;
+    bool exact = false;
+
+    const unsigned per_rank = (unsigned)(P / N), extra = (unsigned)(P % N);
+    const unsigned want = (unsigned)lane % (unsigned)N;
+
+    const uint32_t *wsrc = chunk_w + beg;
+    uint8_t *rdst = rail + beg;
+    unsigned ring[kWideDepth];
+#pragma unroll
+    for (int d = 0; d < kWideDepth; ++d) ring[d] = ((int64_t)d * P + lane < len) ? wsrc[(int64_t)d * P + lane] : 0u;
+
+    for (int64_t i0 = 0; i0 < len; i0 += (int64_t)kWideDepth * P) {
+#pragma unroll
+        for (int d = 0; d < kWideDepth; ++d) {
+            const int64_t p0 = i0 + (int64_t)d * P;
+            if (p0 >= len) break;                   // wave-uniform
+            const unsigned wv = ring[d];
+            {
+                const int64_t nx = p0 + (int64_t)kWideDepth * P + lane;   // refill this slot: kWideDepth periods ahead
+                ring[d] = (nx < len) ? wsrc[nx] : 0u;
+            }
+            unsigned won = 0;
+            if (!exact && __ballot(wv > W_LIMIT) != 0ull) {
+                exact = true;
+                if (has_rail) load = base + (unsigned long long)(key >> S);
+            }
+            bool closed = false;
+            unsigned w0 = 0;
+            if (RUNS && !exact) {
+                w0 = (unsigned)__builtin_amdgcn_readfirstlane((int)wv);
+                const unsigned dmin = group_min_u32<GW>(key) >> S;
+                const unsigned dmax = group_max_u32<GW>(has_rail ? (key >> S) : 0u);
+                const bool ok = (wv == w0) && w0 != 0u && (p0 + P <= len) && (dmax - dmin) < w0;
+                closed = __ballot(!ok) == 0ull;
+            }
+            if (closed) {
+                const unsigned rank = closed_period<GW>(key, has_rail, w0, per_rank, extra);
+                won = rail_of_rank<GW>(rank, q, want);
+            } else if (!exact) {
+#pragma unroll 8
+                for (int t = 0; t < P; ++t) {
+                    const unsigned wS = (unsigned)__builtin_amdgcn_readlane((int)wv, t) << S;
+                    const unsigned bumped = key + wS;
+                    const unsigned m = group_min_u32<GW>(key);
+                    won = (lane == t) ? m : won;
+                    key = (key == m) ? bumped : key;
+                }
+                won &= (unsigned)(GW - 1);
+            } else {
+#pragma unroll 2
+                for (int t = 0; t < P; ++t) {
+                    const unsigned w = (unsigned)__builtin_amdgcn_readlane((int)wv, t);
+                    const unsigned js = group_argmin_u64<GW>(load, q);
+                    load += (q == js) ? (unsigned long long)w : 0ull;
+                    won = (lane == t) ? js : won;
+                }
+            }
+            if (!exact) {
+                const unsigned adv = group_min_u32<GW>(key) >> S;
+                if (has_rail) { key -= adv << S; base += adv; }
+            }
+            if (p0 + lane < len) rdst[p0 + lane] = (uint8_t)won;
+        }
+    }
+    if (lane < N) S_out[(int64_t)inst * N + lane] = (int64_t)(exact ? load : base + (unsigned long long)(key >> S));
+}
+
+template <int GW, bool RUNS>
 static int launch_lpt(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
                       int64_t *S, hipStream_t st)
 {
     constexpr int IPW = 64 / GW;
-    const int64_t waves = (n_inst + IPW - 1) / IPW;
-    const int64_t blocks = (waves + kLptWaves - 1) / kLptWaves;
-    hipLaunchKernelGGL((lpt_spray_kernel<GW>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off, chunk_w,
-                       (int)n_inst, N, rail, S);
+    // packed once it yields at least two wavefronts per SIMD (256 CUs x 4 SIMDs); wide below that
+    const bool packed = IPW > 1 && n_inst >= (int64_t)2048 * IPW;
+    if (packed) {
+        const int64_t waves = (n_inst + IPW - 1) / IPW;
+        const int64_t blocks = (waves + kLptWaves - 1) / kLptWaves;
+        hipLaunchKernelGGL((lpt_packed_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
+                           chunk_w, (int)n_inst, N, rail, S);
+    } else {
+        const int64_t blocks = (n_inst + kLptWaves - 1) / kLptWaves;
+        hipLaunchKernelGGL((lpt_wide_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
+                           chunk_w, (int)n_inst, N, rail, S);
+    }
     return launch_status();
 }
 
-}  // namespace rs
-
-extern "C" int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
-                                   const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream)
+template <bool RUNS>
+static int lpt_entry(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch, const railsched_topo_t *h_topo,
+                     uint8_t *rail, int64_t *S, void *stream)
 {
-    using namespace rs;
     if (int rc = check_topo(h_topo)) return rc;
     if (batch < 0) return RAILSCHED_ERR_INVALID_ARG;
     const int64_t n_inst = (int64_t)batch * h_topo->nodes;
@@ -191,9 +430,23 @@ extern "C" int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chu
     if (!chunk_off || !S) return RAILSCHED_ERR_NULL_PTR;   // chunk_w / rail may be NULL only when there are no chunks
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int N = h_topo->rails;
-    if (N <= 4) return launch_lpt<4>(chunk_off, chunk_w, n_inst, N, rail, S, st);
-    if (N <= 8) return launch_lpt<8>(chunk_off, chunk_w, n_inst, N, rail, S, st);
-    if (N <= 16) return launch_lpt<16>(chunk_off, chunk_w, n_inst, N, rail, S, st);
-    if (N <= 32) return launch_lpt<32>(chunk_off, chunk_w, n_inst, N, rail, S, st);
-    return launch_lpt<64>(chunk_off, chunk_w, n_inst, N, rail, S, st);
+    if (N <= 4) return launch_lpt<4, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
+    if (N <= 8) return launch_lpt<8, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
+    if (N <= 16) return launch_lpt<16, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
+    if (N <= 32) return launch_lpt<32, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
+    return launch_lpt<64, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
+}
+
+}  // namespace rs
+
+extern "C" int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
+                                   const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream)
+{
+    return rs::lpt_entry<true>(chunk_off, chunk_w, batch, h_topo, rail, S, stream);
+}
+
+extern "C" int railsched_lpt_spray_chunkwise(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
+                                             const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream)
+{
+    return rs::lpt_entry<false>(chunk_off, chunk_w, batch, h_topo, rail, S, stream);
 }

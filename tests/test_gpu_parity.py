@@ -196,10 +196,11 @@ def _lpt_case(weights_per_inst, M, N, batch=1):
     w = np.concatenate([np.asarray(x, dtype=np.uint32) for x in weights_per_inst]) if sum(lens) else np.zeros(0, np.uint32)
     topo = rs.Topo(M, N, 1 << 20)
     wt = torch.from_numpy(w.view(np.int32).copy()).to(DEV) if w.size else torch.zeros(1, dtype=torch.int32, device=DEV)
-    rail, S = rs.lpt_spray(torch.from_numpy(off).to(DEV), wt, batch, topo)
     rail_c, S_c = oracle.lpt_batch(off, w, batch, M, N)
-    assert np.array_equal(rail.cpu().numpy()[:w.size], rail_c)
-    assert np.array_equal(S.cpu().numpy(), S_c)
+    for chunkwise in (False, True):
+        rail, S = rs.lpt_spray(torch.from_numpy(off).to(DEV), wt, batch, topo, chunkwise=chunkwise)
+        assert np.array_equal(rail.cpu().numpy()[:w.size], rail_c), f"rail, chunkwise={chunkwise}"
+        assert np.array_equal(S.cpu().numpy(), S_c), f"S, chunkwise={chunkwise}"
 
 
 @pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 8, 11, 16, 24, 32, 40, 64])
@@ -235,7 +236,8 @@ def test_lpt_large_weights_take_the_exact_path(N):
 
 def test_lpt_weights_at_the_packing_limit():
     # weights just below / at / above the switch-over, many chunks so the loads pass 2^32
-    for N, lim in ((8, ((0xFFFFFFFF >> 3) // 34) - 1), (64, ((0xFFFFFFFF >> 6) // 66) - 1)):
+    for N, lim in ((8, ((0xFFFFFFFF >> 3) // 34) - 1), (8, ((0xFFFFFFFF >> 3) // 66) - 1), (64, ((0xFFFFFFFF >> 6) // 66) - 1),
+                   (4, ((0xFFFFFFFF >> 2) // 66) - 1), (16, ((0xFFFFFFFF >> 4) // 66) - 1)):
         insts = [np.full(400, lim, dtype=np.uint32), np.full(400, lim + 1, dtype=np.uint32),
                  np.concatenate([np.full(200, lim), np.arange(200, 0, -1)]).astype(np.uint32)]
         _lpt_case(insts, 3, N)
@@ -246,6 +248,67 @@ def test_lpt_tight_family_and_small_cases():
     _lpt_case([[9, 7, 3], [], [4]], 3, 5)
     _lpt_case([[], []], 2, 8)
     _lpt_case([[7] * 1000], 1, 8)
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 6, 7, 8, 12, 16, 31, 32, 48, 64])
+def test_lpt_long_runs_of_equal_weights(N):
+    # runs much longer than a period, entered from balanced and from unbalanced loads, of every
+    # residue modulo N, with weights that make max-min equal to, just below and just above the run weight
+    rng = np.random.default_rng(500 + N)
+    insts = []
+    for i in range(23):
+        parts = []
+        for _ in range(int(rng.integers(1, 6))):
+            w = int(rng.choice([0, 1, 7, 4096, 65536, 262144, 100000]))
+            parts.append(np.full(int(rng.integers(1, 400)), w))
+            if rng.random() < 0.5:
+                parts.append(rng.integers(0, 300000, size=int(rng.integers(0, 40))))
+        w = np.concatenate(parts)
+        if i % 2 == 0:
+            w = np.sort(w)[::-1]
+        insts.append(w)
+    insts.append(np.concatenate([[300], np.full(500, 300)]))                 # spread == weight on entry
+    insts.append(np.concatenate([[299], np.full(500, 300)]))
+    insts.append(np.concatenate([[301], np.full(500, 300)]))
+    insts.append(np.concatenate([[1000, 900, 800], np.full(777, 100), np.full(333, 3)]))
+    _lpt_case(insts, len(insts), N)
+
+
+def test_lpt_chunk_lists_from_stage3_shapes():
+    # what stage 3 emits: one long run of C, then sorted tails on a coarse lattice
+    rng = np.random.default_rng(77)
+    C, gran = 262144, 8192
+    insts = []
+    for i in range(40):
+        nfull = int(rng.integers(0, 9000))
+        tails = np.sort(rng.integers(1, C // gran, size=int(rng.integers(0, 450))) * gran)[::-1]
+        insts.append(np.concatenate([np.full(nfull, C), tails]))
+    _lpt_case(insts, 8, 8, batch=5)
+
+
+@pytest.mark.parametrize("N", [3, 4, 7, 8, 13, 16, 20, 32])
+def test_lpt_packed_shape_many_instances(N):
+    # enough instances that several share a wavefront (one per lane group): ragged lengths, runs, mixed weights
+    gw = 4 if N <= 4 else 8 if N <= 8 else 16 if N <= 16 else 32
+    n_inst = 2048 * (64 // gw) + 37
+    rng = np.random.default_rng(900 + N)
+    lens = rng.integers(0, 120, size=n_inst)
+    lens[rng.random(n_inst) < 0.02] = 0
+    lens[:50] = rng.integers(300, 900, size=50)
+    insts = []
+    for i, n in enumerate(lens):
+        kind = i % 4
+        if kind == 0:
+            w = np.full(n, 65536)
+        elif kind == 1:
+            w = np.sort(rng.integers(1, 32, size=n) * 8192)[::-1]
+        elif kind == 2:
+            w = np.concatenate([np.full(n // 2, 262144), np.sort(rng.integers(1, 262144, size=n - n // 2))[::-1]])
+        else:
+            w = rng.integers(0, 1 << 20, size=n)
+        insts.append(w)
+    insts[7] = np.concatenate([[5_000_000_00], rng.integers(0, 1 << 30, size=40)])   # drags its wavefront onto the exact path
+    _lpt_case(insts, 1, N, batch=n_inst)                      # one node per matrix, n_inst matrices
 
 
 def test_lpt_many_instances():
