@@ -26,7 +26,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c2", help="workload (c1, c2; default c2 = the benchmark workload)")
-    ap.add_argument("--cpu-layers", type=int, default=8, help="layers of the workload the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-layers", type=int, default=-1,
+                    help="layers of the workload the CPU oracle is timed on (-1 = all, 0 = skip)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device copy first: a kernel of known traffic to scale profiler byte counters by")
     return ap.parse_args()
 
 
@@ -57,6 +60,12 @@ def main():
         logits[b * cfg.rows_per_layer:(b + 1) * cfg.rows_per_layer] = W.gen_logits(cfg, b, device=dev)
     eg_np = W.expert_gpu_table(cfg)
     expert_gpu = torch.from_numpy(eg_np).to(dev)
+
+    if args.copy_probe:
+        probe = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        probe.copy_(logits.view(-1)[: 1 << 28])
+        torch.cuda.synchronize()
+        del probe
 
     # ---- size the record arrays once (count query), then a plan that allocates nothing per step
     idx0 = rs.route_topk(logits, cfg.k)
@@ -103,6 +112,19 @@ def main():
     stage_ms = {n: v / args.steps for n, v in stage_ms.items()}
 
     assert int(plan.chunk_off[-1].item()) == total_chunks
+
+    # ---- supplementary: the plain per-chunk LPT kernel on the same records (same outputs, no closed-form periods)
+    rail2, S2 = torch.empty_like(plan.rail), torch.empty_like(plan.S)
+    cw = []
+    for i in range(3 + min(args.steps, 10)):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(rail2, S2), chunkwise=True)
+        e1.record()
+        cw.append((e0, e1))
+    torch.cuda.synchronize()
+    chunkwise_ms = sum(a.elapsed_time(b) for a, b in cw[3:]) / max(len(cw) - 3, 1)
+    assert torch.equal(rail2[:total_chunks], plan.rail[:total_chunks]) and torch.equal(S2, plan.S)
     stats = plan.stats.cpu().numpy()
     ratio = stats[:, 0] / np.maximum(stats[:, 3], 1)
 
@@ -112,6 +134,12 @@ def main():
     k1_gbps = k1_bytes / (stage_ms["route_topk"] * 1e-3) / 1e9
     routing_gbps = (k1_bytes + k2_bytes) / ((stage_ms["route_topk"] + stage_ms["traffic_matrix"]) * 1e-3) / 1e9
     dominant = max(stage_ms, key=stage_ms.get)
+    # LPT against the VALU issue rate: ceil(log2 N) cross-lane mins + compare + select + add per chunk and lane group,
+    # 64/GW lane groups per wavefront instruction; 256 CUs x 4 SIMDs issue one wave64 VALU instruction per 4 cycles at 2.4 GHz
+    gw = 4 if cfg.N <= 4 else 8 if cfg.N <= 8 else 16 if cfg.N <= 16 else 32 if cfg.N <= 32 else 64
+    instr_per_chunk = (gw.bit_length() - 1 + 3) / (64 // gw)
+    valu_peak = 256 * 4 * 2.4e9 / 4 / 1e9            # G wave-instructions/s
+    lpt_rate = total_chunks / (stage_ms["lpt_spray"] * 1e-3)
 
     out = {
         "metric": "LPT-sprayed chunks/s over the whole path (route_topk, traffic_matrix, chunk_sort, lpt_spray, eval)",
@@ -127,7 +155,11 @@ def main():
         "stage_ms": stage_ms,
         "routing_to_traffic_matrix_GBps": routing_gbps,
         "routing_frac_of_hbm_peak": routing_gbps / HBM_PEAK_GBPS,
-        "lpt_spray_chunks_per_s": total_chunks / (stage_ms["lpt_spray"] * 1e-3),
+        "lpt_spray_chunks_per_s": lpt_rate,
+        "lpt_roofline": {"bound": "alu", "achieved": lpt_rate * instr_per_chunk / 1e9, "peak": valu_peak,
+                         "unit": "G wave-instr/s", "frac": lpt_rate * instr_per_chunk / 1e9 / valu_peak,
+                         "note": f"{B * cfg.M} instances cannot fill 1024 SIMDs: the serial chain's latency, not issue rate, bounds this workload"},
+        "lpt_spray_chunkwise_ms": chunkwise_ms,
         "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
         "completion_time_us_max": float(stats[:, 0].max() / cfg.rail_bw_Bps * 1e6),
         "roofline": {"kernel": "route_topk_kernel", "bound": "hbm", "achieved": k1_gbps, "peak": HBM_PEAK_GBPS,
@@ -137,9 +169,9 @@ def main():
     }
 
     # ---- CPU baseline: the oracle as it stands, on the first layers of the same workload
-    if args.cpu_layers > 0:
+    if args.cpu_layers != 0:
         import oracle
-        L = min(args.cpu_layers, B)
+        L = B if args.cpu_layers < 0 else min(args.cpu_layers, B)
         x = logits[: L * cfg.rows_per_layer].cpu().numpy()
         c0 = time.perf_counter()
         idx_c = oracle.route_topk(x, cfg.k)
