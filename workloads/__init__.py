@@ -31,7 +31,7 @@ import torch
 
 __all__ = [
     "Config", "CONFIGS", "get_config", "expert_gpu_table", "expert_bias",
-    "gen_logits", "gen_flow_matrices", "mix64_np", "symmetric_matrix",
+    "gen_logits", "gen_flow_matrices", "gen_flow_matrices_device", "mix64_np", "symmetric_matrix",
 ]
 
 
@@ -235,6 +235,34 @@ def gen_flow_matrices(cfg: Config, first: int = 0, count: Optional[int] = None) 
         size = np.floor(np.exp(mu + cfg.sigma * z) / cfg.round_bytes + 0.5) * cfg.round_bytes
         m = np.where(u1 < cfg.p_zero, 0.0, size).astype(np.int64).reshape(G, G)
         np.fill_diagonal(m, 0)
+        out[i] = m
+    return out
+
+
+def gen_flow_matrices_device(cfg: Config, device, first: int = 0, count: Optional[int] = None) -> torch.Tensor:
+    """Same recipe as gen_flow_matrices, evaluated with torch on `device` (int64 [count][G][G]).
+
+    exp/log/cos come from the device's math library, so the values can differ from the numpy ones in
+    rare rounding cases: whoever uses this must hand copies of the SAME tensor to every consumer."""
+    assert cfg.kind == "flows"
+    if count is None:
+        count = cfg.batch - first
+    G = cfg.G
+    idx = torch.arange(G * G, dtype=torch.int64, device=device)
+    mu = math.log(cfg.mu_bytes)
+    out = torch.empty((count, G, G), dtype=torch.int64, device=device)
+
+    def uni(b, salt):
+        h = _mix64_torch(idx * _s64(_GOLDEN) + _s64(_stream_key(cfg.seed, b, salt)))
+        return (_lsr(h, 11).to(torch.float64) + 0.5) * (1.0 / 9007199254740992.0)
+
+    for i in range(count):
+        b = first + i
+        u1, u2, u3 = uni(b, 0xF10A1), uni(b, 0xF10A2), uni(b, 0xF10A3)
+        z = torch.sqrt(-2.0 * torch.log(u2)) * torch.cos(2.0 * math.pi * u3)
+        size = torch.floor(torch.exp(mu + cfg.sigma * z) / cfg.round_bytes + 0.5) * cfg.round_bytes
+        m = torch.where(u1 < cfg.p_zero, torch.zeros_like(size), size).to(torch.int64).view(G, G)
+        m.fill_diagonal_(0)
         out[i] = m
     return out
 
