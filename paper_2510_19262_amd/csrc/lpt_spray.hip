@@ -19,6 +19,11 @@
 // closed_period below).  railsched_lpt_spray uses that shortcut, railsched_lpt_spray_chunkwise never
 // does; their outputs are identical.
 //
+// Leading run.  From empty rails a run of one weight w > 0 is pure round robin: chunk i goes to rail
+// i mod N whatever happened elsewhere, so it needs no state and is written by a streaming kernel over
+// all chunks of all instances at once (lpt_prefix_kernel), which also finds, per instance, where the
+// run ends.  The serial kernels then start behind it with the closed-form loads.
+//
 // Two launch shapes.  "Packed": 64/GW instances share a wavefront, one per lane group, so one
 // instruction stream advances several schedulers - the shape for tens of thousands of instances,
 // where issue slots are the limit.  "Wide": one instance per wavefront, its state replicated in
@@ -158,6 +163,95 @@ __device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsi
     return res;
 }
 
+// ================================================================================ leading run
+constexpr int kPfThreads = 256;
+constexpr int kPfTile = 8192;       // chunk positions per workgroup iteration (8 x uint4 per thread)
+constexpr int kPfStage = 1024;      // instance boundaries staged in LDS per tile
+constexpr int kPfBlocks = 2048;
+
+__global__ void lpt_prefix_init_kernel(int64_t *run_end, int n_inst, int N)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_inst; i += gridDim.x * blockDim.x) run_end[(int64_t)i * N] = INT64_MAX;
+}
+
+__device__ __forceinline__ int last_le_i64(const int64_t *v, int n, int64_t x)   // last i in [0,n) with v[i] <= x (v[0] <= x)
+{
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (v[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Every chunk position p of every instance: rail[p] = (position inside the instance) mod N, and
+// run_end[inst*N] = min(position inside the instance of the first weight that differs from the
+// instance's first weight).  Positions are handled four at a time at multiples of four, so weights
+// load as 16 bytes and rails store as 4 bytes whatever the instance offsets are.  run_end lives in the
+// first slot of the instance's S row, which the serial kernel overwrites with the loads afterwards.
+__global__ __launch_bounds__(kPfThreads) void lpt_prefix_kernel(const int64_t *__restrict__ chunk_off,
+                                                                const uint32_t *__restrict__ chunk_w, int n_inst, int N,
+                                                                int nmask, uint8_t *__restrict__ rail, int64_t *run_end,
+                                                                int wide_ok)
+{
+    __shared__ int64_t s_off[kPfStage + 1];
+    __shared__ uint32_t s_w0[kPfStage];
+    const int64_t total = chunk_off[n_inst];
+    for (int64_t t0 = (int64_t)blockIdx.x * kPfTile; t0 < total; t0 += (int64_t)gridDim.x * kPfTile) {
+        const int64_t t1 = t0 + kPfTile < total ? t0 + kPfTile : total;
+        const int inst_lo = last_le_i64(chunk_off, n_inst, t0);
+        const int inst_hi = last_le_i64(chunk_off, n_inst, t1 - 1);
+        const int cnt = inst_hi - inst_lo + 1;
+        const bool staged = cnt <= kPfStage;
+        __syncthreads();                                   // previous tile is done with the stage
+        if (staged) {
+            for (int i = threadIdx.x; i <= cnt; i += kPfThreads) s_off[i] = chunk_off[inst_lo + i];
+            for (int i = threadIdx.x; i < cnt; i += kPfThreads) {
+                const int64_t b = chunk_off[inst_lo + i];
+                s_w0[i] = b < total ? chunk_w[b] : 0u;      // an empty instance's value is never used
+            }
+        }
+        __syncthreads();
+        for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPfThreads * 4) {
+            uint32_t w[4];
+            const bool full = p + 4 <= total;
+            if (full && wide_ok) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(chunk_w + p);
+                w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = (p + e < total) ? chunk_w[p + e] : 0u;
+            }
+            int li = staged ? last_le_i64(s_off, cnt, p) : last_le_i64(chunk_off, n_inst, p) - inst_lo;
+            uint32_t packed = 0;
+            int64_t miss_inst = -1, miss_pos = 0;          // first mismatch seen by this thread, per instance
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (p + e >= total) break;
+                int64_t nxt = staged ? s_off[li + 1] : chunk_off[inst_lo + li + 1];
+                while (p + e >= nxt) { ++li; nxt = staged ? s_off[li + 1] : chunk_off[inst_lo + li + 1]; }
+                const int64_t b = staged ? s_off[li] : chunk_off[inst_lo + li];
+                const uint32_t w0 = staged ? s_w0[li] : chunk_w[b];
+                const int64_t i = p + e - b;
+                const uint32_t r = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
+                packed |= r << (8 * e);
+                if (w[e] != w0 && miss_inst != inst_lo + li) {
+                    if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
+                    miss_inst = inst_lo + li; miss_pos = i;
+                }
+            }
+            // most positions behind the run's end find a smaller value already there and skip the atomic
+            if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
+            if (full && wide_ok) {
+                *reinterpret_cast<uint32_t *>(rail + p) = packed;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) if (p + e < total) rail[p + e] = (uint8_t)(packed >> (8 * e));
+            }
+        }
+    }
+}
+
 // ================================================================================ packed shape
 // value held by lane T of the caller's GW-lane group
 template <int GW, int T>
@@ -223,15 +317,27 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
     const int inst = wave * IPW + lane / GW;
     const bool has_inst = inst < n_inst;
     const bool has_rail = has_inst && (int)q < N;
-    const int64_t beg = has_inst ? chunk_off[inst] : 0;
-    const int64_t len = has_inst ? chunk_off[inst + 1] - beg : 0;
+    int64_t beg = has_inst ? chunk_off[inst] : 0;
+    int64_t len = has_inst ? chunk_off[inst + 1] - beg : 0;
+    unsigned long long base = 0;
+    if (RUNS && len > 0) {
+        // skip the leading run (already assigned round robin): start behind it with equal loads
+        const unsigned w0 = chunk_w[beg];
+        int64_t r0 = S_out[(int64_t)inst * N];
+        r0 = r0 < len ? r0 : len;
+        if (w0 != 0u && w0 <= W_LIMIT) {
+            const int64_t skip = r0 - r0 % N;
+            base = (unsigned long long)w0 * (unsigned long long)(skip / N);
+            beg += skip; len -= skip;
+        }
+    }
 
     int64_t max_len = len;                          // the wave runs as long as its longest instance
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) { const int64_t o = __shfl_xor(max_len, d); max_len = o > max_len ? o : max_len; }
 
     unsigned key = has_rail ? q : 0xFFFFFFFFu;
-    unsigned long long base = 0, load = has_rail ? 0ull : ~0ull;
+    unsigned long long load = has_rail ? 0ull : ~0ull;
     bool exact = false;                             // wave-uniform
 
     const unsigned per_rank = (unsigned)(STEP / N), extra = (unsigned)(STEP % N);
@@ -326,11 +432,23 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t 
     const int inst = (int)((blockIdx.x * (unsigned)kLptWaves) + (threadIdx.x >> 6));
     if (inst >= n_inst) return;                     // whole wavefront leaves; nothing below synchronises across waves
     const bool has_rail = (int)q < N;
-    const int64_t beg = chunk_off[inst];
-    const int64_t len = chunk_off[inst + 1] - beg;
+    int64_t beg = chunk_off[inst];
+    int64_t len = chunk_off[inst + 1] - beg;
+    unsigned long long base = 0;
+    if (RUNS && len > 0) {
+        // skip the leading run (already assigned round robin): start behind it with equal loads
+        const unsigned w0 = chunk_w[beg];
+        int64_t r0 = S_out[(int64_t)inst * N];
+        r0 = r0 < len ? r0 : len;
+        if (w0 != 0u && w0 <= W_LIMIT) {
+            const int64_t skip = r0 - r0 % N;
+            base = (unsigned long long)w0 * (unsigned long long)(skip / N);
+            beg += skip; len -= skip;
+        }
+    }
 
     unsigned key = has_rail ? q : 0xFFFFFFFFu;
-    unsigned long long base = 0, load = has_rail ? 0ull : ~0ull;
+    unsigned long long load = has_rail ? 0ull : ~0ull;
     bool exact = false;
 
     const unsigned per_rank = (unsigned)(P / N), extra = (unsigned)(P % N);
@@ -403,6 +521,14 @@ static int launch_lpt(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t
                       int64_t *S, hipStream_t st)
 {
     constexpr int IPW = 64 / GW;
+    if (RUNS) {
+        hipLaunchKernelGGL(lpt_prefix_init_kernel, dim3((unsigned)((n_inst + 255) / 256 > 1024 ? 1024 : (n_inst + 255) / 256)), dim3(256),
+                           0, st, S, (int)n_inst, N);
+        const int wide_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(rail) % 4 == 0) ? 1 : 0;
+        hipLaunchKernelGGL(lpt_prefix_kernel, dim3(kPfBlocks), dim3(kPfThreads), 0, st, chunk_off, chunk_w, (int)n_inst, N,
+                           is_pow2(N) ? N - 1 : -1, rail, S, wide_ok);
+        if (int rc = launch_status()) return rc;
+    }
     // packed once it yields at least two wavefronts per SIMD (256 CUs x 4 SIMDs); wide below that
     const bool packed = IPW > 1 && n_inst >= (int64_t)2048 * IPW;
     if (packed) {
