@@ -99,6 +99,121 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float *__restrict
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Packed-key variant for rows of 64..256 logits (LANES = 16, 32 or 64 lanes per row, one float4 each).
+// Every logit becomes one 32-bit key: the upper bits are the order-preserving integer image of the
+// float cut to 32 - IDXBITS bits, the low IDXBITS bits hold (MASK - expert index), so keys are unique,
+// a plain unsigned max picks "largest value, lowest index", and one v_max_u32 per DPP step replaces
+// the (value, index) pair exchange.  Each lane keeps its four keys sorted, so removing a winner is a
+// shift.  Cutting the value is only safe when no two of the k winners, nor the last winner and the
+// best loser, share a cut value; that is checked, and a row group that fails the check (two of its
+// top logits within 2^-17 relative or closer) is redone with full (value, index) comparisons.
+// ---------------------------------------------------------------------------------------------
+template <int LANES>
+__device__ __forceinline__ unsigned group_max_all(unsigned v)
+{
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));   // row_half_mirror
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false));   // row_mirror
+    if constexpr (LANES == 32) v = max(v, xlane<16>(v));
+    if constexpr (LANES == 64) {
+        v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false));   // row_bcast15 into rows 1,3
+        v = max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false));   // row_bcast31 into rows 2,3
+        v = (unsigned)__builtin_amdgcn_readlane((int)v, 63);
+    }
+    return v;
+}
+
+template <unsigned MASK>
+__device__ __forceinline__ unsigned make_key(float f, unsigned idx)
+{
+    unsigned b = (unsigned)__float_as_int(f);
+    b = (b == 0x80000000u) ? 0u : b;                                    // -0 ties with +0
+    const unsigned ord = b ^ ((unsigned)((int)b >> 31) | 0x80000000u);  // monotone float -> unsigned
+    return (ord & ~MASK) | (MASK - idx);
+}
+
+__device__ __forceinline__ void sort2_desc(unsigned &a, unsigned &b)
+{
+    const unsigned hi = max(a, b), lo = min(a, b);
+    a = hi; b = lo;
+}
+
+template <int LANES>
+__global__ __launch_bounds__(256) void route_topk_keys_kernel(const float *__restrict__ logits, int64_t rows, int E, int k,
+                                                              int32_t *__restrict__ topk_idx)
+{
+    constexpr int RPW = 64 / LANES;                 // rows per wavefront
+    constexpr unsigned MASK = 4u * LANES - 1u;      // expert index bits of a key
+    const int lane = threadIdx.x & 63;
+    const int q = lane % LANES;
+    const int64_t first = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LANES;
+    const int64_t stride = (int64_t)gridDim.x * 4 * RPW;
+    const int64_t wave_first = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW;
+    const int e0 = 4 * q;
+    const float4 none = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+
+    float4 x = (first < rows && e0 < E) ? *reinterpret_cast<const float4 *>(logits + first * E + e0) : none;
+    for (int64_t w0 = wave_first; w0 < rows; w0 += stride) {            // wave-uniform trip count
+        const int64_t row = first + (w0 - wave_first);
+        const bool live = row < rows;
+        const bool has = live && e0 < E;
+        const float4 cur = x;
+        {   // next row of this lane group, in flight while the rounds below run
+            const int64_t nrow = row + stride;
+            x = (nrow < rows && e0 < E) ? *reinterpret_cast<const float4 *>(logits + nrow * E + e0) : none;
+        }
+        unsigned k0 = has ? make_key<MASK>(cur.x, e0 + 0) : 0u, k1 = has ? make_key<MASK>(cur.y, e0 + 1) : 0u;
+        unsigned k2 = has ? make_key<MASK>(cur.z, e0 + 2) : 0u, k3 = has ? make_key<MASK>(cur.w, e0 + 3) : 0u;
+        sort2_desc(k0, k1); sort2_desc(k2, k3); sort2_desc(k0, k2); sort2_desc(k1, k3); sort2_desc(k1, k2);
+
+        unsigned mine = 0, prev = 0xFFFFFFFFu;
+        bool bad = false;
+        for (int sel = 0; sel < k; ++sel) {
+            const unsigned K = group_max_all<LANES>(k0);
+            bad = bad || ((prev ^ K) <= MASK);                          // two winners with the same cut value
+            mine = (q == sel) ? K : mine;
+            const bool win = (k0 == K);
+            k0 = win ? k1 : k0; k1 = win ? k2 : k1; k2 = win ? k3 : k2; k3 = win ? 0u : k3;
+            prev = K;
+        }
+        bad = bad || (k0 != 0u && ((k0 ^ prev) <= MASK));               // best loser against the last winner
+        int result = (int)(MASK - (mine & MASK));
+
+        if (__ballot(bad) != 0ull) {                                    // rare: full comparisons for this wavefront's rows
+            float v[4] = {cur.x, cur.y, cur.z, cur.w};
+            if (!has) { v[0] = v[1] = v[2] = v[3] = -INFINITY; }
+            for (int sel = 0; sel < k; ++sel) {
+                float bv = -INFINITY;
+                int bi = INT_MAX;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool better = v[j] > bv;
+                    bv = better ? v[j] : bv;
+                    bi = better ? e0 + j : bi;
+                }
+                group_argmax<LANES>(bv, bi);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = (e0 + j == bi) ? -INFINITY : v[j];
+                result = (q == sel) ? bi : result;
+            }
+        }
+        if (live && q < k) topk_idx[row * k + q] = result;
+    }
+}
+
+template <int LANES>
+static int launch_topk_keys(const float *logits, int64_t rows, int E, int k, int32_t *out, hipStream_t st)
+{
+    constexpr int ROWS_PER_BLOCK = 4 * (64 / LANES);
+    int64_t blocks = (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL((route_topk_keys_kernel<LANES>), dim3((unsigned)blocks), dim3(256), 0, st, logits, rows, E, k, out);
+    return launch_status();
+}
+
 template <int LANES, int VPL>
 static int launch_topk(const float *logits, int64_t rows, int E, int k, int32_t *out, hipStream_t st)
 {
@@ -125,6 +240,10 @@ extern "C" int railsched_route_topk(const float *logits, int64_t rows, int32_t E
     if (rows == 0) return RAILSCHED_OK;
     if (!logits || !topk_idx) return RAILSCHED_ERR_NULL_PTR;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool vec4 = (E % 4 == 0) && (reinterpret_cast<uintptr_t>(logits) % 16 == 0);
+    if (vec4 && E > 32 && E <= 64 && k <= 16) return launch_topk_keys<16>(logits, rows, E, k, topk_idx, st);
+    if (vec4 && E > 64 && E <= 128 && k <= 32) return launch_topk_keys<32>(logits, rows, E, k, topk_idx, st);
+    if (vec4 && E > 128 && E <= 256 && k <= 64) return launch_topk_keys<64>(logits, rows, E, k, topk_idx, st);
     if (E <= 4) return launch_topk<1, 4>(logits, rows, E, k, topk_idx, st);
     if (E <= 8) return launch_topk<1, 8>(logits, rows, E, k, topk_idx, st);
     if (E <= 16) return launch_topk<4, 4>(logits, rows, E, k, topk_idx, st);

@@ -79,6 +79,20 @@ def test_topk_crafted_ties():
     assert np.array_equal(got, np.tile(np.arange(8), (130, 1)))
 
 
+@pytest.mark.parametrize("E,k", [(64, 6), (128, 8), (256, 8), (256, 64), (200, 5), (36, 16)])
+def test_topk_values_that_differ_in_the_last_bits(E, k):
+    # logits packed so closely that only the lowest mantissa bits (or nothing) separate the leaders
+    rng = np.random.default_rng(E + k)
+    rows = 1500
+    base = rng.choice(np.array([1.0, -1.0, 3.5, -0.0, 1e-30, -7e5], dtype=np.float32), size=(rows, 1))
+    ulps = rng.integers(0, 6, size=(rows, E)).astype(np.int32)
+    x = (base.view(np.int32) + ulps).view(np.float32)
+    x[::3] = rng.standard_normal((x[::3].shape[0], E)).astype(np.float32)     # ordinary rows in the same wavefronts
+    assert np.all(np.isfinite(x))
+    got = rs.route_topk(torch.from_numpy(x).to(DEV), k).cpu().numpy()
+    assert np.array_equal(got, oracle.route_topk(x, k))
+
+
 def test_topk_unaligned_rows_and_empty():
     x = torch.randn(1001 * 8 + 1, device=DEV)[1:].view(1001, 8)   # base pointer off 16-byte alignment
     assert np.array_equal(rs.route_topk(x.contiguous(), 2).cpu().numpy(), oracle.route_topk(x.cpu().numpy(), 2))
