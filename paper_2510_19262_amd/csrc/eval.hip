@@ -7,8 +7,8 @@
 // Kernel 1: the chunk range of matrix b is cut into `slices` equal parts; one workgroup streams a
 // part (9 bytes per chunk), accumulates the G = M*N receive bins in LDS and writes them, plus the
 // largest weight it saw, to its own slot of the workspace with plain stores.
-// Kernel 2: one workgroup per matrix adds the slots in slice order and derives the statistics from
-// S (as produced by stage 4) and R.  No global atomics anywhere: every result is a fixed-order sum.
+// Kernel 2: one workgroup per matrix adds the slots and derives the statistics from S (as produced by
+// stage 4) and R.  No global atomics anywhere; all sums are integer, so their order cannot matter.
 #include "common.h"
 
 namespace rs {
@@ -60,43 +60,64 @@ __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
     if (threadIdx.x == 0) slot[a.G] = (int64_t)ev_wmax;
 }
 
-__device__ __forceinline__ int64_t block_reduce(int64_t v, bool take_max, int64_t *sh)
+constexpr int kRedThreads = 1024;
+constexpr int kRedWaves = kRedThreads / 64;
+
+__device__ __forceinline__ int64_t block_reduce(int64_t v, bool take_max, int64_t *sh)   // sh: kRedWaves entries
 {
-    __syncthreads();
-    sh[threadIdx.x] = v;
-    __syncthreads();
-    for (int d = kEvThreads / 2; d >= 1; d >>= 1) {
-        if ((int)threadIdx.x < d) {
-            const int64_t x = sh[threadIdx.x], y = sh[threadIdx.x + d];
-            sh[threadIdx.x] = take_max ? (x > y ? x : y) : (x + y);
-        }
-        __syncthreads();
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const int64_t o = __shfl_xor(v, d);
+        v = take_max ? (o > v ? o : v) : (v + o);
     }
-    return sh[0];
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int64_t r = sh[0];
+    for (int w = 1; w < kRedWaves; ++w) r = take_max ? (sh[w] > r ? sh[w] : r) : (r + sh[w]);
+    return r;
 }
 
-__global__ __launch_bounds__(kEvThreads) void eval_reduce_kernel(EvArgs a)
+// One workgroup of 16 wavefronts per matrix.  Receive bins: a wavefront covers 64 consecutive bins
+// (or, when G < 64, several slices side by side), the 16 wavefronts split the slices, LDS joins them.
+__global__ __launch_bounds__(kRedThreads) void eval_reduce_kernel(EvArgs a)
 {
-    __shared__ int64_t sh[kEvThreads];
+    __shared__ int64_t part[kRedWaves][64];
+    __shared__ int64_t sh[kRedWaves];
     const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t *slots = a.partial + (int64_t)b * a.slices * (a.G + 1);
     int64_t *Rb = a.R + (int64_t)b * a.G;
     const int64_t *Sb = a.S + (int64_t)b * a.G;
 
-    for (int i = threadIdx.x; i < a.G; i += kEvThreads) {
+    int width = 64;                                   // lanes per slice row: 64, or the power of two >= G
+    while (width / 2 >= a.G) width /= 2;
+    const int sub = 64 / width;                       // slices a wavefront reads side by side
+    const int ts = lane / width, li = lane % width;
+    for (int base = 0; base < a.G; base += 64) {
+        const int i = base + li;
         int64_t acc = 0;
-        for (int t = 0; t < a.slices; ++t) acc += slots[(int64_t)t * (a.G + 1) + i];
-        Rb[i] = acc;
+        if (i < a.G)
+            for (int t = wave * sub + ts; t < a.slices; t += kRedWaves * sub) acc += slots[(int64_t)t * (a.G + 1) + i];
+        __syncthreads();                              // previous round's readers are done
+        part[wave][lane] = acc;
+        __syncthreads();
+        if (wave == 0 && lane < width && base + lane < a.G) {
+            int64_t r = 0;
+            for (int w = 0; w < kRedWaves; ++w)
+                for (int u = 0; u < sub; ++u) r += part[w][u * width + lane];
+            Rb[base + lane] = r;
+        }
     }
     int64_t wmax = 0;
-    for (int t = threadIdx.x; t < a.slices; t += kEvThreads) {
+    for (int t = threadIdx.x; t < a.slices; t += kRedThreads) {
         const int64_t x = slots[(int64_t)t * (a.G + 1) + a.G];
         wmax = x > wmax ? x : wmax;
     }
     __syncthreads();   // R[b] written by this workgroup is read back below
 
     int64_t max_s = 0, max_r = 0, lb = 0, total = 0, spread = 0;
-    for (int k = threadIdx.x; k < a.M; k += kEvThreads) {
+    for (int k = threadIdx.x; k < a.M; k += kRedThreads) {
         int64_t out = 0, in = 0, smin = INT64_MAX, smax = 0;
         for (int n = 0; n < a.N; ++n) {
             const int64_t s = Sb[k * a.N + n], r = Rb[k * a.N + n];
@@ -180,6 +201,6 @@ extern "C" int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w,
     }
     hipLaunchKernelGGL(eval_partial_kernel, dim3((unsigned)a.slices, (unsigned)batch), dim3(kEvThreads), lds, st, a);
     if (int rc = launch_status()) return rc;
-    hipLaunchKernelGGL(eval_reduce_kernel, dim3((unsigned)batch), dim3(kEvThreads), 0, st, a);
+    hipLaunchKernelGGL(eval_reduce_kernel, dim3((unsigned)batch), dim3(kRedThreads), 0, st, a);
     return launch_status();
 }

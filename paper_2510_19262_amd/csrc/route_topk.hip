@@ -13,6 +13,21 @@
 
 namespace rs {
 
+// Logits are read once and indices written once: streaming (non-temporal) accesses keep them from
+// displacing anything useful in the caches.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float4 load_stream4(const float *p)
+{
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream2(int32_t *p, int a, int b)
+{
+    i32x2 v; v.x = a; v.y = b;
+    __builtin_nontemporal_store(v, reinterpret_cast<i32x2 *>(p));
+}
+
 template <int LANES, int VPL, bool VEC4>
 __device__ __forceinline__ int slot_index(int q, int j)
 {
@@ -61,7 +76,7 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float *__restrict
             for (int c = 0; c < VPL / 4; ++c) {
                 const int e0 = 4 * (q + LANES * c);
                 float4 x = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-                if (live && e0 < E) x = *reinterpret_cast<const float4 *>(logits + row * E + e0);
+                if (live && e0 < E) x = load_stream4(logits + row * E + e0);
                 v[4 * c + 0] = x.x; v[4 * c + 1] = x.y; v[4 * c + 2] = x.z; v[4 * c + 3] = x.w;
             }
         } else {
@@ -94,7 +109,7 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float *__restrict
             }
         }
         if constexpr (LANES == 1) {
-            if (k == 2 && live) *reinterpret_cast<int2 *>(topk_idx + row * 2) = make_int2(keep0, keep1);
+            if (k == 2 && live) store_stream2(topk_idx + row * 2, keep0, keep1);
         }
     }
 }
@@ -155,7 +170,7 @@ __global__ __launch_bounds__(256) void route_topk_keys_kernel(const float *__res
     const int e0 = 4 * q;
     const float4 none = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
 
-    float4 x = (first < rows && e0 < E) ? *reinterpret_cast<const float4 *>(logits + first * E + e0) : none;
+    float4 x = (first < rows && e0 < E) ? load_stream4(logits + first * E + e0) : none;
     for (int64_t w0 = wave_first; w0 < rows; w0 += stride) {            // wave-uniform trip count
         const int64_t row = first + (w0 - wave_first);
         const bool live = row < rows;
@@ -163,7 +178,7 @@ __global__ __launch_bounds__(256) void route_topk_keys_kernel(const float *__res
         const float4 cur = x;
         {   // next row of this lane group, in flight while the rounds below run
             const int64_t nrow = row + stride;
-            x = (nrow < rows && e0 < E) ? *reinterpret_cast<const float4 *>(logits + nrow * E + e0) : none;
+            x = (nrow < rows && e0 < E) ? load_stream4(logits + nrow * E + e0) : none;
         }
         unsigned k0 = has ? make_key<MASK>(cur.x, e0 + 0) : 0u, k1 = has ? make_key<MASK>(cur.y, e0 + 1) : 0u;
         unsigned k2 = has ? make_key<MASK>(cur.z, e0 + 2) : 0u, k3 = has ? make_key<MASK>(cur.w, e0 + 3) : 0u;
@@ -219,7 +234,7 @@ static int launch_topk(const float *logits, int64_t rows, int E, int k, int32_t 
 {
     constexpr int ROWS_PER_BLOCK = 256 / LANES;
     int64_t blocks = (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
-    const int64_t cap = 256 * 64;   // enough resident waves for the whole chip; longer inputs loop
+    const int64_t cap = 1 << 22;    // one row group per thread measured fastest; only absurd sizes loop
     if (blocks > cap) blocks = cap;
     const bool vec4 = (E % 4 == 0) && (reinterpret_cast<uintptr_t>(logits) % 16 == 0);
     if (vec4)

@@ -26,56 +26,74 @@ struct TmArgs {
     int32_t k, kshift;       // kshift >= 0 when k is a power of two
     int32_t E, R, rmask;     // rmask >= 0 when R is a power of two
     int32_t G, splits;
+    int32_t copies, lanes_per_period;   // LDS histogram replicas and the lane period of the replica pattern
     int32_t table_in_lds;
 };
 
-__device__ __forceinline__ void tm_count(const TmArgs &a, const int32_t *table, unsigned *bins, int64_t slot, int32_t e)
+template <bool FAST>
+__device__ __forceinline__ void tm_count(const TmArgs &a, const int32_t *table, unsigned *bins, int64_t slot, int32_t e)   // bins: this lane's replica
 {
-    const int64_t t = a.kshift >= 0 ? (slot >> a.kshift) : (slot / a.k);
-    const int rho = a.rmask >= 0 ? (int)(t & a.rmask) : (int)(t % a.R);
+    // FAST: k and R are powers of two (shift and mask instead of division)
+    const int64_t t = FAST ? (slot >> a.kshift) : (slot / a.k);
+    const int rho = FAST ? (int)(t & a.rmask) : (int)(t % a.R);
     if ((unsigned)e < (unsigned)a.E) {
         const int32_t d = table[e * a.R + rho];
         if ((unsigned)d < (unsigned)a.G) atomicAdd(&bins[d], 1u);
     }
 }
 
+constexpr int kTmUnroll = 4;        // 16-byte index loads in flight per thread
+
+template <bool FAST>
 __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
 {
     extern __shared__ unsigned tm_lds[];
-    unsigned *bins = tm_lds;                                            // [G]
-    int32_t *lds_table = reinterpret_cast<int32_t *>(tm_lds + a.G);     // [E*R] when it fits
+    // [copies][G] counters.  Lanes whose tokens share a replica index rho - every lanes_per_period-th
+    // lane - would pile onto the bins of the popular experts; they get different copies instead.
+    unsigned *all_bins = tm_lds;
+    unsigned *bins = all_bins + (size_t)((threadIdx.x / a.lanes_per_period) & (a.copies - 1)) * a.G;
+    int32_t *lds_table = reinterpret_cast<int32_t *>(tm_lds + (size_t)a.copies * a.G);   // [E*R] when it fits
     const int64_t pair = blockIdx.x / a.splits;                         // b*G + s
     const int part = blockIdx.x % a.splits;
 
-    for (int i = threadIdx.x; i < a.G; i += kTmThreads) bins[i] = 0;
+    for (int i = threadIdx.x; i < a.G * a.copies; i += kTmThreads) all_bins[i] = 0;
     if (a.table_in_lds)
         for (int i = threadIdx.x; i < a.E * a.R; i += kTmThreads) lds_table[i] = a.expert_gpu[i];
     __syncthreads();
     const int32_t *table = a.table_in_lds ? lds_table : a.expert_gpu;
 
-    // this workgroup's slice [lo, hi) of the pair's slots, cut at multiples of 4 slots
+    // this workgroup's slice of the pair's slots, cut at multiples of 4 slots
     const int64_t quads = (a.slots_per_gpu + 3) / 4;
     const int64_t qlo = quads * part / a.splits, qhi = quads * (part + 1) / a.splits;
     const int32_t *src = a.topk_idx + pair * a.slots_per_gpu;
     const bool aligned = (reinterpret_cast<uintptr_t>(src) % 16) == 0;
-    for (int64_t qd = qlo + threadIdx.x; qd < qhi; qd += kTmThreads) {
-        const int64_t s0 = qd * 4;
-        if (aligned && s0 + 4 <= a.slots_per_gpu) {
-            const int4 e = *reinterpret_cast<const int4 *>(src + s0);
-            tm_count(a, table, bins, s0 + 0, e.x);
-            tm_count(a, table, bins, s0 + 1, e.y);
-            tm_count(a, table, bins, s0 + 2, e.z);
-            tm_count(a, table, bins, s0 + 3, e.w);
-        } else {
-            for (int j = 0; j < 4; ++j)
-                if (s0 + j < a.slots_per_gpu) tm_count(a, table, bins, s0 + j, src[s0 + j]);
+    const int64_t qfull = aligned ? (a.slots_per_gpu / 4 < qhi ? a.slots_per_gpu / 4 : qhi) : qlo;   // whole, aligned quads
+    int64_t qd = qlo + threadIdx.x;
+    for (; qd + (int64_t)(kTmUnroll - 1) * kTmThreads < qfull; qd += (int64_t)kTmUnroll * kTmThreads) {
+        int4 e[kTmUnroll];
+#pragma unroll
+        for (int u = 0; u < kTmUnroll; ++u) e[u] = *reinterpret_cast<const int4 *>(src + (qd + (int64_t)u * kTmThreads) * 4);
+#pragma unroll
+        for (int u = 0; u < kTmUnroll; ++u) {
+            const int64_t s0 = (qd + (int64_t)u * kTmThreads) * 4;
+            tm_count<FAST>(a, table, bins, s0 + 0, e[u].x);
+            tm_count<FAST>(a, table, bins, s0 + 1, e[u].y);
+            tm_count<FAST>(a, table, bins, s0 + 2, e[u].z);
+            tm_count<FAST>(a, table, bins, s0 + 3, e[u].w);
         }
+    }
+    for (; qd < qhi; qd += kTmThreads) {
+        const int64_t s0 = qd * 4;
+        for (int j = 0; j < 4; ++j)
+            if (s0 + j < a.slots_per_gpu) tm_count<FAST>(a, table, bins, s0 + j, src[s0 + j]);
     }
     __syncthreads();
 
     int64_t *dst = a.D1 + pair * a.G;
     for (int i = threadIdx.x; i < a.G; i += kTmThreads) {
-        const int64_t bytes = (int64_t)bins[i] * a.payload;
+        unsigned cnt = 0;
+        for (int c = 0; c < a.copies; ++c) cnt += all_bins[(size_t)c * a.G + i];
+        const int64_t bytes = (int64_t)cnt * a.payload;
         if (a.splits == 1) dst[i] = bytes;                               // sole owner: plain store, zeros included
         else if (bytes) atomicAdd(reinterpret_cast<unsigned long long *>(dst + i), (unsigned long long)bytes);
     }
@@ -103,7 +121,11 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
     a.k = k; a.kshift = is_pow2(k) ? ilog2(k) : -1;
     a.E = E; a.R = R; a.rmask = is_pow2(R) ? R - 1 : -1;
     a.G = (int32_t)G;
-    a.table_in_lds = ((int64_t)E * R <= kTmTableMax && 4 * (G + (int64_t)E * R) <= 64 * 1024) ? 1 : 0;
+    a.copies = 1;
+    while (a.copies < 8 && (int64_t)a.copies * 2 * G <= 8192) a.copies *= 2;
+    // a lane holds 4 consecutive slots, so rho repeats every R*k/4 lanes when that is a whole number
+    a.lanes_per_period = ((int64_t)R * k % 4 == 0 && (int64_t)R * k / 4 <= 64) ? (int32_t)((int64_t)R * k / 4) : 1;
+    a.table_in_lds = ((int64_t)E * R <= kTmTableMax && 4 * (a.copies * G + (int64_t)E * R) <= 64 * 1024) ? 1 : 0;
 
     // enough workgroups to cover the chip, but no slice shorter than 16 Ki slots
     const int64_t pairs = (int64_t)batch * G;
@@ -119,7 +141,10 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
         hipLaunchKernelGGL(fill_zero_i64, dim3((unsigned)((n + 1023) / 1024 > 4096 ? 4096 : (n + 1023) / 1024)), dim3(256), 0, st, D1, n);
         if (int rc = launch_status()) return rc;
     }
-    const size_t lds = sizeof(unsigned) * (size_t)G + (a.table_in_lds ? sizeof(int32_t) * (size_t)E * R : 0);
-    hipLaunchKernelGGL(traffic_matrix_kernel, dim3((unsigned)(pairs * splits)), dim3(kTmThreads), lds, st, a);
+    const size_t lds = sizeof(unsigned) * (size_t)G * a.copies + (a.table_in_lds ? sizeof(int32_t) * (size_t)E * R : 0);
+    if (a.kshift >= 0 && a.rmask >= 0)
+        hipLaunchKernelGGL(traffic_matrix_kernel<true>, dim3((unsigned)(pairs * splits)), dim3(kTmThreads), lds, st, a);
+    else
+        hipLaunchKernelGGL(traffic_matrix_kernel<false>, dim3((unsigned)(pairs * splits)), dim3(kTmThreads), lds, st, a);
     return launch_status();
 }
