@@ -31,7 +31,7 @@ struct CsArgs {
     int64_t C;
     int32_t cshift;      // >= 0 when C is a power of two
     int32_t M, N, G, NF, intra;
-    int32_t n_inst, n_pass;
+    int32_t n_inst;
 };
 
 __device__ __forceinline__ void split_bytes(const CsArgs &a, int64_t B, uint32_t &q, uint32_t &r)
@@ -144,20 +144,28 @@ __global__ __launch_bounds__(64) void cs_tail_kernel(CsArgs a)
     const unsigned long long lt = (1ull << lane) - 1ull;
     const int64_t *rows = a.D1 + ((int64_t)b * a.G + (int64_t)k * a.N) * a.G;
 
-    // tails in canonical order
+    // tails in canonical order; which key bits differ at all between them
     int nt = 0;
+    unsigned any1 = 0u, all1 = 0xFFFFFFFFu;
     for (int f0 = 0; f0 < a.NF; f0 += 64) {
         const int f = f0 + lane;
         uint32_t q = 0, r = 0;
         if (f < a.NF) { split_bytes(a, flow_bytes(a, rows, k, f), q, r); rem[f] = r; }
         const unsigned long long m = __ballot(r != 0);
-        if (r) idx_a[nt + __popcll(m & lt)] = (unsigned short)f;
+        if (r) { idx_a[nt + __popcll(m & lt)] = (unsigned short)f; any1 |= r; all1 &= r; }
         nt += __popcll(m);
     }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) { any1 |= (unsigned)__shfl_xor((int)any1, d); all1 &= (unsigned)__shfl_xor((int)all1, d); }
     __syncthreads();
+    // bits that are equal in every key cannot change the order: sort on the span of differing bits only
+    // (token payloads make tails multiples of some power of two, so the span is usually one digit wide)
+    const unsigned diff = any1 ^ all1;
+    const int lo_bit = diff ? __ffs((int)diff) - 1 : 0;
+    const int n_pass = (nt > 1 && diff) ? (32 - __clz((int)diff) - lo_bit + 7) / 8 : 0;
 
-    for (int pass = 0; pass < a.n_pass; ++pass) {
-        const int shift = 8 * pass;
+    for (int pass = 0; pass < n_pass; ++pass) {
+        const int shift = lo_bit + 8 * pass;
         for (int i = lane; i < 256; i += 64) hist[i] = 0;
         __syncthreads();
         for (int i = lane; i < nt; i += 64) atomicAdd(&hist[255u - ((rem[idx_a[i]] >> shift) & 255u)], 1u);
@@ -228,9 +236,30 @@ __device__ __forceinline__ int last_le64(const int64_t *v, int n, int64_t x)
     return lo;
 }
 
-__global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a)
+// last i in [0,n) with v[i] <= x (v[0] <= x), searched 64 ways per step by the whole wavefront:
+// lane l probes the l-th of 64 evenly spaced entries, the highest lane that still sees v <= x wins.
+__device__ __forceinline__ int wave_last_le(const uint32_t *v, int n, uint32_t x)
 {
-    __shared__ uint32_t stage[kFillStage];
+    const int lane = threadIdx.x & 63;
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int step = (hi - lo + 63) / 64;
+        const int idx = lo + lane * step;
+        const unsigned long long ok = __ballot(idx < hi && v[idx] <= x);   // a prefix of lanes; lane 0 always
+        const int top = 63 - __clzll((long long)ok);
+        lo = lo + top * step;
+        hi = (lo + step < hi) ? lo + step : hi;
+    }
+    return lo;
+}
+
+// Positions [p0,p1) of one instance's full-chunk region.  Positions are grouped by fours at multiples
+// of four of the global record index, so a thread finds the flow of its first position by binary
+// search, walks to the next flows if its four positions cross a boundary, and stores 16 bytes per array.
+__global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec_ok)
+{
+    __shared__ uint32_t st_fs[kFillStage + 1];
+    __shared__ uint32_t st_cs[kFillStage];
     if (a.chunk_off[a.n_inst] > a.capacity) return;
     const int64_t n_tiles = a.tile_off[a.n_inst];
     for (int64_t u = blockIdx.x; u < n_tiles; u += gridDim.x) {
@@ -240,20 +269,56 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a)
         const uint32_t p1 = (n_full - p0 < (uint32_t)kTile) ? n_full : p0 + (uint32_t)kTile;
         const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
         const uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
-        const int f_lo = last_le(fs, a.NF, p0);
-        const int f_hi = last_le(fs, a.NF, p1 - 1);
+        const int f_lo = wave_last_le(fs, a.NF, p0);
+        const int f_hi = wave_last_le(fs, a.NF, p1 - 1);
         const int nf = f_hi - f_lo + 1;
         const bool staged = nf <= kFillStage;
         __syncthreads();                                                 // previous tile is done with the stage
-        if (staged)
-            for (int i = threadIdx.x; i < nf; i += kFillThreads) stage[i] = fs[f_lo + i];
+        if (staged) {
+            for (int i = threadIdx.x; i < nf; i += kFillThreads) {
+                st_fs[i] = fs[f_lo + i];
+                if (a.perm) st_cs[i] = cs[f_lo + i];
+            }
+            if (threadIdx.x == 0) st_fs[nf] = 0xFFFFFFFFu;               // nothing starts behind the last staged flow
+        }
         __syncthreads();
         const int64_t out0 = a.chunk_off[inst];
-        for (uint32_t p = p0 + threadIdx.x; p < p1; p += kFillThreads) {
-            const int f = f_lo + (staged ? last_le(stage, nf, p) : last_le(fs + f_lo, nf, p));
-            a.chunk_w[out0 + p] = (uint32_t)a.C;
-            a.chunk_flow[out0 + p] = (uint32_t)f;
-            if (a.perm) a.perm[out0 + p] = cs[f] + (p - fs[f]);
+        const uint32_t cw = (uint32_t)a.C;
+        if (staged && vec_ok) {
+            const uint32_t head = (uint32_t)((4 - ((out0 + p0) & 3)) & 3);      // scalar positions before the first aligned group
+            const uint32_t pa = (p1 - p0 < head) ? p1 : p0 + head;
+            const uint32_t groups = (p1 - pa) / 4;
+            const uint32_t pb = pa + groups * 4;                                  // scalar positions from here on
+            for (uint32_t g = threadIdx.x; g < groups; g += kFillThreads) {
+                const uint32_t p = pa + 4 * g;
+                int j = last_le(st_fs, nf, p);
+                uint32_t fl[4], pm[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    while (st_fs[j + 1] <= p + e) ++j;
+                    fl[e] = (uint32_t)(f_lo + j);
+                    pm[e] = a.perm ? st_cs[j] + (p + e - st_fs[j]) : 0u;
+                }
+                *reinterpret_cast<uint4 *>(a.chunk_w + out0 + p) = make_uint4(cw, cw, cw, cw);
+                *reinterpret_cast<uint4 *>(a.chunk_flow + out0 + p) = make_uint4(fl[0], fl[1], fl[2], fl[3]);
+                if (a.perm) *reinterpret_cast<uint4 *>(a.perm + out0 + p) = make_uint4(pm[0], pm[1], pm[2], pm[3]);
+            }
+            // the few positions before the first and behind the last aligned group
+            const uint32_t n_edge = (pa - p0) + (p1 - pb);
+            if (threadIdx.x < n_edge) {
+                const uint32_t p = threadIdx.x < pa - p0 ? p0 + threadIdx.x : pb + (threadIdx.x - (pa - p0));
+                const int j = last_le(st_fs, nf, p);
+                a.chunk_w[out0 + p] = cw;
+                a.chunk_flow[out0 + p] = (uint32_t)(f_lo + j);
+                if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
+            }
+        } else {
+            for (uint32_t p = p0 + threadIdx.x; p < p1; p += kFillThreads) {
+                const int f = f_lo + (staged ? last_le(st_fs, nf, p) : last_le(fs + f_lo, nf, p));
+                a.chunk_w[out0 + p] = cw;
+                a.chunk_flow[out0 + p] = (uint32_t)f;
+                if (a.perm) a.perm[out0 + p] = cs[f] + (p - fs[f]);
+            }
         }
     }
 }
@@ -313,7 +378,6 @@ extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const rail
     a.cshift = is_pow2(a.C) ? ilog2(a.C) : -1;
     a.M = (int32_t)M; a.N = (int32_t)N; a.G = (int32_t)G; a.NF = (int32_t)NF; a.intra = h_topo->include_intra_node;
     a.n_inst = (int32_t)n_inst;
-    a.n_pass = a.C <= 1 ? 0 : (ilog2(a.C - 1) + 1 + 7) / 8;             // tail weights are < C
 
     if (n_inst > 0) {
         hipLaunchKernelGGL(cs_count_kernel, dim3((unsigned)n_inst), dim3(64), 0, st, a);
@@ -331,6 +395,8 @@ extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const rail
     }
     hipLaunchKernelGGL(cs_tail_kernel, dim3((unsigned)n_inst), dim3(64), lds, st, a);
     if (int rc = launch_status()) return rc;
-    hipLaunchKernelGGL(cs_fill_kernel, dim3(kFillBlocks), dim3(kFillThreads), 0, st, a);
+    const int vec_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(chunk_flow) % 16 == 0 &&
+                        reinterpret_cast<uintptr_t>(perm) % 16 == 0) ? 1 : 0;
+    hipLaunchKernelGGL(cs_fill_kernel, dim3(kFillBlocks), dim3(kFillThreads), 0, st, a, vec_ok);
     return launch_status();
 }
