@@ -18,6 +18,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes one route_topk launch moves on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
+# 1 GiB copy of known traffic (profiles/c2_whole_path.md): 1034.98 MiB read + 256.00 MiB written.
+ROUTE_TOPK_C2_TRAFFIC_BYTES = int((1034.98 + 256.00) * 1024 * 1024)
 
 
 def parse():
@@ -163,7 +166,8 @@ def main():
         "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
         "completion_time_us_max": float(stats[:, 0].max() / cfg.rail_bw_Bps * 1e6),
         "roofline": {"kernel": "route_topk_kernel", "bound": "hbm", "achieved": k1_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": k1_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": k1_gbps / HBM_PEAK_GBPS,
+                     "traffic": ROUTE_TOPK_C2_TRAFFIC_BYTES if cfg.name == "c2" else None,
                      "algorithmic_bytes_per_launch": k1_bytes, "avg_launch_ms": stage_ms["route_topk"],
                      "slowest_stage": dominant},
     }
