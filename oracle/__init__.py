@@ -176,6 +176,30 @@ def eval_batch(chunk_off, w, flow, rail, batch, M, N):
     return Ssum, R, stats
 
 
+def transpose_batch(D1) -> np.ndarray:
+    """Traffic of the second all-to-all: every matrix transposed."""
+    D1 = _chk(D1, np.int64)
+    out = np.empty_like(D1)
+    lib().oracle_transpose_batch(_p(D1), D1.shape[0], C.c_int64(D1.shape[1]), _p(out))
+    return out
+
+
+POLICIES = {"nic_direct": 0, "flow_hash": 1, "random_spray": 2, "round_robin": 3}
+
+
+def assign_policy(policy, seed, chunk_off, w, flow, batch, M, N):
+    """Rail of every chunk under one of the comparison schemes: (rail, S)."""
+    chunk_off = _chk(chunk_off, np.int64)
+    w = _chk(w, np.uint32)
+    rail = np.empty(w.shape[0], dtype=np.uint8)
+    S = np.empty((batch, M, N), dtype=np.int64)
+    rc = lib().oracle_assign_policy(POLICIES[policy] if isinstance(policy, str) else int(policy), C.c_uint64(seed),
+                                    _p(chunk_off), _p(w), _p(_chk(flow, np.uint32)), batch, M, N, _p(rail), _p(S))
+    if rc:
+        raise ValueError(f"oracle_assign_policy rc={rc}")
+    return rail, S
+
+
 # ---------------------------------------------------------------- derived, exact
 def load_mse(L, normalized: bool = False) -> Fraction:
     """Algorithm 2 step 6: mu = mean load, MSE = (1/N) sum (L_j - mu)^2, as an exact

@@ -379,3 +379,65 @@ void oracle_eval_batch(const int64_t *chunk_off, const uint32_t *w, const uint32
         oracle_eval(chunk_off + (int64_t)b * M, w, flow, rail, M, N,
                     Ssum + (int64_t)b * M * N, R + (int64_t)b * M * N, stats + (int64_t)b * 8);
 }
+
+/* ------------------------------------------------------------------------
+ * Second all-to-all (Algorithm 1 step 4, expert outputs back to the token owners): every byte
+ * sent from GPU s to GPU d in the first all-to-all returns from d to s, so the traffic matrix of
+ * the second one is the transpose, matrix by matrix: D1T[b][d][s] = D1[b][s][d].
+ * ---------------------------------------------------------------------- */
+void oracle_transpose_batch(const int64_t *D1, int batch, int64_t G, int64_t *D1T)
+{
+    for (int b = 0; b < batch; ++b)
+        for (int64_t s = 0; s < G; ++s)
+            for (int64_t d = 0; d < G; ++d)
+                D1T[((int64_t)b * G + d) * G + s] = D1[((int64_t)b * G + s) * G + d];
+}
+
+/* ------------------------------------------------------------------------
+ * Arithmetic stand-ins for the path-selection schemes RailS is compared with (Sections 1, 2.2 and
+ * 6.1): the same chunk records, a different rule for the rail of each chunk.
+ *   0 NIC-direct : no spraying, a GPU's traffic leaves through its own NIC: rail = source local GPU
+ *                  (flow id div G).  The "direct rails without multipath transport" case.
+ *   1 flow hash  : static per-flow hashing as in ECMP: every chunk of a GPU-to-GPU flow takes the rail
+ *                  hash(instance, flow id) mod N.
+ *   2 random spray: every chunk independently, hash(position of the chunk in the record arrays) mod N.
+ *   3 round robin : chunk i of the instance (in stored order) takes rail i mod N, blind to sizes.
+ * hash(x) = splitmix64 finaliser of (seed + 0x9E3779B97F4A7C15 * (x + 1)).
+ * S receives the per-rail send loads of the instance.
+ * ---------------------------------------------------------------------- */
+static uint64_t o_mix64(uint64_t z)
+{
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+static uint64_t o_hash(uint64_t seed, uint64_t x)
+{
+    return o_mix64(seed + 0x9E3779B97F4A7C15ull * (x + 1));
+}
+
+int oracle_assign_policy(int policy, uint64_t seed, const int64_t *chunk_off, const uint32_t *w,
+                         const uint32_t *flow, int batch, int M, int N, uint8_t *rail, int64_t *S)
+{
+    const int64_t G = (int64_t)M * N, NF = (int64_t)N * G;
+    const int64_t inst_n = (int64_t)batch * M;
+    if (policy < 0 || policy > 3) return -1;
+    for (int64_t inst = 0; inst < inst_n; ++inst) {
+        int64_t *L = S + inst * N;
+        for (int n = 0; n < N; ++n) L[n] = 0;
+        for (int64_t i = chunk_off[inst]; i < chunk_off[inst + 1]; ++i) {
+            int r;
+            switch (policy) {
+                case 0: r = (int)(flow[i] / G); break;
+                case 1: r = (int)(o_hash(seed, (uint64_t)inst * (uint64_t)NF + flow[i]) % (uint64_t)N); break;
+                case 2: r = (int)(o_hash(seed, (uint64_t)i) % (uint64_t)N); break;
+                default: r = (int)((i - chunk_off[inst]) % N); break;
+            }
+            rail[i] = (uint8_t)r;
+            L[r] += (int64_t)w[i];
+        }
+    }
+    return 0;
+}

@@ -393,3 +393,85 @@ def test_flows_workload_shape():
     assert 0.55 < (D1 == 0).mean() < 0.85
     again = W.gen_flow_matrices(cfg, first=1, count=1)
     assert np.array_equal(again[0], D1[1])                                  # counter based: order independent
+
+
+# ------------------------------------------------------------------ second all-to-all, comparison schemes
+def test_transpose_is_numpy_transpose():
+    rng = np.random.default_rng(21)
+    D1 = rng.integers(0, 1 << 40, size=(3, 12, 12)).astype(np.int64)
+    T = oracle.transpose_batch(D1)
+    assert np.array_equal(T, np.transpose(D1, (0, 2, 1)))
+    assert np.array_equal(oracle.transpose_batch(T), D1)
+    assert not np.array_equal(T, D1)
+
+
+def _records(seed=22, M=4, N=4, C=4096, B=2):
+    rng = np.random.default_rng(seed)
+    D1 = _rand_matrix(rng, M * N, C)[None].repeat(B, axis=0)
+    D1[1] = _rand_matrix(rng, M * N, C)
+    off, w, flow, perm = oracle.chunk_sort_batch(D1, M, N, C)
+    return D1, off, w, flow, M, N, B
+
+
+def test_policy_nic_direct_is_the_row_sum():
+    # without spraying a GPU's inter-node bytes all leave on its own NIC: S[b][k][n] = row sum of GPU (k,n)
+    D1, off, w, flow, M, N, B = _records()
+    rail, S = oracle.assign_policy("nic_direct", 0, off, w, flow, B, M, N)
+    G = M * N
+    inter = D1.copy()
+    for k in range(M):
+        inter[:, k * N:(k + 1) * N, k * N:(k + 1) * N] = 0
+    assert np.array_equal(S.reshape(B, G), inter.sum(axis=2))
+    assert np.array_equal(rail, (flow // G).astype(np.uint8))
+
+
+def test_policy_round_robin_closed_form():
+    D1, off, w, flow, M, N, B = _records()
+    rail, S = oracle.assign_policy("round_robin", 0, off, w, flow, B, M, N)
+    for inst in range(B * M):
+        o, e = off[inst], off[inst + 1]
+        assert np.array_equal(rail[o:e], np.arange(e - o) % N)
+        assert np.array_equal(S.reshape(-1, N)[inst], np.bincount(rail[o:e], weights=w[o:e].astype(np.float64), minlength=N).astype(np.int64))
+
+
+def _hash_np(seed, x):
+    with np.errstate(over="ignore"):
+        return W.mix64_np(np.uint64(seed) + np.uint64(0x9E3779B97F4A7C15) * (x.astype(np.uint64) + np.uint64(1)))
+
+
+def test_policy_hashes_match_a_numpy_restatement():
+    D1, off, w, flow, M, N, B = _records()
+    G, NF = M * N, N * M * N
+    seed = 12345
+    rail, S = oracle.assign_policy("flow_hash", seed, off, w, flow, B, M, N)
+    inst = np.repeat(np.arange(B * M), np.diff(off))
+    assert np.array_equal(rail, (_hash_np(seed, inst.astype(np.uint64) * np.uint64(NF) + flow) % np.uint64(N)).astype(np.uint8))
+    for i in range(B * M):                                   # a flow never changes rail
+        o, e = off[i], off[i + 1]
+        for f in np.unique(flow[o:e]):
+            assert np.unique(rail[o:e][flow[o:e] == f]).size == 1
+    rail2, S2 = oracle.assign_policy("random_spray", seed, off, w, flow, B, M, N)
+    assert np.array_equal(rail2, (_hash_np(seed, np.arange(w.size)) % np.uint64(N)).astype(np.uint8))
+    counts = np.bincount(rail2, minlength=N)
+    assert counts.min() > 0.8 * w.size / N and counts.max() < 1.2 * w.size / N      # roughly uniform
+    for r, s_ in ((rail, S), (rail2, S2)):
+        for i in range(B * M):
+            o, e = off[i], off[i + 1]
+            assert np.array_equal(s_.reshape(-1, N)[i], np.bincount(r[o:e], weights=w[o:e].astype(np.float64), minlength=N).astype(np.int64))
+    assert not np.array_equal(oracle.assign_policy("random_spray", seed + 1, off, w, flow, B, M, N)[0], rail2)
+
+
+def test_lpt_is_never_worse_than_the_lower_bound_and_beats_blind_schemes_on_skew():
+    # one hot GPU per node: NIC-direct piles everything on one rail, LPT spreads it
+    M, N, C = 4, 4, 4096
+    G = M * N
+    D1 = np.full((1, G, G), C, dtype=np.int64)
+    for k in range(M):
+        D1[0, k * N, :] = 40 * C + 123
+    off, w, flow, perm = oracle.chunk_sort_batch(D1, M, N, C)
+    rail_l, S_l = oracle.lpt_batch(off, w, 1, M, N)
+    st_l = oracle.eval_batch(off, w, flow, rail_l, 1, M, N)[2][0]
+    rail_d, S_d = oracle.assign_policy("nic_direct", 0, off, w, flow, 1, M, N)
+    st_d = oracle.eval_batch(off, w, flow, rail_d, 1, M, N)[2][0]
+    assert st_l[3] == st_d[3] and st_l[0] >= st_l[3]
+    assert st_d[0] > 2 * st_l[0]
