@@ -131,6 +131,29 @@ def main():
     stats = plan.stats.cpu().numpy()
     ratio = stats[:, 0] / np.maximum(stats[:, 3], 1)
 
+    # ---- supplementary: the comparison schemes on the same chunk records, and the second all-to-all (transposed traffic)
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn(); e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+    R2, stats2 = torch.empty_like(plan.R), torch.empty_like(plan.stats)
+    schemes = {"lpt": {"makespan_over_lb_max": float(ratio.max()), "makespan_over_lb_mean": float(ratio.mean())}}
+    for pol in ("nic_direct", "flow_hash", "random_spray", "round_robin"):
+        ms = timed(lambda: rs.assign_policy(pol, 1, plan.chunk_off, plan.chunk_w, plan.chunk_flow, B, topo, out=(rail2, S2)))
+        rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, rail2, S2, B, topo, out=(R2, stats2), ws=plan.ws_eval)
+        st2 = stats2.cpu().numpy()
+        r2 = st2[:, 0] / np.maximum(st2[:, 3], 1)
+        schemes[pol] = {"makespan_over_lb_max": float(r2.max()), "makespan_over_lb_mean": float(r2.mean()), "assign_ms": ms}
+    D1T = torch.empty_like(plan.D1)
+    tr_ms = timed(lambda: rs.transpose_matrix(plan.D1, topo, out=D1T))
+    n_comb = int(rs.chunk_count(D1T, topo, plan.ws_sort)[-1].item())
+    plan_c = rs.Plan(topo, B, n_comb, dev, want_perm=True)
+    comb_ms = timed(lambda: plan_c.schedule(D1T))
+    st_c = plan_c.stats.cpu().numpy()
+    r_c = st_c[:, 0] / np.maximum(st_c[:, 3], 1)
+    combine = {"transpose_ms": tr_ms, "schedule_ms": comb_ms, "chunks": n_comb, "makespan_over_lb_max": float(r_c.max())}
+    rs.chunk_sort(plan.D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
+
     # ---- roofline of the dominant kernel (route_topk streams the logits once)
     k1_bytes = rows * (4 * cfg.E + 4 * cfg.k)
     k2_bytes = rows * 4 * cfg.k + 8 * B * G * G
@@ -164,6 +187,8 @@ def main():
                          "note": f"{B * cfg.M} instances cannot fill 1024 SIMDs: the serial chain's latency, not issue rate, bounds this workload"},
         "lpt_spray_chunkwise_ms": chunkwise_ms,
         "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
+        "schemes": schemes,
+        "second_all_to_all": combine,
         "completion_time_us_max": float(stats[:, 0].max() / cfg.rail_bw_Bps * 1e6),
         "roofline": {"kernel": "route_topk_kernel", "bound": "hbm", "achieved": k1_gbps, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": k1_gbps / HBM_PEAK_GBPS,

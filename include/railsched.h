@@ -155,6 +155,32 @@ int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w, const uint
                    const uint8_t *rail, const int64_t *S, int32_t batch, const railsched_topo_t *h_topo,
                    int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Second all-to-all of an MoE layer (Algorithm 1 step 4: expert outputs return to the token owners):
+ * its traffic is the first one's reversed, D1T[b][d][s] = D1[b][s][d]; stages 3-5 then run on D1T.
+ *   D1, D1T [batch][G][G] int64, distinct buffers.
+ * Errors: NULL_PTR, INVALID_ARG (also D1 == D1T), UNSUPPORTED.
+ * ------------------------------------------------------------------------------------------- */
+int railsched_transpose_matrix(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *D1T,
+                               void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * The path-selection schemes RailS is compared with (Sections 1, 2.2 and 6.1), reduced to arithmetic
+ * on the chunk records of stage 3: same inputs and outputs as stage 4, another rule for the rail.
+ *   RAILSCHED_POLICY_NIC_DIRECT   a GPU's traffic leaves through its own NIC: rail = flow id div G
+ *   RAILSCHED_POLICY_FLOW_HASH    static per-flow hashing (ECMP-like): hash(instance*N*G + flow id) mod N
+ *   RAILSCHED_POLICY_RANDOM_SPRAY per chunk: hash(index of the chunk in the record arrays) mod N
+ *   RAILSCHED_POLICY_ROUND_ROBIN  chunk i of the instance, in stored order, takes rail i mod N
+ * hash(x) = splitmix64 finaliser of (seed + 0x9E3779B97F4A7C15 * (x + 1)), 64-bit wrapping.
+ *   rail [chunks] uint8 (out), S [batch][M][N] int64 send loads (out); feed both to railsched_eval.
+ * Errors: NULL_PTR, INVALID_ARG (unknown policy), UNSUPPORTED.
+ * ------------------------------------------------------------------------------------------- */
+enum { RAILSCHED_POLICY_NIC_DIRECT = 0, RAILSCHED_POLICY_FLOW_HASH = 1, RAILSCHED_POLICY_RANDOM_SPRAY = 2,
+       RAILSCHED_POLICY_ROUND_ROBIN = 3 };
+int railsched_assign_policy(int32_t policy, uint64_t seed, const int64_t *chunk_off, const uint32_t *chunk_w,
+                            const uint32_t *chunk_flow, int32_t batch, const railsched_topo_t *h_topo,
+                            uint8_t *rail, int64_t *S, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

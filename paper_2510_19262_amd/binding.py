@@ -21,7 +21,7 @@ _lib = None
 EXPORTS = (
     "railsched_version", "railsched_strerror", "railsched_route_topk", "railsched_traffic_matrix",
     "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray", "railsched_lpt_spray_chunkwise",
-    "railsched_eval_workspace_bytes", "railsched_eval",
+    "railsched_eval_workspace_bytes", "railsched_eval", "railsched_transpose_matrix", "railsched_assign_policy",
 )
 
 
@@ -81,6 +81,10 @@ def load():
     lib.railsched_eval_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_eval_workspace_bytes.restype = SZ
     lib.railsched_eval.argtypes = [P, P, P, P, P, I32, TP, P, P, P, SZ, P]
+    lib.railsched_transpose_matrix.argtypes = [P, I32, TP, P, P]
+    lib.railsched_assign_policy.argtypes = [I32, C.c_uint64, P, P, P, I32, TP, P, P, P]
+    lib.railsched_transpose_matrix.restype = C.c_int
+    lib.railsched_assign_policy.restype = C.c_int
     for fn in ("railsched_route_topk", "railsched_traffic_matrix", "railsched_chunk_sort", "railsched_lpt_spray",
                "railsched_lpt_spray_chunkwise", "railsched_eval"):
         getattr(lib, fn).restype = C.c_int
@@ -245,6 +249,33 @@ def eval(chunk_off, chunk_w, chunk_flow, rail, S, batch: int, topo: Topo, out=No
 
 
 evaluate = eval
+
+POLICIES = {"nic_direct": 0, "flow_hash": 1, "random_spray": 2, "round_robin": 3}
+
+
+def transpose_matrix(D1: torch.Tensor, topo: Topo, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Traffic of the second all-to-all: D1T[b][d][s] = D1[b][s][d]."""
+    _dev(D1, torch.int64, "D1")
+    if out is None:
+        out = torch.empty_like(D1)
+    t = topo.c()
+    _check(load().railsched_transpose_matrix(_ptr(D1), D1.shape[0], C.byref(t), _ptr(out), _stream()),
+           "railsched_transpose_matrix")
+    return out
+
+
+def assign_policy(policy, seed: int, chunk_off, chunk_w, chunk_flow, batch: int, topo: Topo, out=None):
+    """Rails under a comparison scheme ("nic_direct", "flow_hash", "random_spray", "round_robin") -> (rail, S)."""
+    if out is None:
+        rail = torch.empty(max(chunk_w.numel(), 1), dtype=torch.uint8, device=chunk_off.device)
+        S = torch.empty((batch, topo.nodes, topo.rails), dtype=torch.int64, device=chunk_off.device)
+    else:
+        rail, S = out
+    t = topo.c()
+    pol = POLICIES[policy] if isinstance(policy, str) else int(policy)
+    _check(load().railsched_assign_policy(pol, seed, _ptr(chunk_off), _ptr(chunk_w), _ptr(chunk_flow), batch, C.byref(t),
+                                          _ptr(rail), _ptr(S), _stream()), "railsched_assign_policy")
+    return rail, S
 
 
 # ---------------------------------------------------------------------------------- whole path

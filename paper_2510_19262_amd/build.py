@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librailsched.so")
-SOURCES = ["api.hip", "route_topk.hip", "traffic_matrix.hip", "chunk_sort.hip", "lpt_spray.hip", "eval.hip"]
+SOURCES = ["api.hip", "route_topk.hip", "traffic_matrix.hip", "chunk_sort.hip", "lpt_spray.hip", "eval.hip", "extras.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -37,7 +37,7 @@ def build(force: bool = True) -> str:
     if not force and not stale():
         return LIB
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     return LIB

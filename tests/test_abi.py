@@ -101,6 +101,22 @@ def test_chunk_sort_and_eval_validation():
     assert lib.railsched_lpt_spray(None, FAKE, 1, C.byref(t), FAKE, FAKE, None) == -2
 
 
+def test_extras_validation():
+    lib = rs.load()
+    t = _topo()
+    tr = lib.railsched_transpose_matrix
+    assert tr(FAKE, -1, C.byref(t), P(0x2000), None) == -1
+    assert tr(None, 1, C.byref(t), P(0x2000), None) == -2
+    assert tr(FAKE, 1, C.byref(t), FAKE, None) == -1           # in place is refused
+    assert tr(FAKE, 0, C.byref(t), FAKE, None) == 0
+    ap = lib.railsched_assign_policy
+    assert ap(4, 0, FAKE, FAKE, FAKE, 1, C.byref(t), FAKE, FAKE, None) == -1
+    assert ap(-1, 0, FAKE, FAKE, FAKE, 1, C.byref(t), FAKE, FAKE, None) == -1
+    assert ap(0, 0, None, FAKE, FAKE, 1, C.byref(t), FAKE, FAKE, None) == -2
+    assert ap(0, 0, FAKE, FAKE, FAKE, 1, C.byref(t), FAKE, None, None) == -2
+    assert ap(0, 0, FAKE, FAKE, FAKE, 0, C.byref(t), FAKE, FAKE, None) == 0
+
+
 def test_binding_rejects_host_tensors():
     import torch
     with pytest.raises(ValueError):
