@@ -200,6 +200,15 @@ def assign_policy(policy, seed, chunk_off, w, flow, batch, M, N):
     return rail, S
 
 
+def port_round_robin(chunk_off, rail, batch, M, N, P) -> np.ndarray:
+    """Port (queue pair) of every chunk: round robin per rail inside each instance."""
+    chunk_off = _chk(chunk_off, np.int64)
+    rail = _chk(rail, np.uint8)
+    port = np.empty(rail.shape[0], dtype=np.uint8)
+    lib().oracle_port_round_robin(_p(chunk_off), _p(rail), batch, M, N, P, _p(port))
+    return port
+
+
 # ---------------------------------------------------------------- derived, exact
 def load_mse(L, normalized: bool = False) -> Fraction:
     """Algorithm 2 step 6: mu = mean load, MSE = (1/N) sum (L_j - mu)^2, as an exact

@@ -441,3 +441,23 @@ int oracle_assign_policy(int policy, uint64_t seed, const int64_t *chunk_off, co
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Spraying execution, port choice (Algorithm 2 step 4: "select port p from NIC j* by round-robin"):
+ * every rail of a node hands its chunks to its P ports (queue pairs) in turn, so the chunk that is
+ * the c-th one put on its rail within its instance (c = 0, 1, ...) takes port c mod P.
+ * ---------------------------------------------------------------------- */
+void oracle_port_round_robin(const int64_t *chunk_off, const uint8_t *rail, int batch, int M, int N, int P,
+                             uint8_t *port)
+{
+    const int64_t inst_n = (int64_t)batch * M;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t inst = 0; inst < inst_n; ++inst) {
+        int64_t seen[ORACLE_MAX_N];
+        for (int n = 0; n < N; ++n) seen[n] = 0;
+        for (int64_t i = chunk_off[inst]; i < chunk_off[inst + 1]; ++i) {
+            port[i] = (uint8_t)(seen[rail[i]] % P);
+            seen[rail[i]] += 1;
+        }
+    }
+}

@@ -475,3 +475,19 @@ def test_lpt_is_never_worse_than_the_lower_bound_and_beats_blind_schemes_on_skew
     st_d = oracle.eval_batch(off, w, flow, rail_d, 1, M, N)[2][0]
     assert st_l[3] == st_d[3] and st_l[0] >= st_l[3]
     assert st_d[0] > 2 * st_l[0]
+
+
+def test_port_round_robin():
+    import pandas as pd
+    D1, off, w, flow, M, N, B = _records(seed=31)
+    rail, _ = oracle.lpt_batch(off, w, B, M, N)
+    inst = np.repeat(np.arange(B * M), np.diff(off))
+    for P in (1, 3, 4, 256):
+        port = oracle.port_round_robin(off, rail, B, M, N, P)
+        ref = pd.DataFrame({"i": inst, "r": rail}).groupby(["i", "r"]).cumcount().to_numpy() % P   # library cumulative count
+        assert np.array_equal(port, ref.astype(np.uint8))
+    assert not oracle.port_round_robin(off, rail, B, M, N, 1).any()
+    # equal weights: rail = i mod N, so the port is (i div N) mod P
+    off2 = np.array([0, 50], dtype=np.int64)
+    rail2, _ = oracle.lpt(np.full(50, 7, dtype=np.uint32), 4)
+    assert np.array_equal(oracle.port_round_robin(off2, rail2, 1, 1, 4, 3), (np.arange(50) // 4) % 3)
