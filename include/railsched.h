@@ -181,6 +181,22 @@ int railsched_assign_policy(int32_t policy, uint64_t seed, const int64_t *chunk_
                             const uint32_t *chunk_flow, int32_t batch, const railsched_topo_t *h_topo,
                             uint8_t *rail, int64_t *S, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Spraying execution, port choice (Algorithm 2 step 4: "select port p from NIC j* by round-robin"):
+ * each rail of a node hands its chunks to its `ports` queue pairs in turn; the chunk that is the c-th
+ * one (c = 0, 1, ...) put on its rail inside its instance, in stored order, takes port c mod ports.
+ *   rail [chunks] uint8 (in), port [chunks] uint8 (out), 1 <= ports <= 256.
+ * `capacity` is an upper bound of the chunk count (the size of the record arrays) and sizes the
+ * workspace: railsched_port_round_robin_workspace_bytes(batch, topo, capacity) bytes, 256-byte aligned.
+ * If chunk_off[batch*M] exceeds capacity, the ports of the chunks beyond what the workspace covers are
+ * not written.
+ * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (ports > 256), WORKSPACE.
+ * ------------------------------------------------------------------------------------------- */
+size_t railsched_port_round_robin_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo, int64_t capacity);
+int railsched_port_round_robin(const int64_t *chunk_off, const uint8_t *rail, int32_t batch,
+                               const railsched_topo_t *h_topo, int32_t ports, int64_t capacity, uint8_t *port,
+                               void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

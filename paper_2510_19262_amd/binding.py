@@ -22,6 +22,7 @@ EXPORTS = (
     "railsched_version", "railsched_strerror", "railsched_route_topk", "railsched_traffic_matrix",
     "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray", "railsched_lpt_spray_chunkwise",
     "railsched_eval_workspace_bytes", "railsched_eval", "railsched_transpose_matrix", "railsched_assign_policy",
+    "railsched_port_round_robin_workspace_bytes", "railsched_port_round_robin",
 )
 
 
@@ -83,6 +84,10 @@ def load():
     lib.railsched_eval.argtypes = [P, P, P, P, P, I32, TP, P, P, P, SZ, P]
     lib.railsched_transpose_matrix.argtypes = [P, I32, TP, P, P]
     lib.railsched_assign_policy.argtypes = [I32, C.c_uint64, P, P, P, I32, TP, P, P, P]
+    lib.railsched_port_round_robin_workspace_bytes.argtypes = [I32, TP, I64]
+    lib.railsched_port_round_robin_workspace_bytes.restype = SZ
+    lib.railsched_port_round_robin.argtypes = [P, P, I32, TP, I32, I64, P, P, SZ, P]
+    lib.railsched_port_round_robin.restype = C.c_int
     lib.railsched_transpose_matrix.restype = C.c_int
     lib.railsched_assign_policy.restype = C.c_int
     for fn in ("railsched_route_topk", "railsched_traffic_matrix", "railsched_chunk_sort", "railsched_lpt_spray",
@@ -313,3 +318,16 @@ class Plan:
         eval(self.chunk_off, self.chunk_w, self.chunk_flow, self.rail, self.S, self.batch, self.topo,
              out=(self.R, self.stats), ws=self.ws_eval)
         return self.stats
+
+
+def port_round_robin(chunk_off, rail, batch: int, topo: Topo, ports: int, capacity: Optional[int] = None, out=None, ws=None):
+    """Port (queue pair) of every chunk: round robin per rail inside each instance -> uint8 [chunks]."""
+    if capacity is None:
+        capacity = rail.numel()
+    t = topo.c()
+    if ws is None:
+        ws = _ws(load().railsched_port_round_robin_workspace_bytes(batch, C.byref(t), capacity), chunk_off.device)
+    port = torch.empty(max(capacity, 1), dtype=torch.uint8, device=chunk_off.device) if out is None else out
+    _check(load().railsched_port_round_robin(_ptr(chunk_off), _ptr(rail), batch, C.byref(t), ports, capacity, _ptr(port),
+                                             _ptr(ws), ws.numel(), _stream()), "railsched_port_round_robin")
+    return port

@@ -150,6 +150,136 @@ __global__ __launch_bounds__(kPolThreads) void policy_kernel(PolArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------------ port round robin
+// Algorithm 2 step 4.  port[i] = (how many earlier chunks of the same instance went to the same rail) mod P.
+// Instances are cut into tiles of kPortTile chunks; (1) tile offsets per instance, (2) per-tile per-rail
+// counts, (3) per instance an exclusive scan of the counts over its tiles, (4) per tile the running
+// counts: one wavefront walks the tile 64 chunks at a time, lanes with the same rail find each other by
+// ballot matching, rank = running count + number of lower lanes with that rail.
+constexpr int kPortTile = 4096;
+constexpr int kPortWaves = 4;
+constexpr int kPortBlocks = 2048;
+
+struct PortArgs {
+    const int64_t *chunk_off;
+    const uint8_t *rail;
+    uint8_t *port;
+    int64_t *tile_off;          // [n_inst + 1]
+    uint32_t *cnt;              // [tiles][N]: counts, then exclusive prefixes inside the instance
+    int64_t max_tiles;
+    int32_t n_inst, N, P, pmask, rail_bits;
+};
+
+__global__ __launch_bounds__(1024) void port_tiles_kernel(PortArgs a)
+{
+    __shared__ int64_t sh[1024];
+    __shared__ int64_t carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < a.n_inst; base += 1024) {
+        const int i = base + tid;
+        const int64_t v = i < a.n_inst ? (a.chunk_off[i + 1] - a.chunk_off[i] + kPortTile - 1) / kPortTile : 0;
+        sh[tid] = v;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {
+            const int64_t x = tid >= d ? sh[tid - d] : 0;
+            __syncthreads();
+            sh[tid] += x;
+            __syncthreads();
+        }
+        if (i < a.n_inst) a.tile_off[i] = carry + sh[tid] - v;
+        __syncthreads();
+        if (tid == 1023) carry += sh[1023];
+        __syncthreads();
+    }
+    if (tid == 0) a.tile_off[a.n_inst] = carry;
+}
+
+__device__ __forceinline__ int wave_last_le_i64(const int64_t *v, int n, int64_t x)   // 64-way search by the whole wavefront
+{
+    const int lane = threadIdx.x & 63;
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int step = (hi - lo + 63) / 64;
+        const int idx = lo + lane * step;
+        const unsigned long long ok = __ballot(idx < hi && v[idx] <= x);
+        const int top = 63 - __clzll((long long)ok);
+        lo = lo + top * step;
+        hi = (lo + step < hi) ? lo + step : hi;
+    }
+    return lo;
+}
+
+template <bool ASSIGN>
+__global__ __launch_bounds__(64 * kPortWaves) void port_tile_kernel(PortArgs a)
+{
+    __shared__ unsigned run[kPortWaves][kMaxRails];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    int64_t n_tiles = a.tile_off[a.n_inst];
+    if (n_tiles > a.max_tiles) n_tiles = a.max_tiles;               // workspace sized for fewer chunks: never write past it
+    unsigned *mine = run[wv];
+    for (int64_t u = (int64_t)blockIdx.x * kPortWaves + wv; u < n_tiles; u += (int64_t)gridDim.x * kPortWaves) {
+        const int inst = wave_last_le_i64(a.tile_off, a.n_inst, u);
+        const int64_t beg = a.chunk_off[inst] + (u - a.tile_off[inst]) * kPortTile;
+        const int64_t end = (beg + kPortTile < a.chunk_off[inst + 1]) ? beg + kPortTile : a.chunk_off[inst + 1];
+        uint32_t *c = a.cnt + u * a.N;
+        if (lane < a.N) mine[lane] = ASSIGN ? c[lane] : 0u;
+        __builtin_amdgcn_wave_barrier();
+        for (int64_t i0 = beg; i0 < end; i0 += 64) {
+            const int64_t i = i0 + lane;
+            const bool act = i < end;
+            const unsigned r = act ? a.rail[i] : 0u;
+            const bool ok = act && r < (unsigned)a.N;
+            if (!ASSIGN) {
+                if (ok) atomicAdd(&mine[r], 1u);
+            } else {
+                unsigned long long peers = __ballot(ok);
+                for (int bit = 0; bit < a.rail_bits; ++bit) {
+                    const bool one = (r >> bit) & 1u;
+                    const unsigned long long bm = __ballot(ok && one);
+                    peers &= one ? bm : ~bm;
+                }
+                const unsigned base = ok ? mine[r] : 0u;
+                const unsigned rank = base + (unsigned)__popcll(peers & lt);
+                if (act) a.port[i] = ok ? (uint8_t)(a.pmask >= 0 ? (rank & (unsigned)a.pmask) : (rank % (unsigned)a.P)) : (uint8_t)0;
+                __builtin_amdgcn_wave_barrier();
+                if (ok && (peers >> lane) == 1ull) mine[r] = base + (unsigned)__popcll(peers);   // highest lane of the peer set
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+        if (!ASSIGN) {
+            __builtin_amdgcn_wave_barrier();
+            if (lane < a.N) c[lane] = mine[lane];
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// exclusive scan of the per-tile counts over the tiles of one instance; lane = rail
+__global__ __launch_bounds__(64) void port_scan_kernel(PortArgs a)
+{
+    const int inst = blockIdx.x, lane = threadIdx.x;
+    int64_t t0 = a.tile_off[inst], t1 = a.tile_off[inst + 1];
+    if (t1 > a.max_tiles) t1 = a.max_tiles;
+    if (lane >= a.N) return;
+    unsigned running = 0;
+    for (int64_t t = t0; t < t1; ++t) {
+        const unsigned v = a.cnt[t * a.N + lane];
+        a.cnt[t * a.N + lane] = running;
+        running += v;
+    }
+}
+
+static void port_ws_layout(int64_t n_inst, int64_t max_tiles, int N, size_t off[3])
+{
+    size_t o = 0;
+    off[0] = o; o += align_up(sizeof(int64_t) * (size_t)(n_inst + 1), 256);
+    off[1] = o; o += align_up(sizeof(uint32_t) * (size_t)max_tiles * (size_t)N, 256);
+    off[2] = o;
+}
+
 }  // namespace rs
 
 extern "C" int railsched_transpose_matrix(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *D1T,
@@ -192,5 +322,49 @@ extern "C" int railsched_assign_policy(int32_t policy, uint64_t seed, const int6
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256 > 1024 ? 1024 : (n + 255) / 256)), dim3(256), 0, st, S, n);
     if (int rc = launch_status()) return rc;
     hipLaunchKernelGGL(policy_kernel, dim3(kPolBlocks), dim3(kPolThreads), 0, st, a);
+    return launch_status();
+}
+
+extern "C" size_t railsched_port_round_robin_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo, int64_t capacity)
+{
+    using namespace rs;
+    if (check_topo(h_topo) != RAILSCHED_OK || batch < 0 || capacity < 0) return 0;
+    const int64_t n_inst = (int64_t)batch * h_topo->nodes;
+    size_t off[3];
+    port_ws_layout(n_inst, capacity / kPortTile + n_inst + 1, h_topo->rails, off);
+    return off[2];
+}
+
+extern "C" int railsched_port_round_robin(const int64_t *chunk_off, const uint8_t *rail, int32_t batch,
+                                          const railsched_topo_t *h_topo, int32_t ports, int64_t capacity, uint8_t *port,
+                                          void *ws, size_t ws_bytes, void *stream)
+{
+    using namespace rs;
+    if (int rc = check_topo(h_topo)) return rc;
+    if (batch < 0 || capacity < 0 || ports < 1) return RAILSCHED_ERR_INVALID_ARG;
+    if (ports > 256) return RAILSCHED_ERR_UNSUPPORTED;
+    const int64_t n_inst = (int64_t)batch * h_topo->nodes;
+    if (n_inst > 0x7FFFFFFFll / 64) return RAILSCHED_ERR_UNSUPPORTED;
+    if (n_inst == 0) return RAILSCHED_OK;
+    if (!chunk_off || (capacity > 0 && (!rail || !port))) return RAILSCHED_ERR_NULL_PTR;
+    const int64_t max_tiles = capacity / kPortTile + n_inst + 1;
+    size_t off[3];
+    port_ws_layout(n_inst, max_tiles, h_topo->rails, off);
+    if (!ws || ws_bytes < off[2] || reinterpret_cast<uintptr_t>(ws) % 256) return RAILSCHED_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PortArgs a;
+    a.chunk_off = chunk_off; a.rail = rail; a.port = port;
+    a.tile_off = reinterpret_cast<int64_t *>(static_cast<char *>(ws) + off[0]);
+    a.cnt = reinterpret_cast<uint32_t *>(static_cast<char *>(ws) + off[1]);
+    a.max_tiles = max_tiles;
+    a.n_inst = (int32_t)n_inst; a.N = h_topo->rails; a.P = ports; a.pmask = is_pow2(ports) ? ports - 1 : -1;
+    a.rail_bits = a.N > 1 ? ilog2(a.N - 1) + 1 : 0;
+    hipLaunchKernelGGL(port_tiles_kernel, dim3(1), dim3(1024), 0, st, a);
+    if (int rc = launch_status()) return rc;
+    hipLaunchKernelGGL(port_tile_kernel<false>, dim3(kPortBlocks), dim3(64 * kPortWaves), 0, st, a);
+    if (int rc = launch_status()) return rc;
+    hipLaunchKernelGGL(port_scan_kernel, dim3((unsigned)n_inst), dim3(64), 0, st, a);
+    if (int rc = launch_status()) return rc;
+    hipLaunchKernelGGL(port_tile_kernel<true>, dim3(kPortBlocks), dim3(64 * kPortWaves), 0, st, a);
     return launch_status();
 }

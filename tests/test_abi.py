@@ -117,6 +117,21 @@ def test_extras_validation():
     assert ap(0, 0, FAKE, FAKE, FAKE, 0, C.byref(t), FAKE, FAKE, None) == 0
 
 
+def test_port_round_robin_validation():
+    lib = rs.load()
+    t = _topo()
+    need = lib.railsched_port_round_robin_workspace_bytes(2, C.byref(t), 100000)
+    assert need > 0 and need % 256 == 0
+    f = lib.railsched_port_round_robin
+    assert f(FAKE, FAKE, 2, C.byref(t), 0, 10, FAKE, FAKE, need, None) == -1
+    assert f(FAKE, FAKE, 2, C.byref(t), 257, 10, FAKE, FAKE, need, None) == -3
+    assert f(FAKE, FAKE, 2, C.byref(t), 4, -1, FAKE, FAKE, need, None) == -1
+    assert f(None, FAKE, 2, C.byref(t), 4, 10, FAKE, FAKE, need, None) == -2
+    assert f(FAKE, FAKE, 2, C.byref(t), 4, 10, None, FAKE, need, None) == -2
+    assert f(FAKE, FAKE, 2, C.byref(t), 4, 100000, FAKE, FAKE, need - 1, None) == -5
+    assert f(FAKE, FAKE, 0, C.byref(t), 4, 10, FAKE, FAKE, need, None) == 0
+
+
 def test_binding_rejects_host_tensors():
     import torch
     with pytest.raises(ValueError):

@@ -118,3 +118,33 @@ def test_lpt_beats_the_comparison_schemes_on_config2_shape():
         st = st.cpu().numpy()
         assert np.all(st[:, 3] == st_lpt[:, 3])                      # same lower bound: same traffic
         assert np.all(st[:, 1] >= st_lpt[:, 1])                      # LPT's worst send NIC is never worse
+
+
+@pytest.mark.parametrize("M,N,C,B,P", [(4, 4, 4096, 2, 4), (3, 5, 1000, 3, 3), (8, 8, 65536, 2, 256), (2, 33, 256, 1, 1), (2, 64, 128, 1, 7)])
+def test_port_round_robin_matches_oracle(M, N, C, B, P):
+    rng = np.random.default_rng(M + N + P)
+    D1 = _rand_stack(rng, B, M * N, C)
+    topo = rs.Topo(M, N, C)
+    off, w, flow = _records_dev(D1, topo)
+    rail, S = rs.lpt_spray(off, w, B, topo)
+    n = int(off[-1].item())
+    port = rs.port_round_robin(off, rail, B, topo, P, capacity=n)
+    assert np.array_equal(port.cpu().numpy()[:n], oracle.port_round_robin(off.cpu().numpy(), rail.cpu().numpy()[:n], B, M, N, P))
+
+
+def test_port_round_robin_long_instances():
+    # several tiles per instance, empty instances in between, rails from random spraying
+    M, N, C, B, P = 6, 8, 4096, 2, 16
+    rng = np.random.default_rng(77)
+    G = M * N
+    D1 = (np.exp(rng.normal(np.log(60 * C), 1.5, size=(B, G, G))) // 512 * 512).astype(np.int64)
+    D1[rng.random((B, G, G)) < 0.5] = 0
+    D1[1, 8:16, :] = 0
+    topo = rs.Topo(M, N, C)
+    off, w, flow = _records_dev(D1, topo)
+    n = int(off[-1].item())
+    assert np.diff(off.cpu().numpy()).max() > 5 * 4096
+    for policy in ("random_spray", "nic_direct"):
+        rail, S = rs.assign_policy(policy, 3, off, w, flow, B, topo)
+        port = rs.port_round_robin(off, rail, B, topo, P, capacity=n + 1000)
+        assert np.array_equal(port.cpu().numpy()[:n], oracle.port_round_robin(off.cpu().numpy(), rail.cpu().numpy()[:n], B, M, N, P))
