@@ -148,3 +148,48 @@ def test_port_round_robin_long_instances():
         rail, S = rs.assign_policy(policy, 3, off, w, flow, B, topo)
         port = rs.port_round_robin(off, rail, B, topo, P, capacity=n + 1000)
         assert np.array_equal(port.cpu().numpy()[:n], oracle.port_round_robin(off.cpu().numpy(), rail.cpu().numpy()[:n], B, M, N, P))
+
+
+def test_whole_path_replays_from_a_hip_graph():
+    # the library enqueues kernels only (no allocation, no host synchronisation, no memset nodes), so a caller
+    # may capture a pass into a HIP graph; every replay must equal the eager result for the inputs of that moment
+    cfg = W.get_config("c2").scaled(batch=2, tokens_per_gpu=4096)
+    topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes)
+    B = cfg.batch
+    eg = torch.from_numpy(W.expert_gpu_table(cfg)).to(DEV)
+    variants = [torch.cat([W.gen_logits(cfg, b + 10 * v, device=DEV) for b in range(B)]) for v in range(3)]
+    logits = variants[0].clone()
+    rows = logits.shape[0]
+    cap = 0
+    for v in variants:                                              # capacity that fits every variant
+        D = rs.traffic_matrix(rs.route_topk(v, cfg.k), B, cfg.tokens_per_gpu, eg, cfg.payload_bytes, topo)
+        cap = max(cap, int(rs.chunk_count(D, topo)[-1].item()))
+    plan = rs.Plan(topo, B, cap, DEV, rows=rows, k=cfg.k)
+
+    def step():
+        plan.route(logits, cfg.tokens_per_gpu, eg, cfg.payload_bytes)
+        plan.schedule()
+
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rnd in range(5):
+        logits.copy_(variants[rnd % 3])
+        step()                                                      # eager reference for these inputs
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (plan.topk_idx, plan.D1, plan.chunk_off, plan.S, plan.R, plan.stats)]
+        n = int(plan.chunk_off[-1].item())
+        want_rec = [t[:n].clone() for t in (plan.chunk_w, plan.chunk_flow, plan.perm, plan.rail)]
+        for t in (plan.topk_idx, plan.D1, plan.chunk_off, plan.S, plan.R, plan.stats, plan.chunk_w, plan.chunk_flow, plan.perm, plan.rail):
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (plan.topk_idx, plan.D1, plan.chunk_off, plan.S, plan.R, plan.stats)
+        assert all(torch.equal(a, b) for a, b in zip(want, got)), f"replay {rnd}"
+        got_rec = (plan.chunk_w, plan.chunk_flow, plan.perm, plan.rail)
+        assert all(torch.equal(a, b[:n]) for a, b in zip(want_rec, got_rec)), f"replay {rnd} records"
