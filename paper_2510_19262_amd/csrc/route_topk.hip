@@ -156,62 +156,130 @@ __device__ __forceinline__ void sort2_desc(unsigned &a, unsigned &b)
     a = hi; b = lo;
 }
 
-template <int LANES>
+// descending sort of 8 unique keys: Batcher's odd-even merge network, 19 exchanges
+__device__ __forceinline__ void sort8_desc(unsigned (&a)[8])
+{
+    sort2_desc(a[0], a[1]); sort2_desc(a[2], a[3]); sort2_desc(a[4], a[5]); sort2_desc(a[6], a[7]);
+    sort2_desc(a[0], a[2]); sort2_desc(a[1], a[3]); sort2_desc(a[4], a[6]); sort2_desc(a[5], a[7]);
+    sort2_desc(a[1], a[2]); sort2_desc(a[5], a[6]);
+    sort2_desc(a[0], a[4]); sort2_desc(a[1], a[5]); sort2_desc(a[2], a[6]); sort2_desc(a[3], a[7]);
+    sort2_desc(a[2], a[4]); sort2_desc(a[3], a[5]);
+    sort2_desc(a[1], a[2]); sort2_desc(a[3], a[4]); sort2_desc(a[5], a[6]);
+}
+
+// the 8 largest of two descending 8-lists, descending: max(a[i], b[7-i]) is that set as a bitonic sequence
+__device__ __forceinline__ void top8_of_two(unsigned (&a)[8], const unsigned (&b)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = max(a[i], b[7 - i]);
+    sort2_desc(a[0], a[4]); sort2_desc(a[1], a[5]); sort2_desc(a[2], a[6]); sort2_desc(a[3], a[7]);
+    sort2_desc(a[0], a[2]); sort2_desc(a[1], a[3]); sort2_desc(a[4], a[6]); sort2_desc(a[5], a[7]);
+    sort2_desc(a[0], a[1]); sort2_desc(a[2], a[3]); sort2_desc(a[4], a[5]); sort2_desc(a[6], a[7]);
+}
+
+// drop the head of a descending list held in registers (the winner's lane only)
+template <int L, int J>
+__device__ __forceinline__ void list_pop(unsigned (&lst)[8], bool win)
+{
+    if constexpr (J + 1 < L) {
+        lst[J] = win ? lst[J + 1] : lst[J];
+        list_pop<L, J + 1>(lst, win);
+    } else {
+        lst[J] = win ? 0u : lst[J];
+    }
+}
+
+// LANES lanes per row, VPL logits per lane (VPL/4 float4 loads, interleaved over the lanes), a sorted list of
+// L = min(VPL, 8) keys per lane: with k <= 8 a lane can never contribute more than its 8 best.  Fewer lanes per
+// row mean fewer cross-lane steps per round and more rows per wavefront; the rounds dominate the instruction count.
+template <int LANES, int VPL>
 __global__ __launch_bounds__(256) void route_topk_keys_kernel(const float *__restrict__ logits, int64_t rows, int E, int k,
                                                               int32_t *__restrict__ topk_idx)
 {
     constexpr int RPW = 64 / LANES;                 // rows per wavefront
-    constexpr unsigned MASK = 4u * LANES - 1u;      // expert index bits of a key
+    constexpr int NV = VPL / 4;                     // float4 loads per lane and row
+    constexpr int L = VPL < 8 ? VPL : 8;            // sorted keys kept per lane
+    constexpr unsigned MASK = (unsigned)(LANES * VPL) - 1u;   // expert index bits of a key
+    static_assert(VPL == 4 || VPL == 8 || VPL == 16, "4, 8 or 16 logits per lane");
     const int lane = threadIdx.x & 63;
     const int q = lane % LANES;
-    const int64_t first = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LANES;
-    const int64_t stride = (int64_t)gridDim.x * 4 * RPW;
     const int64_t wave_first = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW;
-    const int e0 = 4 * q;
+    const int64_t first = wave_first + lane / LANES;
+    const int64_t stride = (int64_t)gridDim.x * 4 * RPW;
     const float4 none = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
 
-    float4 x = (first < rows && e0 < E) ? load_stream4(logits + first * E + e0) : none;
+    float4 x[NV];
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+        const int e0 = 4 * (q + LANES * c);
+        x[c] = (first < rows && e0 < E) ? load_stream4(logits + first * E + e0) : none;
+    }
     for (int64_t w0 = wave_first; w0 < rows; w0 += stride) {            // wave-uniform trip count
         const int64_t row = first + (w0 - wave_first);
         const bool live = row < rows;
-        const bool has = live && e0 < E;
-        const float4 cur = x;
-        {   // next row of this lane group, in flight while the rounds below run
-            const int64_t nrow = row + stride;
-            x = (nrow < rows && e0 < E) ? load_stream4(logits + nrow * E + e0) : none;
+        float4 cur[NV];
+        unsigned key[VPL];
+#pragma unroll
+        for (int c = 0; c < NV; ++c) {
+            const int e0 = 4 * (q + LANES * c);
+            const bool has = live && e0 < E;
+            cur[c] = x[c];
+            const int64_t nrow = row + stride;                          // next row, in flight while the rounds below run
+            x[c] = (nrow < rows && e0 < E) ? load_stream4(logits + nrow * E + e0) : none;
+            key[4 * c + 0] = has ? make_key<MASK>(cur[c].x, e0 + 0) : 0u; key[4 * c + 1] = has ? make_key<MASK>(cur[c].y, e0 + 1) : 0u;
+            key[4 * c + 2] = has ? make_key<MASK>(cur[c].z, e0 + 2) : 0u; key[4 * c + 3] = has ? make_key<MASK>(cur[c].w, e0 + 3) : 0u;
         }
-        unsigned k0 = has ? make_key<MASK>(cur.x, e0 + 0) : 0u, k1 = has ? make_key<MASK>(cur.y, e0 + 1) : 0u;
-        unsigned k2 = has ? make_key<MASK>(cur.z, e0 + 2) : 0u, k3 = has ? make_key<MASK>(cur.w, e0 + 3) : 0u;
-        sort2_desc(k0, k1); sort2_desc(k2, k3); sort2_desc(k0, k2); sort2_desc(k1, k3); sort2_desc(k1, k2);
+        unsigned lst[8];                                                // lst[0..L) descending, the lane's candidates
+        if constexpr (VPL == 4) {
+            sort2_desc(key[0], key[1]); sort2_desc(key[2], key[3]); sort2_desc(key[0], key[2]); sort2_desc(key[1], key[3]);
+            sort2_desc(key[1], key[2]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) lst[j] = key[j];
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) lst[j] = key[j];
+            sort8_desc(lst);
+            if constexpr (VPL == 16) {
+                unsigned hi[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) hi[j] = key[8 + j];
+                sort8_desc(hi);
+                top8_of_two(lst, hi);
+            }
+        }
 
-        unsigned mine = 0, prev = 0xFFFFFFFFu;
-        bool bad = false;
+        unsigned mine = 0, prev = 0;
         for (int sel = 0; sel < k; ++sel) {
-            const unsigned K = group_max_all<LANES>(k0);
-            bad = bad || ((prev ^ K) <= MASK);                          // two winners with the same cut value
+            const unsigned K = group_max_all<LANES>(lst[0]);
             mine = (q == sel) ? K : mine;
-            const bool win = (k0 == K);
-            k0 = win ? k1 : k0; k1 = win ? k2 : k1; k2 = win ? k3 : k2; k3 = win ? 0u : k3;
+            const bool win = (lst[0] == K);
+            list_pop<L, 0>(lst, win);
             prev = K;
         }
-        bad = bad || (k0 != 0u && ((k0 ^ prev) <= MASK));               // best loser against the last winner
+        // the value cut is safe iff neighbouring winners, and the last winner and the best loser, differ above the index bits
+        const unsigned up = (unsigned)__shfl_up((int)mine, 1);          // previous winner (lane q-1 of the same row)
+        bool bad = (q >= 1 && q < k && ((mine ^ up) <= MASK)) || (lst[0] != 0u && ((lst[0] ^ prev) <= MASK));
         int result = (int)(MASK - (mine & MASK));
-
         if (__ballot(bad) != 0ull) {                                    // rare: full comparisons for this wavefront's rows
-            float v[4] = {cur.x, cur.y, cur.z, cur.w};
-            if (!has) { v[0] = v[1] = v[2] = v[3] = -INFINITY; }
+            float v[VPL];
+#pragma unroll
+            for (int c = 0; c < NV; ++c) {
+                const bool has = live && 4 * (q + LANES * c) < E;
+                v[4 * c + 0] = has ? cur[c].x : -INFINITY; v[4 * c + 1] = has ? cur[c].y : -INFINITY;
+                v[4 * c + 2] = has ? cur[c].z : -INFINITY; v[4 * c + 3] = has ? cur[c].w : -INFINITY;
+            }
             for (int sel = 0; sel < k; ++sel) {
                 float bv = -INFINITY;
                 int bi = INT_MAX;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < VPL; ++j) {
                     const bool better = v[j] > bv;
                     bv = better ? v[j] : bv;
-                    bi = better ? e0 + j : bi;
+                    bi = better ? slot_index<LANES, VPL, true>(q, j) : bi;
                 }
                 group_argmax<LANES>(bv, bi);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) v[j] = (e0 + j == bi) ? -INFINITY : v[j];
+                for (int j = 0; j < VPL; ++j) v[j] = (slot_index<LANES, VPL, true>(q, j) == bi) ? -INFINITY : v[j];
                 result = (q == sel) ? bi : result;
             }
         }
@@ -219,13 +287,13 @@ __global__ __launch_bounds__(256) void route_topk_keys_kernel(const float *__res
     }
 }
 
-template <int LANES>
+template <int LANES, int VPL>
 static int launch_topk_keys(const float *logits, int64_t rows, int E, int k, int32_t *out, hipStream_t st)
 {
     constexpr int ROWS_PER_BLOCK = 4 * (64 / LANES);
     int64_t blocks = (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
     if (blocks > 256 * 32) blocks = 256 * 32;
-    hipLaunchKernelGGL((route_topk_keys_kernel<LANES>), dim3((unsigned)blocks), dim3(256), 0, st, logits, rows, E, k, out);
+    hipLaunchKernelGGL((route_topk_keys_kernel<LANES, VPL>), dim3((unsigned)blocks), dim3(256), 0, st, logits, rows, E, k, out);
     return launch_status();
 }
 
@@ -256,9 +324,11 @@ extern "C" int railsched_route_topk(const float *logits, int64_t rows, int32_t E
     if (!logits || !topk_idx) return RAILSCHED_ERR_NULL_PTR;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool vec4 = (E % 4 == 0) && (reinterpret_cast<uintptr_t>(logits) % 16 == 0);
-    if (vec4 && E > 32 && E <= 64 && k <= 16) return launch_topk_keys<16>(logits, rows, E, k, topk_idx, st);
-    if (vec4 && E > 64 && E <= 128 && k <= 32) return launch_topk_keys<32>(logits, rows, E, k, topk_idx, st);
-    if (vec4 && E > 128 && E <= 256 && k <= 64) return launch_topk_keys<64>(logits, rows, E, k, topk_idx, st);
+    if (vec4 && E > 32 && E <= 64 && k <= 16) return launch_topk_keys<16, 4>(logits, rows, E, k, topk_idx, st);
+    if (vec4 && E > 64 && E <= 128 && k <= 8) return launch_topk_keys<16, 8>(logits, rows, E, k, topk_idx, st);
+    if (vec4 && E > 64 && E <= 128 && k <= 32) return launch_topk_keys<32, 4>(logits, rows, E, k, topk_idx, st);
+    if (vec4 && E > 128 && E <= 256 && k <= 8) return launch_topk_keys<32, 8>(logits, rows, E, k, topk_idx, st);
+    if (vec4 && E > 128 && E <= 256 && k <= 64) return launch_topk_keys<64, 4>(logits, rows, E, k, topk_idx, st);
     if (E <= 4) return launch_topk<1, 4>(logits, rows, E, k, topk_idx, st);
     if (E <= 8) return launch_topk<1, 8>(logits, rows, E, k, topk_idx, st);
     if (E <= 16) return launch_topk<4, 4>(logits, rows, E, k, topk_idx, st);
