@@ -24,6 +24,7 @@ struct EvArgs {
     int64_t *partial;        // [batch][slices][G + 1]
     int32_t M, N, G, slices;
     int32_t nshift, gmask;   // >= 0 when N / G are powers of two
+    int32_t wide_ok;         // record arrays aligned for 16-byte (weights, flows) and 4-byte (rails) loads
 };
 
 __device__ __forceinline__ int dst_node(const EvArgs &a, uint32_t flow)
@@ -46,12 +47,27 @@ __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
     const int64_t n = hi_m - lo_m;
     const int64_t lo = lo_m + n * t / a.slices, hi = lo_m + n * (t + 1) / a.slices;
     unsigned wmax = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kEvThreads) {
-        const uint32_t w = a.chunk_w[i];
-        const int f = dst_node(a, a.chunk_flow[i]);
-        const int r = a.rail[i];
-        if (f < a.M && r < a.N) atomicAdd(&ev_bins[f * a.N + r], (unsigned long long)w);   // LDS, workgroup-private
+    auto one = [&](uint32_t w, uint32_t flow, unsigned r) {
+        const int f = dst_node(a, flow);
+        if (f < a.M && r < (unsigned)a.N) atomicAdd(&ev_bins[f * a.N + r], (unsigned long long)w);   // LDS, workgroup-private
         wmax = w > wmax ? w : wmax;
+    };
+    // whole groups of four records at multiples of four: 16-byte loads of weight and flow, 4 bytes of rails
+    const int64_t alo = a.wide_ok ? ((lo + 3) & ~int64_t(3)) : hi, ahi = a.wide_ok ? (hi & ~int64_t(3)) : hi;
+    if (alo < ahi) {
+        for (int64_t i = alo + (int64_t)threadIdx.x * 4; i < ahi; i += (int64_t)kEvThreads * 4) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(a.chunk_w + i);
+            const uint4 fl = *reinterpret_cast<const uint4 *>(a.chunk_flow + i);
+            const uint32_t rr = *reinterpret_cast<const uint32_t *>(a.rail + i);
+            one(w.x, fl.x, rr & 255u); one(w.y, fl.y, (rr >> 8) & 255u); one(w.z, fl.z, (rr >> 16) & 255u); one(w.w, fl.w, rr >> 24);
+        }
+        const int64_t n_edge = (alo - lo) + (hi - ahi);                 // at most 6 records outside the aligned span
+        if ((int64_t)threadIdx.x < n_edge) {
+            const int64_t i = (int64_t)threadIdx.x < alo - lo ? lo + threadIdx.x : ahi + (threadIdx.x - (alo - lo));
+            one(a.chunk_w[i], a.chunk_flow[i], a.rail[i]);
+        }
+    } else {
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kEvThreads) one(a.chunk_w[i], a.chunk_flow[i], a.rail[i]);
     }
     atomicMax(&ev_wmax, wmax);
     __syncthreads();
@@ -192,6 +208,8 @@ extern "C" int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w,
     a.M = h_topo->nodes; a.N = h_topo->rails; a.G = a.M * a.N; a.slices = eval_slices(batch);
     a.nshift = is_pow2(a.N) ? ilog2(a.N) : -1;
     a.gmask = is_pow2(a.G) ? a.G - 1 : -1;
+    a.wide_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(chunk_flow) % 16 == 0 &&
+                 reinterpret_cast<uintptr_t>(rail) % 4 == 0) ? 1 : 0;
 
     const size_t lds = sizeof(unsigned long long) * (size_t)a.G;
     if (lds > 48 * 1024) {
