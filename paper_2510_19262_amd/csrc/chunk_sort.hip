@@ -236,23 +236,6 @@ __device__ __forceinline__ int last_le64(const int64_t *v, int n, int64_t x)
     return lo;
 }
 
-// last i in [0,n) with v[i] <= x (v[0] <= x), searched 64 ways per step by the whole wavefront:
-// lane l probes the l-th of 64 evenly spaced entries, the highest lane that still sees v <= x wins.
-__device__ __forceinline__ int wave_last_le(const uint32_t *v, int n, uint32_t x)
-{
-    const int lane = threadIdx.x & 63;
-    int lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int step = (hi - lo + 63) / 64;
-        const int idx = lo + lane * step;
-        const unsigned long long ok = __ballot(idx < hi && v[idx] <= x);   // a prefix of lanes; lane 0 always
-        const int top = 63 - __clzll((long long)ok);
-        lo = lo + top * step;
-        hi = (lo + step < hi) ? lo + step : hi;
-    }
-    return lo;
-}
-
 // Positions [p0,p1) of one instance's full-chunk region.  Positions are grouped by fours at multiples
 // of four of the global record index, so a thread finds the flow of its first position by binary
 // search, walks to the next flows if its four positions cross a boundary, and stores 16 bytes per array.
@@ -263,14 +246,14 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec
     if (a.chunk_off[a.n_inst] > a.capacity) return;
     const int64_t n_tiles = a.tile_off[a.n_inst];
     for (int64_t u = blockIdx.x; u < n_tiles; u += gridDim.x) {
-        const int inst = last_le64(a.tile_off, a.n_inst, u);             // tile_off[inst] <= u < tile_off[inst+1]
+        const int inst = wave_last_le<int64_t>(a.tile_off, a.n_inst, u);  // tile_off[inst] <= u < tile_off[inst+1]
         const uint32_t n_full = (uint32_t)a.cnt_full[inst];
         const uint32_t p0 = (uint32_t)(u - a.tile_off[inst]) * (uint32_t)kTile;
         const uint32_t p1 = (n_full - p0 < (uint32_t)kTile) ? n_full : p0 + (uint32_t)kTile;
         const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
         const uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
-        const int f_lo = wave_last_le(fs, a.NF, p0);
-        const int f_hi = wave_last_le(fs, a.NF, p1 - 1);
+        const int f_lo = wave_last_le<uint32_t>(fs, a.NF, p0);
+        const int f_hi = wave_last_le<uint32_t>(fs, a.NF, p1 - 1);
         const int nf = f_hi - f_lo + 1;
         const bool staged = nf <= kFillStage;
         __syncthreads();                                                 // previous tile is done with the stage

@@ -61,6 +61,25 @@ template <int OFF>
 __device__ __forceinline__ unsigned xlane(unsigned v) { return (unsigned)xlane<OFF>((int)v); }
 template <int OFF>
 __device__ __forceinline__ float xlane(float v) { return __int_as_float(xlane<OFF>(__float_as_int(v))); }
+
+// last i in [0,n) with v[i] <= x (v[0] <= x), searched 64 ways per step by the whole wavefront: lane l probes
+// the l-th of 64 evenly spaced entries and the highest lane that still sees v <= x wins.  Two or three dependent
+// memory round trips instead of log2(n); every lane of the wavefront must call it with the same arguments.
+template <typename T>
+__device__ __forceinline__ int wave_last_le(const T *v, int n, T x)
+{
+    const int lane = threadIdx.x & 63;
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int step = (hi - lo + 63) / 64;
+        const int idx = lo + lane * step;
+        const unsigned long long ok = __ballot(idx < hi && v[idx] <= x);   // a prefix of lanes; lane 0 always
+        const int top = 63 - __clzll((long long)ok);
+        lo = lo + top * step;
+        hi = (lo + step < hi) ? lo + step : hi;
+    }
+    return lo;
+}
 #endif
 
 }  // namespace rs

@@ -95,8 +95,8 @@ __global__ __launch_bounds__(kPolThreads) void policy_kernel(PolArgs a)
     const int64_t total = a.chunk_off[a.n_inst];
     for (int64_t t0 = (int64_t)blockIdx.x * kPolTile; t0 < total; t0 += (int64_t)gridDim.x * kPolTile) {
         const int64_t t1 = t0 + kPolTile < total ? t0 + kPolTile : total;
-        const int inst_lo = pol_last_le(a.chunk_off, a.n_inst, t0);
-        const int inst_hi = pol_last_le(a.chunk_off, a.n_inst, t1 - 1);
+        const int inst_lo = wave_last_le<int64_t>(a.chunk_off, a.n_inst, t0);
+        const int inst_hi = wave_last_le<int64_t>(a.chunk_off, a.n_inst, t1 - 1);
         const int cnt = inst_hi - inst_lo + 1;
         const bool staged = cnt <= kPolStage;
         __syncthreads();                                   // previous tile is done with the LDS
@@ -196,21 +196,6 @@ __global__ __launch_bounds__(1024) void port_tiles_kernel(PortArgs a)
     if (tid == 0) a.tile_off[a.n_inst] = carry;
 }
 
-__device__ __forceinline__ int wave_last_le_i64(const int64_t *v, int n, int64_t x)   // 64-way search by the whole wavefront
-{
-    const int lane = threadIdx.x & 63;
-    int lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int step = (hi - lo + 63) / 64;
-        const int idx = lo + lane * step;
-        const unsigned long long ok = __ballot(idx < hi && v[idx] <= x);
-        const int top = 63 - __clzll((long long)ok);
-        lo = lo + top * step;
-        hi = (lo + step < hi) ? lo + step : hi;
-    }
-    return lo;
-}
-
 template <bool ASSIGN>
 __global__ __launch_bounds__(64 * kPortWaves) void port_tile_kernel(PortArgs a)
 {
@@ -221,7 +206,7 @@ __global__ __launch_bounds__(64 * kPortWaves) void port_tile_kernel(PortArgs a)
     if (n_tiles > a.max_tiles) n_tiles = a.max_tiles;               // workspace sized for fewer chunks: never write past it
     unsigned *mine = run[wv];
     for (int64_t u = (int64_t)blockIdx.x * kPortWaves + wv; u < n_tiles; u += (int64_t)gridDim.x * kPortWaves) {
-        const int inst = wave_last_le_i64(a.tile_off, a.n_inst, u);
+        const int inst = wave_last_le<int64_t>(a.tile_off, a.n_inst, u);
         const int64_t beg = a.chunk_off[inst] + (u - a.tile_off[inst]) * kPortTile;
         const int64_t end = (beg + kPortTile < a.chunk_off[inst + 1]) ? beg + kPortTile : a.chunk_off[inst + 1];
         uint32_t *c = a.cnt + u * a.N;

@@ -164,8 +164,9 @@ __device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsi
 }
 
 // ================================================================================ leading run
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kPfThreads = 256;
-constexpr int kPfTile = 8192;       // chunk positions per workgroup iteration (8 x uint4 per thread)
+constexpr int kPfTile = 16384;      // chunk positions per workgroup iteration (16 x uint4 per thread)
 constexpr int kPfStage = 1024;      // instance boundaries staged in LDS per tile
 constexpr int kPfBlocks = 2048;
 
@@ -199,8 +200,8 @@ __global__ __launch_bounds__(kPfThreads) void lpt_prefix_kernel(const int64_t *_
     const int64_t total = chunk_off[n_inst];
     for (int64_t t0 = (int64_t)blockIdx.x * kPfTile; t0 < total; t0 += (int64_t)gridDim.x * kPfTile) {
         const int64_t t1 = t0 + kPfTile < total ? t0 + kPfTile : total;
-        const int inst_lo = last_le_i64(chunk_off, n_inst, t0);
-        const int inst_hi = last_le_i64(chunk_off, n_inst, t1 - 1);
+        const int inst_lo = wave_last_le<int64_t>(chunk_off, n_inst, t0);
+        const int inst_hi = wave_last_le<int64_t>(chunk_off, n_inst, t1 - 1);
         const int cnt = inst_hi - inst_lo + 1;
         const bool staged = cnt <= kPfStage;
         __syncthreads();                                   // previous tile is done with the stage
@@ -212,6 +213,45 @@ __global__ __launch_bounds__(kPfThreads) void lpt_prefix_kernel(const int64_t *_
             }
         }
         __syncthreads();
+        if (cnt == 1 && wide_ok && ((t1 - t0) & 3) == 0) {
+            // The tile lies inside one instance (the common case when instances are long): four 16-byte loads
+            // in flight per thread, one comparison per weight, and one atomic per wavefront at most.
+            const int64_t b = s_off[0];
+            const uint32_t w0 = s_w0[0];
+            int64_t miss = INT64_MAX;
+            constexpr int U = 4;
+            for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPfThreads * 4 * U) {
+                u32x4 v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t pu = p + (int64_t)u * kPfThreads * 4;
+                    v[u] = pu < t1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(chunk_w + pu)) : u32x4{w0, w0, w0, w0};
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t pu = p + (int64_t)u * kPfThreads * 4;
+                    if (pu >= t1) break;
+                    const int64_t i = pu - b;
+                    uint32_t r0 = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
+                    uint32_t packed = r0;
+#pragma unroll
+                    for (int e = 1; e < 4; ++e) {
+                        r0 = (r0 + 1 == (uint32_t)N) ? 0u : r0 + 1;
+                        packed |= r0 << (8 * e);
+                    }
+                    const int first = v[u].x != w0 ? 0 : v[u].y != w0 ? 1 : v[u].z != w0 ? 2 : v[u].w != w0 ? 3 : -1;
+                    if (first >= 0 && i + first < miss) miss = i + first;
+                    __builtin_nontemporal_store(packed, reinterpret_cast<uint32_t *>(rail + pu));
+                }
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) { const int64_t o = __shfl_xor(miss, d); miss = o < miss ? o : miss; }
+            if ((threadIdx.x & 63) == 0 && miss != INT64_MAX) {
+                const int64_t slot = (int64_t)inst_lo * N;
+                if (run_end[slot] > miss) atomicMin((long long *)&run_end[slot], (long long)miss);
+            }
+            continue;
+        }
         for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPfThreads * 4) {
             uint32_t w[4];
             const bool full = p + 4 <= total;
