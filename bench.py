@@ -2,7 +2,9 @@
 """Benchmark of the whole rail-spraying path on one MI355X.
 
 A step is one pass of all five stages (route_topk -> traffic_matrix -> chunk_sort -> lpt_spray ->
-eval) over one batch of the Mixtral-8x7B-shaped workload: 8 nodes x 8 rails, 8 experts top-2,
+eval) over one batch of the Mixtral-8x7B-shaped workload, the first two in one pass over the logits
+(railsched_route_traffic writes the same indices and the same matrix as the two separate calls);
+the same step through the five separate calls is timed too and reported as "staged".  Workload: 8 nodes x 8 rails, 8 experts top-2,
 16384 tokens per GPU, 8 KiB tokens, 256 KiB chunks, 32 layers = 32 traffic matrices of 64x64.
 Inputs (1 GiB of fp32 router logits, synthetic, seeded) are resident in HBM before timing starts.
 Prints ONE JSON line.
@@ -18,9 +20,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes one route_topk launch moves on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
-# 1 GiB copy of known traffic (profiles/c2_whole_path.md): 1034.98 MiB read + 256.00 MiB written.
-ROUTE_TOPK_C2_TRAFFIC_BYTES = int((1034.98 + 256.00) * 1024 * 1024)
+# HBM bytes the launches of one route_traffic call (main kernel + reduction of the slice counts) move on this
+# workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy of known traffic (profiles/c2_whole_path.md).
+# route_traffic_kernel 1038.38 MiB read + 272.00 MiB written, rt_reduce_kernel 16.04 MiB read + 1.00 MiB written.
+ROUTE_TRAFFIC_C2_TRAFFIC_BYTES = int((1038.38 + 272.00 + 16.04 + 1.00) * 1024 * 1024)
 
 
 def parse():
@@ -77,9 +80,11 @@ def main():
     del idx0, D10
     plan = rs.Plan(topo, B, total_chunks, dev, rows=rows, k=cfg.k, want_perm=True)
 
-    names = ("route_topk", "traffic_matrix", "chunk_sort", "lpt_spray", "eval")
+    ws_rt = torch.empty(max(rs.route_traffic_workspace_bytes(B, cfg.tokens_per_gpu, cfg.E, topo), 256), dtype=torch.uint8, device=dev)
+    names = {True: ("route_traffic", "chunk_sort", "lpt_spray", "eval"),
+             False: ("route_topk", "traffic_matrix", "chunk_sort", "lpt_spray", "eval")}
 
-    def step(events=None):
+    def step(fused, events=None):
         marks = []
         def mark():
             if events is not None:
@@ -87,8 +92,12 @@ def main():
                 e.record()
                 marks.append(e)
         mark()
-        rs.route_topk(logits, cfg.k, out=plan.topk_idx); mark()
-        rs.traffic_matrix(plan.topk_idx, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=plan.D1); mark()
+        if fused:
+            rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo,
+                             out=(plan.topk_idx, plan.D1), ws=ws_rt); mark()
+        else:
+            rs.route_topk(logits, cfg.k, out=plan.topk_idx); mark()
+            rs.traffic_matrix(plan.topk_idx, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=plan.D1); mark()
         rs.chunk_sort(plan.D1, topo, capacity=plan.capacity,
                       out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort); mark()
         rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S)); mark()
@@ -97,22 +106,27 @@ def main():
         if events is not None:
             events.append(marks)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev = []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(ev)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    def run(fused):
+        for _ in range(args.warmup):
+            step(fused)
+        torch.cuda.synchronize()
+        ev = []
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(fused, ev)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms = {n: 0.0 for n in names[fused]}
+        for marks in ev:
+            for i, n in enumerate(names[fused]):
+                ms[n] += marks[i].elapsed_time(marks[i + 1])
+        return (t1 - t0) * 1e3 / args.steps, {n: v / args.steps for n, v in ms.items()}
 
-    stage_ms = {n: 0.0 for n in names}
-    for marks in ev:
-        for i, n in enumerate(names):
-            stage_ms[n] += marks[i].elapsed_time(marks[i + 1])
-    stage_ms = {n: v / args.steps for n, v in stage_ms.items()}
+    staged_ms_per_step, staged_ms = run(False)
+    idx_staged, D1_staged = plan.topk_idx.clone(), plan.D1.clone()
+    ms_per_step, stage_ms = run(True)                # the timed region the headline value comes from
+    assert torch.equal(idx_staged, plan.topk_idx) and torch.equal(D1_staged, plan.D1)
+    del idx_staged, D1_staged
 
     assert int(plan.chunk_off[-1].item()) == total_chunks
 
@@ -154,11 +168,13 @@ def main():
     combine = {"transpose_ms": tr_ms, "schedule_ms": comb_ms, "chunks": n_comb, "makespan_over_lb_max": float(r_c.max())}
     rs.chunk_sort(plan.D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
 
-    # ---- roofline of the dominant kernel (route_topk streams the logits once)
+    # ---- roofline of the dominant kernel (route_traffic streams the logits once and writes the indices once)
     k1_bytes = rows * (4 * cfg.E + 4 * cfg.k)
     k2_bytes = rows * 4 * cfg.k + 8 * B * G * G
-    k1_gbps = k1_bytes / (stage_ms["route_topk"] * 1e-3) / 1e9
-    routing_gbps = (k1_bytes + k2_bytes) / ((stage_ms["route_topk"] + stage_ms["traffic_matrix"]) * 1e-3) / 1e9
+    rt_bytes = k1_bytes + 8 * B * G * G
+    rt_gbps = rt_bytes / (stage_ms["route_traffic"] * 1e-3) / 1e9
+    k1_gbps = k1_bytes / (staged_ms["route_topk"] * 1e-3) / 1e9
+    staged_routing_gbps = (k1_bytes + k2_bytes) / ((staged_ms["route_topk"] + staged_ms["traffic_matrix"]) * 1e-3) / 1e9
     dominant = max(stage_ms, key=stage_ms.get)
     # LPT against the VALU issue rate: ceil(log2 N) cross-lane mins + compare + select + add per chunk and lane group,
     # 64/GW lane groups per wavefront instruction; 256 CUs x 4 SIMDs issue one wave64 VALU instruction per 4 cycles at 2.4 GHz
@@ -168,7 +184,7 @@ def main():
     lpt_rate = total_chunks / (stage_ms["lpt_spray"] * 1e-3)
 
     out = {
-        "metric": "LPT-sprayed chunks/s over the whole path (route_topk, traffic_matrix, chunk_sort, lpt_spray, eval)",
+        "metric": "LPT-sprayed chunks/s over the whole path (route_topk + traffic_matrix in one pass, chunk_sort, lpt_spray, eval)",
         "value": total_chunks / (ms_per_step * 1e-3),
         "unit": "chunks/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -179,8 +195,11 @@ def main():
                                f"{cfg.tokens_per_gpu} tokens/GPU x {cfg.payload_bytes} B, C={cfg.chunk_bytes} B, {B} matrices of {G}x{G}",
                    "rows": rows, "chunks": total_chunks, "instances": B * cfg.M},
         "stage_ms": stage_ms,
-        "routing_to_traffic_matrix_GBps": routing_gbps,
-        "routing_frac_of_hbm_peak": routing_gbps / HBM_PEAK_GBPS,
+        "staged": {"ms_per_step": staged_ms_per_step, "value": total_chunks / (staged_ms_per_step * 1e-3), "stage_ms": staged_ms,
+                   "note": "the same step through the five separate calls (indices written, then read back)",
+                   "route_topk_GBps": k1_gbps, "routing_to_traffic_matrix_GBps": staged_routing_gbps},
+        "routing_to_traffic_matrix_GBps": rt_gbps,
+        "routing_frac_of_hbm_peak": rt_gbps / HBM_PEAK_GBPS,
         "lpt_spray_chunks_per_s": lpt_rate,
         "lpt_roofline": {"bound": "alu", "achieved": lpt_rate * instr_per_chunk / 1e9, "peak": valu_peak,
                          "unit": "G wave-instr/s", "frac": lpt_rate * instr_per_chunk / 1e9 / valu_peak,
@@ -190,10 +209,11 @@ def main():
         "schemes": schemes,
         "second_all_to_all": combine,
         "completion_time_us_max": float(stats[:, 0].max() / cfg.rail_bw_Bps * 1e6),
-        "roofline": {"kernel": "route_topk_kernel", "bound": "hbm", "achieved": k1_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": k1_gbps / HBM_PEAK_GBPS,
-                     "traffic": ROUTE_TOPK_C2_TRAFFIC_BYTES if cfg.name == "c2" else None,
-                     "algorithmic_bytes_per_launch": k1_bytes, "avg_launch_ms": stage_ms["route_topk"],
+        "roofline": {"kernel": "route_traffic_kernel (with rt_reduce_kernel, the sum of its slice counts, in the same call)",
+                     "bound": "hbm", "achieved": rt_gbps, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": rt_gbps / HBM_PEAK_GBPS,
+                     "traffic": ROUTE_TRAFFIC_C2_TRAFFIC_BYTES if cfg.name == "c2" else None,
+                     "algorithmic_bytes_per_launch": rt_bytes, "avg_launch_ms": stage_ms["route_traffic"],
                      "slowest_stage": dominant},
     }
 

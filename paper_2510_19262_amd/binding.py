@@ -10,7 +10,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 from dataclasses import dataclass
-from typing import Optional
+from typing import Optional, Tuple
 
 import torch
 
@@ -20,6 +20,7 @@ _lib = None
 
 EXPORTS = (
     "railsched_version", "railsched_strerror", "railsched_route_topk", "railsched_traffic_matrix",
+    "railsched_route_traffic_workspace_bytes", "railsched_route_traffic",
     "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray", "railsched_lpt_spray_chunkwise",
     "railsched_eval_workspace_bytes", "railsched_eval", "railsched_transpose_matrix", "railsched_assign_policy",
     "railsched_port_round_robin_workspace_bytes", "railsched_port_round_robin",
@@ -74,6 +75,9 @@ def load():
     TP = C.POINTER(_TopoStruct)
     lib.railsched_route_topk.argtypes = [P, I64, I32, I32, P, P]
     lib.railsched_traffic_matrix.argtypes = [P, I32, I64, I32, P, I32, I32, I64, TP, P, P]
+    lib.railsched_route_traffic_workspace_bytes.argtypes = [I32, I64, I32, TP]
+    lib.railsched_route_traffic_workspace_bytes.restype = SZ
+    lib.railsched_route_traffic.argtypes = [P, I32, I64, I32, I32, P, I32, I64, TP, P, P, P, SZ, P]
     lib.railsched_chunk_sort_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_chunk_sort_workspace_bytes.restype = SZ
     lib.railsched_chunk_sort.argtypes = [P, I32, TP, P, P, P, P, I64, P, SZ, P]
@@ -90,7 +94,8 @@ def load():
     lib.railsched_port_round_robin.restype = C.c_int
     lib.railsched_transpose_matrix.restype = C.c_int
     lib.railsched_assign_policy.restype = C.c_int
-    for fn in ("railsched_route_topk", "railsched_traffic_matrix", "railsched_chunk_sort", "railsched_lpt_spray",
+    for fn in ("railsched_route_topk", "railsched_traffic_matrix",
+    "railsched_route_traffic_workspace_bytes", "railsched_route_traffic", "railsched_chunk_sort", "railsched_lpt_spray",
                "railsched_lpt_spray_chunkwise", "railsched_eval"):
         getattr(lib, fn).restype = C.c_int
     _lib = lib
@@ -162,6 +167,42 @@ def traffic_matrix(topk_idx: torch.Tensor, batch: int, tokens_per_gpu: int, expe
     _check(load().railsched_traffic_matrix(_ptr(topk_idx), batch, tokens_per_gpu, k, _ptr(expert_gpu), E, R,
                                            payload_bytes, C.byref(t), _ptr(out), _stream()), "railsched_traffic_matrix")
     return out
+
+
+def route_traffic_workspace_bytes(batch: int, tokens_per_gpu: int, E: int, topo: Topo) -> int:
+    t = topo.c()
+    return int(load().railsched_route_traffic_workspace_bytes(batch, tokens_per_gpu, E, C.byref(t)))
+
+
+def route_traffic(logits: torch.Tensor, k: int, batch: int, tokens_per_gpu: int, expert_gpu: torch.Tensor,
+                  payload_bytes: int, topo: Topo, want_idx: bool = True,
+                  out: Optional[Tuple[Optional[torch.Tensor], torch.Tensor]] = None, ws: Optional[torch.Tensor] = None):
+    """Stages 1 and 2 in one call: (topk_idx or None, D1)."""
+    _dev(logits, torch.float32, "logits")
+    _dev(expert_gpu, torch.int32, "expert_gpu")
+    rows, E = logits.shape
+    E2, R = expert_gpu.shape
+    G = topo.G
+    if E2 != E:
+        raise ValueError("expert_gpu must have one row per expert")
+    if rows != batch * G * tokens_per_gpu:
+        raise ValueError("logits must hold batch*G*tokens_per_gpu rows")
+    if out is None:
+        idx = torch.empty((rows, k), dtype=torch.int32, device=logits.device) if want_idx else None
+        D1 = torch.empty((batch, G, G), dtype=torch.int64, device=logits.device)
+    else:
+        idx, D1 = out
+    if idx is not None:
+        _dev(idx, torch.int32, "topk_idx")
+    _dev(D1, torch.int64, "D1")
+    if ws is None:
+        ws = _ws(route_traffic_workspace_bytes(batch, tokens_per_gpu, E, topo), logits.device)
+    t = topo.c()
+    _check(load().railsched_route_traffic(_ptr(logits), batch, tokens_per_gpu, E, k, _ptr(expert_gpu), R, payload_bytes,
+                                          C.byref(t), None if idx is None else _ptr(idx), _ptr(D1), _ptr(ws), ws.numel(),
+                                          _stream()),
+           "railsched_route_traffic")
+    return idx, D1
 
 
 # ---------------------------------------------------------------------------------- stage 3

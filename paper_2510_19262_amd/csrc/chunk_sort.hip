@@ -16,10 +16,12 @@
 
 namespace rs {
 
-constexpr int kTile = 16384;        // full-chunk positions per fill tile
+constexpr int kTileMin = 1024;      // full-chunk positions per fill tile: a power of two between these two, chosen per call
+constexpr int kTileMax = 16384;     // so that small batches still spread over a few thousand workgroups
 constexpr int kFillThreads = 256;
 constexpr int kFillStage = 4096;    // flow boundaries staged in LDS per tile
-constexpr int kFillBlocks = 2048;
+constexpr int kFillBlocks = 16384;   // most workgroups of one fill launch; LDS admits five per compute unit, so a grid of
+                                    // several rounds evens out what a grid sized to one round leaves to its last, partly filled round
 
 struct CsArgs {
     const int64_t *D1;
@@ -32,6 +34,7 @@ struct CsArgs {
     int32_t cshift;      // >= 0 when C is a power of two
     int32_t M, N, G, NF, intra;
     int32_t n_inst;
+    int32_t tile;        // full-chunk positions per fill tile
 };
 
 __device__ __forceinline__ void split_bytes(const CsArgs &a, int64_t B, uint32_t &q, uint32_t &r)
@@ -107,7 +110,7 @@ __global__ __launch_bounds__(1024) void cs_scan_kernel(CsArgs a)
     for (int base = 0; base < a.n_inst; base += 1024) {
         const int i = base + tid;
         const int64_t va = i < a.n_inst ? a.cnt_all[i] : 0;
-        const int64_t vt = i < a.n_inst ? (a.cnt_full[i] + kTile - 1) / kTile : 0;
+        const int64_t vt = i < a.n_inst ? (a.cnt_full[i] + a.tile - 1) / a.tile : 0;
         sh_a[tid] = va; sh_t[tid] = vt;
         __syncthreads();
         for (int d = 1; d < 1024; d <<= 1) {
@@ -226,16 +229,6 @@ __device__ __forceinline__ int last_le(const T *v, int n, uint32_t x)   // last 
     return lo;
 }
 
-__device__ __forceinline__ int last_le64(const int64_t *v, int n, int64_t x)
-{
-    int lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (v[mid] <= x) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 // Positions [p0,p1) of one instance's full-chunk region.  Positions are grouped by fours at multiples
 // of four of the global record index, so a thread finds the flow of its first position by binary
 // search, walks to the next flows if its four positions cross a boundary, and stores 16 bytes per array.
@@ -248,8 +241,8 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec
     for (int64_t u = blockIdx.x; u < n_tiles; u += gridDim.x) {
         const int inst = wave_last_le<int64_t>(a.tile_off, a.n_inst, u);  // tile_off[inst] <= u < tile_off[inst+1]
         const uint32_t n_full = (uint32_t)a.cnt_full[inst];
-        const uint32_t p0 = (uint32_t)(u - a.tile_off[inst]) * (uint32_t)kTile;
-        const uint32_t p1 = (n_full - p0 < (uint32_t)kTile) ? n_full : p0 + (uint32_t)kTile;
+        const uint32_t p0 = (uint32_t)(u - a.tile_off[inst]) * (uint32_t)a.tile;
+        const uint32_t p1 = (n_full - p0 < (uint32_t)a.tile) ? n_full : p0 + (uint32_t)a.tile;
         const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
         const uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
         const int f_lo = wave_last_le<uint32_t>(fs, a.NF, p0);
@@ -352,6 +345,8 @@ extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const rail
     CsArgs a;
     a.D1 = D1; a.chunk_off = chunk_off; a.chunk_w = chunk_w; a.chunk_flow = chunk_flow; a.perm = perm;
     a.capacity = capacity;
+    a.tile = kTileMin;
+    while (a.tile < kTileMax && capacity / a.tile > 8192) a.tile *= 2;
     a.cnt_all = reinterpret_cast<int64_t *>(w8 + off[0]);
     a.cnt_full = reinterpret_cast<int64_t *>(w8 + off[1]);
     a.tile_off = reinterpret_cast<int64_t *>(w8 + off[2]);
@@ -380,6 +375,9 @@ extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const rail
     if (int rc = launch_status()) return rc;
     const int vec_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(chunk_flow) % 16 == 0 &&
                         reinterpret_cast<uintptr_t>(perm) % 16 == 0) ? 1 : 0;
-    hipLaunchKernelGGL(cs_fill_kernel, dim3(kFillBlocks), dim3(kFillThreads), 0, st, a, vec_ok);
+    // no launch needs more workgroups than there can be tiles: capacity/tile full ones and one ragged one per instance
+    int64_t fill_blocks = capacity / a.tile + n_inst;
+    fill_blocks = fill_blocks < 1 ? 1 : fill_blocks > kFillBlocks ? kFillBlocks : fill_blocks;
+    hipLaunchKernelGGL(cs_fill_kernel, dim3((unsigned)fill_blocks), dim3(kFillThreads), 0, st, a, vec_ok);
     return launch_status();
 }

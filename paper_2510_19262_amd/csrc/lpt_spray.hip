@@ -166,7 +166,8 @@ __device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsi
 // ================================================================================ leading run
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kPfThreads = 256;
-constexpr int kPfTile = 16384;      // chunk positions per workgroup iteration (16 x uint4 per thread)
+constexpr int kPfTile = 16384;      // most chunk positions per workgroup iteration (16 x uint4 per thread)
+constexpr int kPfPass = kPfThreads * 4;   // positions one pass of the workgroup covers
 constexpr int kPfStage = 1024;      // instance boundaries staged in LDS per tile
 constexpr int kPfBlocks = 2048;
 
@@ -198,8 +199,11 @@ __global__ __launch_bounds__(kPfThreads) void lpt_prefix_kernel(const int64_t *_
     __shared__ int64_t s_off[kPfStage + 1];
     __shared__ uint32_t s_w0[kPfStage];
     const int64_t total = chunk_off[n_inst];
-    for (int64_t t0 = (int64_t)blockIdx.x * kPfTile; t0 < total; t0 += (int64_t)gridDim.x * kPfTile) {
-        const int64_t t1 = t0 + kPfTile < total ? t0 + kPfTile : total;
+    // tile: the share of one workgroup when the whole grid takes one tile each, in whole passes, at most kPfTile
+    int64_t tile = ((total + gridDim.x - 1) / gridDim.x + kPfPass - 1) / kPfPass * kPfPass;
+    tile = tile < kPfPass ? kPfPass : tile > kPfTile ? kPfTile : tile;
+    for (int64_t t0 = (int64_t)blockIdx.x * tile; t0 < total; t0 += (int64_t)gridDim.x * tile) {
+        const int64_t t1 = t0 + tile < total ? t0 + tile : total;
         const int inst_lo = wave_last_le<int64_t>(chunk_off, n_inst, t0);
         const int inst_hi = wave_last_le<int64_t>(chunk_off, n_inst, t1 - 1);
         const int cnt = inst_hi - inst_lo + 1;

@@ -26,7 +26,8 @@ struct TmArgs {
     int32_t k, kshift;       // kshift >= 0 when k is a power of two
     int32_t E, R, rmask;     // rmask >= 0 when R is a power of two
     int32_t G, splits;
-    int32_t copies, lanes_per_period;   // LDS histogram replicas and the lane period of the replica pattern
+    int32_t copies, lanes_per_period;
+    int32_t bin_stride;      // words between histogram copies: odd, so that a bin's copies lie in different LDS banks
     int32_t table_in_lds;
 };
 
@@ -51,12 +52,12 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
     // [copies][G] counters.  Lanes whose tokens share a replica index rho - every lanes_per_period-th
     // lane - would pile onto the bins of the popular experts; they get different copies instead.
     unsigned *all_bins = tm_lds;
-    unsigned *bins = all_bins + (size_t)((threadIdx.x / a.lanes_per_period) & (a.copies - 1)) * a.G;
-    int32_t *lds_table = reinterpret_cast<int32_t *>(tm_lds + (size_t)a.copies * a.G);   // [E*R] when it fits
+    unsigned *bins = all_bins + (size_t)((threadIdx.x / a.lanes_per_period) & (a.copies - 1)) * a.bin_stride;
+    int32_t *lds_table = reinterpret_cast<int32_t *>(tm_lds + (size_t)a.copies * a.bin_stride);   // [E*R] when it fits
     const int64_t pair = blockIdx.x / a.splits;                         // b*G + s
     const int part = blockIdx.x % a.splits;
 
-    for (int i = threadIdx.x; i < a.G * a.copies; i += kTmThreads) all_bins[i] = 0;
+    for (int i = threadIdx.x; i < a.bin_stride * a.copies; i += kTmThreads) all_bins[i] = 0;
     if (a.table_in_lds)
         for (int i = threadIdx.x; i < a.E * a.R; i += kTmThreads) lds_table[i] = a.expert_gpu[i];
     __syncthreads();
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
     int64_t *dst = a.D1 + pair * a.G;
     for (int i = threadIdx.x; i < a.G; i += kTmThreads) {
         unsigned cnt = 0;
-        for (int c = 0; c < a.copies; ++c) cnt += all_bins[(size_t)c * a.G + i];
+        for (int c = 0; c < a.copies; ++c) cnt += all_bins[(size_t)c * a.bin_stride + i];
         const int64_t bytes = (int64_t)cnt * a.payload;
         if (a.splits == 1) dst[i] = bytes;                               // sole owner: plain store, zeros included
         else if (bytes) atomicAdd(reinterpret_cast<unsigned long long *>(dst + i), (unsigned long long)bytes);
@@ -122,10 +123,11 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
     a.E = E; a.R = R; a.rmask = is_pow2(R) ? R - 1 : -1;
     a.G = (int32_t)G;
     a.copies = 1;
-    while (a.copies < 8 && (int64_t)a.copies * 2 * G <= 8192) a.copies *= 2;
+    while (a.copies < 8 && (int64_t)a.copies * 2 * (G | 1) <= 8192) a.copies *= 2;
     // a lane holds 4 consecutive slots, so rho repeats every R*k/4 lanes when that is a whole number
     a.lanes_per_period = ((int64_t)R * k % 4 == 0 && (int64_t)R * k / 4 <= 64) ? (int32_t)((int64_t)R * k / 4) : 1;
-    a.table_in_lds = ((int64_t)E * R <= kTmTableMax && 4 * (a.copies * G + (int64_t)E * R) <= 64 * 1024) ? 1 : 0;
+    a.bin_stride = (int32_t)(a.copies > 1 ? (G | 1) : G);
+    a.table_in_lds = ((int64_t)E * R <= kTmTableMax && 4 * (a.copies * (int64_t)a.bin_stride + (int64_t)E * R) <= 64 * 1024) ? 1 : 0;
 
     // enough workgroups to cover the chip, but no slice shorter than 16 Ki slots
     const int64_t pairs = (int64_t)batch * G;
@@ -141,7 +143,7 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
         hipLaunchKernelGGL(fill_zero_i64, dim3((unsigned)((n + 1023) / 1024 > 4096 ? 4096 : (n + 1023) / 1024)), dim3(256), 0, st, D1, n);
         if (int rc = launch_status()) return rc;
     }
-    const size_t lds = sizeof(unsigned) * (size_t)G * a.copies + (a.table_in_lds ? sizeof(int32_t) * (size_t)E * R : 0);
+    const size_t lds = sizeof(unsigned) * (size_t)a.bin_stride * a.copies + (a.table_in_lds ? sizeof(int32_t) * (size_t)E * R : 0);
     if (a.kshift >= 0 && a.rmask >= 0)
         hipLaunchKernelGGL(traffic_matrix_kernel<true>, dim3((unsigned)(pairs * splits)), dim3(kTmThreads), lds, st, a);
     else

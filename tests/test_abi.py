@@ -73,6 +73,32 @@ def test_traffic_matrix_validation():
     assert f(FAKE, 0, 10, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, None) == 0
 
 
+def test_route_traffic_validation():
+    lib = rs.load()
+    t = _topo()
+    need = lib.railsched_route_traffic_workspace_bytes(1, 10_000, 8, C.byref(t))
+    assert need >= 4 * 16 * 16 * (10_000 // 4096) and need % 256 == 0
+    assert lib.railsched_route_traffic_workspace_bytes(1, 10, 8, C.byref(t)) == 256     # one slice per pair: nothing needed
+    assert lib.railsched_route_traffic_workspace_bytes(1, 10_000, 16, C.byref(t)) == 256
+    assert lib.railsched_route_traffic_workspace_bytes(-1, 10, 8, C.byref(t)) == 0
+    f = lib.railsched_route_traffic   # (logits, batch, tokens_per_gpu, E, k, expert_gpu, R, payload, topo, idx, D1, ws, ws_bytes, stream)
+    assert f(FAKE, -1, 10, 8, 2, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == -1
+    assert f(FAKE, 1, 10, 8, 9, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == -1
+    assert f(FAKE, 1, 10, 8, 2, FAKE, 0, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == -1
+    assert f(FAKE, 1, 10, 8, 2, FAKE, 2, -1, C.byref(t), FAKE, FAKE, FAKE, need, None) == -1
+    assert f(FAKE, 1, 10, 2048, 2, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == -3
+    assert f(FAKE, 1, 1 << 31, 8, 2, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == -3
+    assert f(None, 1, 10, 8, 2, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == -2
+    assert f(FAKE, 1, 10, 8, 2, None, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == -2
+    assert f(FAKE, 1, 10, 8, 2, FAKE, 2, 1024, C.byref(t), FAKE, None, FAKE, need, None) == -2
+    assert f(FAKE, 1, 10, 16, 2, FAKE, 2, 1024, C.byref(t), None, FAKE, FAKE, need, None) == -2   # wide rows need the index array
+    assert f(FAKE, 1, 10, 8, 2, FAKE, 2, 1024, None, FAKE, FAKE, FAKE, need, None) == -2
+    assert f(FAKE, 1, 10_000, 8, 2, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, None, need, None) == -5
+    assert f(FAKE, 1, 10_000, 8, 2, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need - 256, None) == -5
+    assert f(FAKE, 1, 10_000, 8, 2, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, P(0x1001), need, None) == -5
+    assert f(FAKE, 0, 10, 8, 2, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == 0
+
+
 def test_chunk_sort_and_eval_validation():
     lib = rs.load()
     t = _topo()

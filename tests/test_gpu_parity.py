@@ -134,6 +134,63 @@ def test_traffic_matrix_skewed_bins():
     assert np.array_equal(got.cpu().numpy(), oracle.traffic_matrix(idx, 1, tok, eg, 8192, M, N))
 
 
+# ------------------------------------------------------------------------------ stages 1+2 in one call
+def _coarse_logits(rng, rows, E):
+    # a coarse lattice: exact ties between logits of a row are common
+    return (rng.integers(-6, 7, size=(rows, E)) * 0.25).astype(np.float32)
+
+
+@pytest.mark.parametrize("M,N,E,k,R,tok,batch,want_idx", [
+    (4, 4, 8, 2, 2, 2048, 1, True), (8, 8, 8, 2, 8, 4096, 2, True), (8, 8, 8, 2, 8, 4096, 2, False),
+    (2, 3, 6, 3, 1, 777, 2, True), (3, 2, 7, 2, 3, 5000, 3, True), (1, 1, 4, 1, 1, 10, 1, True),
+    (2, 2, 4, 4, 2, 70001, 1, True), (2, 2, 3, 2, 5, 2049, 2, True), (2, 2, 8, 8, 4, 3000, 1, True),
+    (2, 4, 1, 1, 1, 100, 1, True), (2, 4, 2, 1, 2, 4097, 1, False), (2, 2, 5, 5, 2, 0, 2, True),
+    (4, 2, 16, 4, 2, 1000, 2, True), (2, 2, 64, 8, 1, 300, 1, True)])
+def test_route_traffic_matches_the_two_stages_of_the_oracle(M, N, E, k, R, tok, batch, want_idx):
+    rng = np.random.default_rng(M * 1000 + N * 100 + E * 10 + k)
+    G = M * N
+    eg = rng.integers(0, G, size=(E, R)).astype(np.int32)
+    rows = batch * G * tok
+    x = _coarse_logits(rng, rows, E)
+    topo = rs.Topo(M, N, 4096)
+    if E > 8 and not want_idx:
+        pytest.skip("wide rows need the index array")
+    idx, D1 = rs.route_traffic(torch.from_numpy(x).to(DEV).view(rows, E), k, batch, tok, torch.from_numpy(eg).to(DEV), 2048, topo,
+                               want_idx=want_idx)
+    want = oracle.route_topk(x, k) if rows else np.empty((0, k), np.int32)
+    if want_idx:
+        assert np.array_equal(idx.cpu().numpy(), want)
+    else:
+        assert idx is None
+    assert np.array_equal(D1.cpu().numpy(), oracle.traffic_matrix(want, batch, tok, eg, 2048, M, N))
+
+
+def test_route_traffic_unaligned_logits_and_stale_output():
+    M, N, E, k, R, tok = 2, 2, 8, 2, 2, 3001
+    rng = np.random.default_rng(5)
+    G = M * N
+    rows = G * tok
+    x = _coarse_logits(rng, rows, E)
+    eg = rng.integers(0, G, size=(E, R)).astype(np.int32)
+    buf = torch.zeros(rows * E + 1, device=DEV)
+    buf[1:] = torch.from_numpy(x).to(DEV).view(-1)
+    lg = buf[1:].view(rows, E)                                   # base pointer off 16-byte alignment
+    D1 = torch.full((1, G, G), -7, dtype=torch.int64, device=DEV)   # stale contents must be overwritten
+    idx = torch.full((rows, k), -1, dtype=torch.int32, device=DEV)
+    rs.route_traffic(lg, k, 1, tok, torch.from_numpy(eg).to(DEV), 512, rs.Topo(M, N, 4096), out=(idx, D1))
+    want = oracle.route_topk(x, k)
+    assert np.array_equal(idx.cpu().numpy(), want)
+    assert np.array_equal(D1.cpu().numpy(), oracle.traffic_matrix(want, 1, tok, eg, 512, M, N))
+
+
+def test_route_traffic_wide_rows_need_the_index_array():
+    topo = rs.Topo(2, 2, 4096)
+    lg = torch.zeros((4 * 8, 16), device=DEV)
+    eg = torch.zeros((16, 1), dtype=torch.int32, device=DEV)
+    with pytest.raises(rs.RailschedError):
+        rs.route_traffic(lg, 2, 1, 8, eg, 64, topo, want_idx=False)
+
+
 # ------------------------------------------------------------------------------ stages 3-5
 def _rand_stack(rng, B, G, C, p_zero=0.3, hi=6):
     m = rng.integers(0, hi * C, size=(B, G, G)).astype(np.int64)
