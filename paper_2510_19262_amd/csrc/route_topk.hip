@@ -287,6 +287,146 @@ __global__ __launch_bounds__(256) void route_topk_keys_kernel(const float *__res
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Merge variant of the packed-key kernel for k <= 8: no rounds.  A lane sorts its keys eight at a time and keeps
+// the 8 largest (top8_of_two); then the lanes of a row merge pairwise, log2(LANES) times, each keeping the 8 largest
+// of its own and its partner's list - both partners end with the same list, so after the last step every lane of
+// the row holds the row's 8 largest keys in order.  Few lanes per row (4..16) make most of the work lane-local.
+// The value cut is validated as in the rounds kernel: neighbouring winners must differ above the index bits, and
+// exactly k keys of the row may reach the cut value of the k-th winner; other row groups are redone exactly.
+// ---------------------------------------------------------------------------------------------
+template <int OFF>
+__device__ __forceinline__ void merge_with_partner(unsigned (&a)[8])
+{
+    unsigned b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b[i] = xlane<OFF>(a[i]);
+    top8_of_two(a, b);
+}
+
+// WAVES: resident wavefronts per SIMD the register allocation is held to (more for short per-lane key arrays).
+template <int LANES, int VPL, int WAVES>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, 8))) void route_topk_merge_kernel(const float *__restrict__ logits, int64_t rows, int E, int k,
+                                                               int32_t *__restrict__ topk_idx)
+{
+    constexpr int RPW = 64 / LANES;                 // rows per wavefront
+    constexpr int NV = VPL / 4;                     // float4 loads per lane and row
+    constexpr unsigned MASK = (unsigned)(LANES * VPL) - 1u;   // expert index bits of a key
+    static_assert(VPL % 8 == 0 && LANES >= 2 && LANES <= 16, "whole groups of eight keys per lane");
+    const int lane = threadIdx.x & 63;
+    const int q = lane % LANES;
+    const int64_t wave_first = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW;
+    const int64_t first = wave_first + lane / LANES;
+    const int64_t stride = (int64_t)gridDim.x * 4 * RPW;
+    const float4 none = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+
+    for (int64_t w0 = wave_first; w0 < rows; w0 += stride) {            // wave-uniform trip count
+        const int64_t row = first + (w0 - wave_first);
+        const bool live = row < rows;
+        // no prefetch of the next row: the registers buy more resident wavefronts, which hide the loads as well
+        float4 x[NV];
+#pragma unroll
+        for (int c = 0; c < NV; ++c) {
+            const int e0 = 4 * (q + LANES * c);
+            x[c] = (live && e0 < E) ? load_stream4(logits + row * E + e0) : none;
+        }
+        unsigned key[VPL];
+#pragma unroll
+        for (int c = 0; c < NV; ++c) {
+            const int e0 = 4 * (q + LANES * c);
+            const bool has = live && e0 < E;
+            key[4 * c + 0] = has ? make_key<MASK>(x[c].x, e0 + 0) : 0u; key[4 * c + 1] = has ? make_key<MASK>(x[c].y, e0 + 1) : 0u;
+            key[4 * c + 2] = has ? make_key<MASK>(x[c].z, e0 + 2) : 0u; key[4 * c + 3] = has ? make_key<MASK>(x[c].w, e0 + 3) : 0u;
+        }
+        unsigned lst[8];                                                // descending: the best 8 seen so far
+#pragma unroll
+        for (int j = 0; j < 8; ++j) lst[j] = key[j];
+        sort8_desc(lst);
+#pragma unroll
+        for (int g = 1; g < VPL / 8; ++g) {
+            unsigned nxt[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) nxt[j] = key[8 * g + j];
+            sort8_desc(nxt);
+            top8_of_two(lst, nxt);
+        }
+        merge_with_partner<1>(lst);
+        if constexpr (LANES >= 4) merge_with_partner<2>(lst);
+        if constexpr (LANES >= 8) merge_with_partner<4>(lst);
+        if constexpr (LANES >= 16) merge_with_partner<8>(lst);
+
+        // lst[j] = j-th largest key of the row (0 where the row has fewer than 8 logits), the same in all its lanes
+        unsigned kth = lst[0];
+        bool bad = false;
+#pragma unroll
+        for (int j = 1; j < 8; ++j) {
+            if (j < k) {
+                bad = bad || ((lst[j] ^ lst[j - 1]) <= MASK);           // neighbouring winners share a cut value
+                kth = lst[j];
+            }
+        }
+        const unsigned thr = kth & ~MASK;
+        int reach = 0;                                                  // keys of the row at or above the k-th winner's cut value
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) reach += (key[j] >= thr) ? 1 : 0;
+        reach += xlane<1>(reach);
+        if constexpr (LANES >= 4) reach += xlane<2>(reach);
+        if constexpr (LANES >= 8) reach += xlane<4>(reach);
+        if constexpr (LANES >= 16) reach += xlane<8>(reach);
+        bad = live && (bad || reach != k);
+
+        unsigned sel_key[(8 + LANES - 1) / LANES];                      // winners q, q+LANES, ... of this lane
+#pragma unroll
+        for (int r = 0; r < (8 + LANES - 1) / LANES; ++r) {
+            sel_key[r] = 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sel_key[r] = (j == q + r * LANES) ? lst[j] : sel_key[r];
+        }
+        int result[(8 + LANES - 1) / LANES];
+#pragma unroll
+        for (int r = 0; r < (8 + LANES - 1) / LANES; ++r) result[r] = (int)(MASK - (sel_key[r] & MASK));
+
+        if (__ballot(bad) != 0ull) {          // rare: the wavefront's rows are read again and picked by full comparisons
+            float v[VPL];
+#pragma unroll
+            for (int c = 0; c < NV; ++c) {
+                const int e0 = 4 * (q + LANES * c);
+                const float4 cur = (live && e0 < E) ? load_stream4(logits + row * E + e0) : none;
+                v[4 * c + 0] = cur.x; v[4 * c + 1] = cur.y; v[4 * c + 2] = cur.z; v[4 * c + 3] = cur.w;
+            }
+            for (int sel = 0; sel < k; ++sel) {
+                float bv = -INFINITY;
+                int bi = INT_MAX;
+#pragma unroll
+                for (int j = 0; j < VPL; ++j) {
+                    const bool better = v[j] > bv;
+                    bv = better ? v[j] : bv;
+                    bi = better ? slot_index<LANES, VPL, true>(q, j) : bi;
+                }
+                group_argmax<LANES>(bv, bi);
+#pragma unroll
+                for (int j = 0; j < VPL; ++j) v[j] = (slot_index<LANES, VPL, true>(q, j) == bi) ? -INFINITY : v[j];
+#pragma unroll
+                for (int r = 0; r < (8 + LANES - 1) / LANES; ++r) result[r] = (q + r * LANES == sel) ? bi : result[r];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < (8 + LANES - 1) / LANES; ++r)
+            if (live && q + r * LANES < k) topk_idx[row * k + q + r * LANES] = result[r];
+    }
+}
+
+template <int LANES, int VPL, int WAVES>
+static int launch_topk_merge(const float *logits, int64_t rows, int E, int k, int32_t *out, hipStream_t st)
+{
+    constexpr int ROWS_PER_BLOCK = 4 * (64 / LANES);
+    int64_t blocks = (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+    const int64_t cap = 1 << 22;    // one row group per wavefront measured fastest; only absurd sizes loop
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL((route_topk_merge_kernel<LANES, VPL, WAVES>), dim3((unsigned)blocks), dim3(256), 0, st, logits, rows, E, k, out);
+    return launch_status();
+}
+
 template <int LANES, int VPL>
 static int launch_topk_keys(const float *logits, int64_t rows, int E, int k, int32_t *out, hipStream_t st)
 {
@@ -324,10 +464,11 @@ extern "C" int railsched_route_topk(const float *logits, int64_t rows, int32_t E
     if (!logits || !topk_idx) return RAILSCHED_ERR_NULL_PTR;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool vec4 = (E % 4 == 0) && (reinterpret_cast<uintptr_t>(logits) % 16 == 0);
+    if (vec4 && E > 32 && E <= 64 && k <= 8) return launch_topk_merge<4, 16, 6>(logits, rows, E, k, topk_idx, st);
     if (vec4 && E > 32 && E <= 64 && k <= 16) return launch_topk_keys<16, 4>(logits, rows, E, k, topk_idx, st);
-    if (vec4 && E > 64 && E <= 128 && k <= 8) return launch_topk_keys<16, 8>(logits, rows, E, k, topk_idx, st);
+    if (vec4 && E > 64 && E <= 128 && k <= 8) return launch_topk_merge<4, 32, 4>(logits, rows, E, k, topk_idx, st);
     if (vec4 && E > 64 && E <= 128 && k <= 32) return launch_topk_keys<32, 4>(logits, rows, E, k, topk_idx, st);
-    if (vec4 && E > 128 && E <= 256 && k <= 8) return launch_topk_keys<32, 8>(logits, rows, E, k, topk_idx, st);
+    if (vec4 && E > 128 && E <= 256 && k <= 8) return launch_topk_merge<8, 32, 4>(logits, rows, E, k, topk_idx, st);
     if (vec4 && E > 128 && E <= 256 && k <= 64) return launch_topk_keys<64, 4>(logits, rows, E, k, topk_idx, st);
     if (E <= 4) return launch_topk<1, 4>(logits, rows, E, k, topk_idx, st);
     if (E <= 8) return launch_topk<1, 8>(logits, rows, E, k, topk_idx, st);

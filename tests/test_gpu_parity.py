@@ -93,6 +93,17 @@ def test_topk_values_that_differ_in_the_last_bits(E, k):
     assert np.array_equal(got, oracle.route_topk(x, k))
 
 
+@pytest.mark.parametrize("E,k,rows", [(64, 8, 3000), (96, 3, 1111), (128, 8, 2000), (256, 8, 1500), (256, 1, 700), (40, 8, 900)])
+def test_topk_rows_full_of_exact_ties(E, k, rows):
+    # logits on a lattice of 13 values: every row has many equal logits, among the winners and at the cut
+    rng = np.random.default_rng(E * 7 + k)
+    x = (rng.integers(-6, 7, size=(rows, E)) * 0.25).astype(np.float32)
+    x[::7] = 0.0                                                     # whole rows of one value
+    x[1::7, ::2] = -0.0
+    got = rs.route_topk(torch.from_numpy(x).to(DEV), k).cpu().numpy()
+    assert np.array_equal(got, oracle.route_topk(x, k))
+
+
 def test_topk_unaligned_rows_and_empty():
     x = torch.randn(1001 * 8 + 1, device=DEV)[1:].view(1001, 8)   # base pointer off 16-byte alignment
     assert np.array_equal(rs.route_topk(x.contiguous(), 2).cpu().numpy(), oracle.route_topk(x.cpu().numpy(), 2))
