@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Benchmark of the whole rail-spraying path on one MI355X.
+"""Benchmark of the whole rail-spraying path on one MI355X (default: the c2 workload; --config picks another).
 
 A step is one pass of all five stages (route_topk -> traffic_matrix -> chunk_sort -> lpt_spray ->
 eval) over one batch of the Mixtral-8x7B-shaped workload, the first two in one pass over the logits
@@ -31,7 +31,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="c2", help="workload (c1, c2; default c2 = the benchmark workload)")
+    ap.add_argument("--config", default="c2",
+                    help="workload: c2 (default, the benchmark workload) or c1 = whole path with resident logits; c4 = whole path, "
+                         "logits streamed layer by layer; c3, c5 = stages 3-5 on synthetic flow matrices")
+    ap.add_argument("--matrices", type=int, default=0,
+                    help="c3/c5: matrices per step (0 = all of c3, one of c5: a c5 matrix alone is 3.9e9 chunks)")
     ap.add_argument("--cpu-layers", type=int, default=-1,
                     help="layers of the workload the CPU oracle is timed on (-1 = all, 0 = skip)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -55,7 +59,10 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = W.get_config(args.config)
-    assert cfg.kind == "moe"
+    if cfg.kind == "flows":
+        return bench_flows(cfg, args, rs, W, torch, np)
+    if cfg.rows_per_layer * cfg.batch * cfg.E * 4 > 64 << 30:
+        return bench_streamed(cfg, args, rs, W, torch, np)
     topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes, cfg.rail_bw_Bps)
     B, G = cfg.batch, cfg.G
     rows = B * cfg.rows_per_layer
@@ -237,6 +244,124 @@ def main():
                                "sample": f"first {L} of {B} layers ({L * cfg.rows_per_layer} rows, {n_c} chunks), whole path, "
                                          f"{c1 - c0:.2f} s", "matches_gpu": bool(same)}
     print(json.dumps(out))
+
+
+def _events(torch):
+    e = torch.cuda.Event(enable_timing=True)
+    e.record()
+    return e
+
+
+def _stage_rooflines(total_chunks, n_inst, topo, ms, want_perm):
+    """GB/s of stages 3-5 on their algorithmic bytes: D1 read + 8 (12 with perm) B per chunk; 4 + 1 B; 9 B."""
+    NG = topo.rails * topo.G
+    by = {"chunk_sort": 8 * NG * n_inst + (12 if want_perm else 8) * total_chunks,
+          "lpt_spray": 5 * total_chunks, "eval": 9 * total_chunks}
+    return {n: {"GBps": by[n] / (ms[n] * 1e-3) / 1e9, "frac_of_hbm_peak": by[n] / (ms[n] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                "algorithmic_bytes": by[n]} for n in by}
+
+
+def _schedule_steps(rs, torch, plan, D1, topo, B, steps, warmup):
+    names = ("chunk_sort", "lpt_spray", "eval")
+    ms = {n: 0.0 for n in names}
+    for it in range(warmup + steps):
+        e = [_events(torch)]
+        rs.chunk_sort(D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
+        e.append(_events(torch))
+        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S))
+        e.append(_events(torch))
+        rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.rail, plan.S, B, topo, out=(plan.R, plan.stats), ws=plan.ws_eval)
+        e.append(_events(torch))
+        torch.cuda.synchronize()
+        if it >= warmup:
+            for i, n in enumerate(names):
+                ms[n] += e[i].elapsed_time(e[i + 1]) / steps
+    return ms
+
+
+def bench_flows(cfg, args, rs, W, torch, np):
+    """c3 / c5: no routing stage; a step is stages 3-5 over `--matrices` synthetic flow matrices resident in HBM."""
+    dev = "cuda:0"
+    topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes, cfg.rail_bw_Bps)
+    B = args.matrices if args.matrices > 0 else (cfg.batch if cfg.G <= 256 else 1)
+    want_perm = cfg.G <= 256                       # the permutation of a 3.9e9-chunk matrix is left out (16 GB more)
+    D1 = W.gen_flow_matrices_device(cfg, dev, first=0, count=B)
+    total = int(rs.chunk_count(D1, topo)[-1].item())
+    plan = rs.Plan(topo, B, total, dev, want_perm=want_perm)
+    steps, warmup = min(args.steps, 5), min(args.warmup, 2)
+    ms = _schedule_steps(rs, torch, plan, D1, topo, B, steps, warmup)
+    step_ms = sum(ms.values())
+    st = plan.stats.cpu().numpy()
+    ratio = st[:, 0] / np.maximum(st[:, 3], 1)
+    roof = _stage_rooflines(total, B * cfg.M, topo, ms, want_perm)
+    slow = max(ms, key=ms.get)
+    print(json.dumps({
+        "metric": "LPT-sprayed chunks/s over stages 3-5 (chunk_sort, lpt_spray, eval); the workload has no routing stage",
+        "value": total / (step_ms * 1e-3), "unit": "chunks/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64 loads / uint32 weights", "data": "synthetic (seeded lognormal flow matrices)",
+        "config": {"workload": f"{cfg.name}: M={cfg.M} nodes x N={cfg.N} rails, {B} of {cfg.batch} matrices of {cfg.G}x{cfg.G}, "
+                               f"C={cfg.chunk_bytes} B, p_zero={cfg.p_zero}", "chunks": total, "instances": B * cfg.M, "perm": want_perm},
+        "timing": "sum of per-stage event times", "stage_ms": ms, "stage_rooflines": roof,
+        "lpt_spray_chunks_per_s": total / (ms["lpt_spray"] * 1e-3),
+        "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
+        "roofline": {"kernel": slow, "bound": "hbm", "achieved": roof[slow]["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": roof[slow]["frac_of_hbm_peak"], "traffic": None},
+    }))
+
+
+def bench_streamed(cfg, args, rs, W, torch, np):
+    """c4: the logits of all layers do not fit beside the records, so each layer's logits are generated into one
+    buffer (untimed), stages 1-2 are timed per layer, and stages 3-5 run once over all matrices."""
+    dev = "cuda:0"
+    topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes, cfg.rail_bw_Bps)
+    B, G = cfg.batch, cfg.G
+    expert_gpu = torch.from_numpy(W.expert_gpu_table(cfg)).to(dev)
+    D1 = torch.empty((B, G, G), dtype=torch.int64, device=dev)
+    idx = torch.empty((cfg.rows_per_layer, cfg.k), dtype=torch.int32, device=dev)
+    t1 = t2 = 0.0
+    for b in range(B):
+        lg = W.gen_logits(cfg, b, device=dev)
+        if b == 0:
+            rs.route_topk(lg, cfg.k, out=idx)           # warm-up launch
+        e0 = _events(torch)
+        rs.route_topk(lg, cfg.k, out=idx)
+        e1 = _events(torch)
+        rs.traffic_matrix(idx, 1, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=D1[b:b + 1])
+        e2 = _events(torch)
+        torch.cuda.synchronize()
+        t1 += e0.elapsed_time(e1)
+        t2 += e1.elapsed_time(e2)
+        del lg
+    del idx
+    total = int(rs.chunk_count(D1, topo)[-1].item())
+    plan = rs.Plan(topo, B, total, dev, want_perm=True)
+    steps, warmup = min(args.steps, 5), min(args.warmup, 2)
+    ms = _schedule_steps(rs, torch, plan, D1, topo, B, steps, warmup)
+    ms = {"route_topk": t1, "traffic_matrix": t2, **ms}
+    step_ms = sum(ms.values())
+    rows = B * cfg.rows_per_layer
+    k1_bytes = rows * (4 * cfg.E + 4 * cfg.k)
+    k2_bytes = rows * 4 * cfg.k + 8 * B * G * G
+    st = plan.stats.cpu().numpy()
+    ratio = st[:, 0] / np.maximum(st[:, 3], 1)
+    k1_gbps = k1_bytes / (t1 * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "LPT-sprayed chunks/s over the whole path (route_topk, traffic_matrix, chunk_sort, lpt_spray, eval)",
+        "value": total / (step_ms * 1e-3), "unit": "chunks/s", "n_gpus": 1, "steps": 1, "warmup": 1,
+        "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64 loads / uint32 weights / fp32 compare-only", "data": "synthetic (seeded counter-based logits, Zipf expert bias)",
+        "config": {"workload": f"{cfg.name}: M={cfg.M} nodes x N={cfg.N} rails, E={cfg.E} top-{cfg.k}, {cfg.tokens_per_gpu} tokens/GPU x "
+                               f"{cfg.payload_bytes} B, C={cfg.chunk_bytes} B, {B} matrices of {G}x{G}", "rows": rows, "chunks": total,
+                   "instances": B * cfg.M},
+        "timing": "sum of event times: stages 1-2 once per layer (logits regenerated between layers, untimed), stages 3-5 averaged over steps",
+        "stage_ms": ms, "stage_rooflines": _stage_rooflines(total, B * cfg.M, topo, ms, True),
+        "routing_to_traffic_matrix_GBps": (k1_bytes + k2_bytes) / ((t1 + t2) * 1e-3) / 1e9,
+        "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
+        "roofline": {"kernel": "route_topk_merge_kernel", "bound": "hbm", "achieved": k1_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": k1_gbps / HBM_PEAK_GBPS, "traffic": None, "algorithmic_bytes_per_launch": k1_bytes // B,
+                     "avg_launch_ms": t1 / B},
+    }))
 
 
 if __name__ == "__main__":

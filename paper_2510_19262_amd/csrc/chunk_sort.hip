@@ -19,9 +19,8 @@ namespace rs {
 constexpr int kTileMin = 1024;      // full-chunk positions per fill tile: a power of two between these two, chosen per call
 constexpr int kTileMax = 16384;     // so that small batches still spread over a few thousand workgroups
 constexpr int kFillThreads = 256;
-constexpr int kFillStage = 4096;    // flow boundaries staged in LDS per tile
-constexpr int kFillBlocks = 16384;   // most workgroups of one fill launch; LDS admits five per compute unit, so a grid of
-                                    // several rounds evens out what a grid sized to one round leaves to its last, partly filled round
+constexpr int kFillStage = 2048;    // flow boundaries staged in LDS per span (16 KiB with the canonical starts: 8 workgroups per CU)
+constexpr int kFillBlocks = 16384;  // most workgroups of one fill launch: several rounds of the chip, which evens out their ends
 
 struct CsArgs {
     const int64_t *D1;
@@ -229,72 +228,136 @@ __device__ __forceinline__ int last_le(const T *v, int n, uint32_t x)   // last 
     return lo;
 }
 
-// Positions [p0,p1) of one instance's full-chunk region.  Positions are grouped by fours at multiples
-// of four of the global record index, so a thread finds the flow of its first position by binary
-// search, walks to the next flows if its four positions cross a boundary, and stores 16 bytes per array.
+// Full-chunk region of the instances, cut into tiles of a.tile positions; a workgroup takes a contiguous run of
+// tiles, so the instance and the flow its next tile starts in carry over and only its first tile is searched for.
+// A tile is filled in spans: as many flow boundaries as fit are staged in LDS (in rounds of 512, until they reach
+// the tile's end), and the span ends where the staged flows end.  Inside a span positions are grouped by fours at
+// multiples of four of the global record index (16-byte stores); a wavefront walks a contiguous quarter of the
+// groups, 64 at a time, so the flow of its first group is known from the step before, one ballot over the next 64
+// boundaries bounds the flows its 256 positions can lie in, and each lane finishes with a binary search over that
+// handful.
 __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec_ok)
 {
     __shared__ uint32_t st_fs[kFillStage + 1];
     __shared__ uint32_t st_cs[kFillStage];
     if (a.chunk_off[a.n_inst] > a.capacity) return;
     const int64_t n_tiles = a.tile_off[a.n_inst];
-    for (int64_t u = blockIdx.x; u < n_tiles; u += gridDim.x) {
-        const int inst = wave_last_le<int64_t>(a.tile_off, a.n_inst, u);  // tile_off[inst] <= u < tile_off[inst+1]
+    const int64_t u0 = n_tiles * blockIdx.x / gridDim.x, u1 = n_tiles * (blockIdx.x + 1) / gridDim.x;
+    if (u0 >= u1) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int kWaves = kFillThreads / 64;
+    const uint32_t cw = (uint32_t)a.C;
+
+    int inst = wave_last_le<int64_t>(a.tile_off, a.n_inst, u0);          // tile_off[inst] <= u0 < tile_off[inst+1]
+    int64_t t_end = a.tile_off[inst + 1];
+    int fb = -1;                                                         // flow that holds the position before the next span
+    for (int64_t u = u0; u < u1; ++u) {
+        if (u >= t_end) {
+            do { ++inst; t_end = a.tile_off[inst + 1]; } while (u >= t_end);
+            fb = -1;
+        }
         const uint32_t n_full = (uint32_t)a.cnt_full[inst];
-        const uint32_t p0 = (uint32_t)(u - a.tile_off[inst]) * (uint32_t)a.tile;
-        const uint32_t p1 = (n_full - p0 < (uint32_t)a.tile) ? n_full : p0 + (uint32_t)a.tile;
+        const uint32_t t0 = (uint32_t)(u - a.tile_off[inst]) * (uint32_t)a.tile;
+        const uint32_t t1 = (n_full - t0 < (uint32_t)a.tile) ? n_full : t0 + (uint32_t)a.tile;
         const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
         const uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
-        const int f_lo = wave_last_le<uint32_t>(fs, a.NF, p0);
-        const int f_hi = wave_last_le<uint32_t>(fs, a.NF, p1 - 1);
-        const int nf = f_hi - f_lo + 1;
-        const bool staged = nf <= kFillStage;
-        __syncthreads();                                                 // previous tile is done with the stage
-        if (staged) {
-            for (int i = threadIdx.x; i < nf; i += kFillThreads) {
-                st_fs[i] = fs[f_lo + i];
-                if (a.perm) st_cs[i] = cs[f_lo + i];
-            }
-            if (threadIdx.x == 0) st_fs[nf] = 0xFFFFFFFFu;               // nothing starts behind the last staged flow
-        }
-        __syncthreads();
         const int64_t out0 = a.chunk_off[inst];
-        const uint32_t cw = (uint32_t)a.C;
-        if (staged && vec_ok) {
-            const uint32_t head = (uint32_t)((4 - ((out0 + p0) & 3)) & 3);      // scalar positions before the first aligned group
-            const uint32_t pa = (p1 - p0 < head) ? p1 : p0 + head;
-            const uint32_t groups = (p1 - pa) / 4;
-            const uint32_t pb = pa + groups * 4;                                  // scalar positions from here on
-            for (uint32_t g = threadIdx.x; g < groups; g += kFillThreads) {
-                const uint32_t p = pa + 4 * g;
-                int j = last_le(st_fs, nf, p);
-                uint32_t fl[4], pm[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    while (st_fs[j + 1] <= p + e) ++j;
-                    fl[e] = (uint32_t)(f_lo + j);
-                    pm[e] = a.perm ? st_cs[j] + (p + e - st_fs[j]) : 0u;
+        if (fb < 0) fb = wave_last_le<uint32_t>(fs, a.NF, t0);
+
+        uint32_t p0 = t0;
+        while (p0 < t1) {
+            // ---- stage flow starts fb.. until they pass the tile's end, the flows end or the stage is full
+            __syncthreads();                                             // the span before is done with the stage
+            int nf = 0;
+            bool covers = false;
+            while (true) {
+                int want = a.NF - fb - nf;
+                want = want < 512 ? want : 512;
+                want = want < kFillStage - nf ? want : kFillStage - nf;
+                for (int i = threadIdx.x; i < want; i += kFillThreads) {
+                    st_fs[nf + i] = fs[fb + nf + i];
+                    if (a.perm) st_cs[nf + i] = cs[fb + nf + i];
                 }
-                *reinterpret_cast<uint4 *>(a.chunk_w + out0 + p) = make_uint4(cw, cw, cw, cw);
-                *reinterpret_cast<uint4 *>(a.chunk_flow + out0 + p) = make_uint4(fl[0], fl[1], fl[2], fl[3]);
-                if (a.perm) *reinterpret_cast<uint4 *>(a.perm + out0 + p) = make_uint4(pm[0], pm[1], pm[2], pm[3]);
+                __syncthreads();
+                nf += want;
+                covers = (fb + nf >= a.NF) || (st_fs[nf - 1] >= t1);
+                if (covers || nf >= kFillStage) break;
             }
-            // the few positions before the first and behind the last aligned group
-            const uint32_t n_edge = (pa - p0) + (p1 - pb);
-            if (threadIdx.x < n_edge) {
-                const uint32_t p = threadIdx.x < pa - p0 ? p0 + threadIdx.x : pb + (threadIdx.x - (pa - p0));
-                const int j = last_le(st_fs, nf, p);
-                a.chunk_w[out0 + p] = cw;
-                a.chunk_flow[out0 + p] = (uint32_t)(f_lo + j);
-                if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
+            // the span ends at the tile's end, or where the last staged flow starts (it may continue unstaged)
+            uint32_t p1 = t1;
+            if (!covers) {
+                p1 = st_fs[nf - 1];
+                if (p1 <= p0) { fb += nf - 1; continue; }                // a stage full of empty flows: move on in the flows
             }
-        } else {
-            for (uint32_t p = p0 + threadIdx.x; p < p1; p += kFillThreads) {
-                const int f = f_lo + (staged ? last_le(st_fs, nf, p) : last_le(fs + f_lo, nf, p));
-                a.chunk_w[out0 + p] = cw;
-                a.chunk_flow[out0 + p] = (uint32_t)f;
-                if (a.perm) a.perm[out0 + p] = cs[f] + (p - fs[f]);
+            __syncthreads();                                             // everyone has read st_fs[nf-1]
+            if (threadIdx.x == 0) st_fs[nf] = 0xFFFFFFFFu;               // nothing starts behind the staged flows
+            __syncthreads();
+
+            if (vec_ok) {
+                const uint32_t head = (uint32_t)((4 - ((out0 + p0) & 3)) & 3);   // scalar positions before the first aligned group
+                const uint32_t pa = (p1 - p0 < head) ? p1 : p0 + head;
+                const uint32_t groups = (p1 - pa) / 4;
+                const uint32_t pb = pa + groups * 4;                              // scalar positions from here on
+                const uint32_t g0 = (uint32_t)((uint64_t)groups * wave / kWaves), g1 = (uint32_t)((uint64_t)groups * (wave + 1) / kWaves);
+                if (g0 < g1) {
+                    int j_lo = last_le(st_fs, nf, pa + 4 * g0);          // the same in every lane
+                    for (uint32_t gb = g0; gb < g1; gb += 64) {
+                        const bool active = gb + lane < g1;
+                        const uint32_t g = active ? gb + lane : g1 - 1;  // idle lanes shadow the last group
+                        const uint32_t p = pa + 4 * g;
+                        const uint32_t g_last = gb + 63 < g1 ? gb + 63 : g1 - 1;
+                        const uint32_t p_last = pa + 4 * g_last + 3;
+                        // boundaries j_lo+1 .. j_lo+64: those at or below the step's last position form a prefix
+                        const int probe = j_lo + 1 + lane;
+                        const uint32_t pv = probe <= nf ? st_fs[probe] : 0xFFFFFFFFu;
+                        const int inside = __popcll(__ballot(pv <= p_last));
+                        int lo = j_lo, hi = inside < 64 ? j_lo + inside + 1 : nf;   // flow of p lies in [lo, hi)
+                        while (hi - lo > 1) {
+                            const int mid = (lo + hi) >> 1;
+                            if (st_fs[mid] <= p) lo = mid; else hi = mid;
+                        }
+                        int j = lo;
+                        uint32_t nxt = st_fs[j + 1];
+                        uint32_t base = a.perm ? st_cs[j] - st_fs[j] : 0u;       // canonical position = base + p
+                        uint32_t fl[4], pm[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            while (p + e >= nxt) {
+                                ++j;
+                                nxt = st_fs[j + 1];
+                                base = a.perm ? st_cs[j] - st_fs[j] : 0u;
+                            }
+                            fl[e] = (uint32_t)(fb + j);
+                            pm[e] = base + p + e;
+                        }
+                        if (active) {
+                            *reinterpret_cast<uint4 *>(a.chunk_w + out0 + p) = make_uint4(cw, cw, cw, cw);
+                            *reinterpret_cast<uint4 *>(a.chunk_flow + out0 + p) = make_uint4(fl[0], fl[1], fl[2], fl[3]);
+                            if (a.perm) *reinterpret_cast<uint4 *>(a.perm + out0 + p) = make_uint4(pm[0], pm[1], pm[2], pm[3]);
+                        }
+                        j_lo = __builtin_amdgcn_readlane(j, 63);         // flow of the step's last position
+                    }
+                }
+                // the few positions before the first and behind the last aligned group
+                const uint32_t n_edge = (pa - p0) + (p1 - pb);
+                if (threadIdx.x < n_edge) {
+                    const uint32_t p = threadIdx.x < pa - p0 ? p0 + threadIdx.x : pb + (threadIdx.x - (pa - p0));
+                    const int j = last_le(st_fs, nf, p);
+                    a.chunk_w[out0 + p] = cw;
+                    a.chunk_flow[out0 + p] = (uint32_t)(fb + j);
+                    if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
+                }
+            } else {
+                for (uint32_t p = p0 + threadIdx.x; p < p1; p += kFillThreads) {
+                    const int j = last_le(st_fs, nf, p);
+                    a.chunk_w[out0 + p] = cw;
+                    a.chunk_flow[out0 + p] = (uint32_t)(fb + j);
+                    if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
+                }
             }
+            // the next span starts in the flow that holds position p1 - 1
+            fb += last_le(st_fs, nf, p1 - 1);
+            p0 = p1;
         }
     }
 }
