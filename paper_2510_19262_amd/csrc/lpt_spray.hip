@@ -224,29 +224,42 @@ __global__ __launch_bounds__(kPfThreads) void lpt_prefix_kernel(const int64_t *_
             const uint32_t w0 = s_w0[0];
             int64_t miss = INT64_MAX;
             constexpr int U = 4;
-            for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPfThreads * 4 * U) {
-                u32x4 v[U];
+            // memory operations of a wavefront complete in order, so the loads of the next step are issued ahead of
+            // this step's stores instead of behind them
+            int64_t p = t0 + (int64_t)threadIdx.x * 4;
+            u32x4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t pu = p + (int64_t)u * kPfThreads * 4;
+                v[u] = pu < t1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(chunk_w + pu)) : u32x4{w0, w0, w0, w0};
+            }
+            while (p < t1) {
+                uint32_t packed[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const int64_t pu = p + (int64_t)u * kPfThreads * 4;
+                    const int64_t i = p + (int64_t)u * kPfThreads * 4 - b;
+                    uint32_t r0 = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
+                    packed[u] = r0;
+#pragma unroll
+                    for (int e = 1; e < 4; ++e) {
+                        r0 = (r0 + 1 == (uint32_t)N) ? 0u : r0 + 1;
+                        packed[u] |= r0 << (8 * e);
+                    }
+                    const int first = v[u].x != w0 ? 0 : v[u].y != w0 ? 1 : v[u].z != w0 ? 2 : v[u].w != w0 ? 3 : -1;
+                    if (first >= 0 && i + first < miss) miss = i + first;          // padded lanes hold w0: never a miss
+                }
+                const int64_t pn = p + (int64_t)kPfThreads * 4 * U;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t pu = pn + (int64_t)u * kPfThreads * 4;
                     v[u] = pu < t1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(chunk_w + pu)) : u32x4{w0, w0, w0, w0};
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int64_t pu = p + (int64_t)u * kPfThreads * 4;
-                    if (pu >= t1) break;
-                    const int64_t i = pu - b;
-                    uint32_t r0 = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
-                    uint32_t packed = r0;
-#pragma unroll
-                    for (int e = 1; e < 4; ++e) {
-                        r0 = (r0 + 1 == (uint32_t)N) ? 0u : r0 + 1;
-                        packed |= r0 << (8 * e);
-                    }
-                    const int first = v[u].x != w0 ? 0 : v[u].y != w0 ? 1 : v[u].z != w0 ? 2 : v[u].w != w0 ? 3 : -1;
-                    if (first >= 0 && i + first < miss) miss = i + first;
-                    __builtin_nontemporal_store(packed, reinterpret_cast<uint32_t *>(rail + pu));
+                    if (pu < t1) __builtin_nontemporal_store(packed[u], reinterpret_cast<uint32_t *>(rail + pu));
                 }
+                p = pn;
             }
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) { const int64_t o = __shfl_xor(miss, d); miss = o < miss ? o : miss; }
