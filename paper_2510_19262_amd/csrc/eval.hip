@@ -4,8 +4,8 @@
 // Rail n of a source node ends on NIC n of the destination node (one-to-one rail mapping used in the
 // proof of Theorem 3), so R[b][f][n] is the sum of the weights of all chunks of matrix b whose
 // destination GPU lies in node f and that were assigned to rail n - whatever their source node.
-// Kernel 1: the chunk range of matrix b is cut into `slices` equal parts; one workgroup streams a
-// part (9 bytes per chunk), accumulates the G = M*N receive bins in LDS and writes them, plus the
+// Kernel 1: the chunk range of matrix b is dealt in rounds to `slices` workgroups; one workgroup streams its
+// share (9 bytes per chunk), accumulates the G = M*N receive bins in LDS and writes them, plus the
 // largest weight it saw, to its own slot of the workspace with plain stores.
 // Kernel 2: one workgroup per matrix adds the slots and derives the statistics from S (as produced by
 // stage 4) and R.  No global atomics anywhere; all sums are integer, so their order cannot matter.
@@ -25,6 +25,7 @@ struct EvArgs {
     int32_t M, N, G, slices;
     int32_t nshift, gmask;   // >= 0 when N / G are powers of two
     int32_t wide_ok;         // record arrays aligned for 16-byte (weights, flows) and 4-byte (rails) loads
+    int32_t copies;          // LDS copies of the receive bins (power of two); lanes that would add to one bin use different ones
 };
 
 __device__ __forceinline__ int dst_node(const EvArgs &a, uint32_t flow)
@@ -36,16 +37,21 @@ __device__ __forceinline__ int dst_node(const EvArgs &a, uint32_t flow)
 
 __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
 {
-    extern __shared__ unsigned long long ev_bins[];                     // [G]
+    // [copies][G + 1] 64-bit bins.  Consecutive records mostly go to one destination node and cycle through the
+    // rails, so the lanes of a wavefront would pile onto a handful of bins; lanes take different copies instead, and
+    // the odd stride puts a bin's copies in different banks.
+    extern __shared__ unsigned long long ev_all[];
     __shared__ unsigned ev_wmax;
     const int b = blockIdx.y, t = blockIdx.x;
-    for (int i = threadIdx.x; i < a.G; i += kEvThreads) ev_bins[i] = 0;
+    const int stride = a.G + 1;
+    for (int i = threadIdx.x; i < stride * a.copies; i += kEvThreads) ev_all[i] = 0;
     if (threadIdx.x == 0) ev_wmax = 0;
     __syncthreads();
+    unsigned long long *ev_bins = ev_all + (size_t)(((threadIdx.x & 63) >> 1) & (a.copies - 1)) * stride;
 
-    const int64_t lo_m = a.chunk_off[(int64_t)b * a.M], hi_m = a.chunk_off[(int64_t)(b + 1) * a.M];
-    const int64_t n = hi_m - lo_m;
-    const int64_t lo = lo_m + n * t / a.slices, hi = lo_m + n * (t + 1) / a.slices;
+    // matrix b's records are dealt to its `slices` workgroups in rounds of kEvThreads*4, so the workgroups, which run
+    // side by side, read one compact window of the arrays at any time
+    const int64_t lo = a.chunk_off[(int64_t)b * a.M], hi = a.chunk_off[(int64_t)(b + 1) * a.M];
     unsigned wmax = 0;
     auto one = [&](uint32_t w, uint32_t flow, unsigned r) {
         const int f = dst_node(a, flow);
@@ -55,24 +61,30 @@ __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
     // whole groups of four records at multiples of four: 16-byte loads of weight and flow, 4 bytes of rails
     const int64_t alo = a.wide_ok ? ((lo + 3) & ~int64_t(3)) : hi, ahi = a.wide_ok ? (hi & ~int64_t(3)) : hi;
     if (alo < ahi) {
-        for (int64_t i = alo + (int64_t)threadIdx.x * 4; i < ahi; i += (int64_t)kEvThreads * 4) {
+        const int64_t round = (int64_t)a.slices * kEvThreads * 4;
+        for (int64_t i = alo + ((int64_t)t * kEvThreads + threadIdx.x) * 4; i < ahi; i += round) {
             const uint4 w = *reinterpret_cast<const uint4 *>(a.chunk_w + i);
             const uint4 fl = *reinterpret_cast<const uint4 *>(a.chunk_flow + i);
             const uint32_t rr = *reinterpret_cast<const uint32_t *>(a.rail + i);
             one(w.x, fl.x, rr & 255u); one(w.y, fl.y, (rr >> 8) & 255u); one(w.z, fl.z, (rr >> 16) & 255u); one(w.w, fl.w, rr >> 24);
         }
         const int64_t n_edge = (alo - lo) + (hi - ahi);                 // at most 6 records outside the aligned span
-        if ((int64_t)threadIdx.x < n_edge) {
+        if (t == 0 && (int64_t)threadIdx.x < n_edge) {
             const int64_t i = (int64_t)threadIdx.x < alo - lo ? lo + threadIdx.x : ahi + (threadIdx.x - (alo - lo));
             one(a.chunk_w[i], a.chunk_flow[i], a.rail[i]);
         }
     } else {
-        for (int64_t i = lo + threadIdx.x; i < hi; i += kEvThreads) one(a.chunk_w[i], a.chunk_flow[i], a.rail[i]);
+        for (int64_t i = lo + (int64_t)t * kEvThreads + threadIdx.x; i < hi; i += (int64_t)a.slices * kEvThreads)
+            one(a.chunk_w[i], a.chunk_flow[i], a.rail[i]);
     }
     atomicMax(&ev_wmax, wmax);
     __syncthreads();
     int64_t *slot = a.partial + ((int64_t)b * a.slices + t) * (a.G + 1);
-    for (int i = threadIdx.x; i < a.G; i += kEvThreads) slot[i] = (int64_t)ev_bins[i];
+    for (int i = threadIdx.x; i < a.G; i += kEvThreads) {
+        unsigned long long sum = 0;
+        for (int c = 0; c < a.copies; ++c) sum += ev_all[(size_t)c * stride + i];
+        slot[i] = (int64_t)sum;
+    }
     if (threadIdx.x == 0) slot[a.G] = (int64_t)ev_wmax;
 }
 
@@ -211,7 +223,9 @@ extern "C" int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w,
     a.wide_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(chunk_flow) % 16 == 0 &&
                  reinterpret_cast<uintptr_t>(rail) % 4 == 0) ? 1 : 0;
 
-    const size_t lds = sizeof(unsigned long long) * (size_t)a.G;
+    a.copies = 16;
+    while (a.copies > 1 && sizeof(unsigned long long) * (size_t)(a.G + 1) * a.copies > 40 * 1024) a.copies /= 2;
+    const size_t lds = sizeof(unsigned long long) * (size_t)(a.G + 1) * a.copies;
     if (lds > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(eval_partial_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds) != hipSuccess)
