@@ -178,6 +178,23 @@ int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w, const uint
                    int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Stages 3-5 in one call (Algorithm 2 steps 1-3 and 6; Section 4.1 S and R; Theorems 2-3): the outputs of
+ * railsched_chunk_sort, railsched_lpt_spray and railsched_eval run one after the other on the same
+ * arguments, bit for bit.  Batches of at most 1024 instances with N*G <= 2048 flows and
+ * capacity <= 32768 chunks per instance take three launches instead of nine (one workgroup per instance
+ * does the instance's split, sort, allocation and receive loads); all others run the three stages.
+ *   D1 [batch][G][G] int64 (in);  chunk_off [batch*M+1];  chunk_w, chunk_flow, perm (perm may be NULL),
+ *   rail: `capacity` records each;  S, R [batch][M][N] int64;  stats [batch][8] int64   (out)
+ *   ws: railsched_schedule_workspace_bytes(batch, topo) bytes, 256-byte aligned.
+ * If chunk_off[batch*M] > capacity the record arrays are left alone and S, R, stats are undefined.
+ * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (as the three stages), WORKSPACE.
+ * ------------------------------------------------------------------------------------------- */
+size_t railsched_schedule_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo);
+int railsched_schedule(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off,
+                       uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm, int64_t capacity, uint8_t *rail,
+                       int64_t *S, int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Second all-to-all of an MoE layer (Algorithm 1 step 4: expert outputs return to the token owners):
  * its traffic is the first one's reversed, D1T[b][d][s] = D1[b][s][d]; stages 3-5 then run on D1T.
  *   D1, D1T [batch][G][G] int64, distinct buffers.

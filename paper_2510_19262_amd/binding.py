@@ -22,7 +22,7 @@ EXPORTS = (
     "railsched_version", "railsched_strerror", "railsched_route_topk", "railsched_traffic_matrix",
     "railsched_route_traffic_workspace_bytes", "railsched_route_traffic",
     "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray", "railsched_lpt_spray_chunkwise",
-    "railsched_eval_workspace_bytes", "railsched_eval", "railsched_transpose_matrix", "railsched_assign_policy",
+    "railsched_eval_workspace_bytes", "railsched_eval", "railsched_schedule_workspace_bytes", "railsched_schedule", "railsched_transpose_matrix", "railsched_assign_policy",
     "railsched_port_round_robin_workspace_bytes", "railsched_port_round_robin",
 )
 
@@ -86,6 +86,9 @@ def load():
     lib.railsched_eval_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_eval_workspace_bytes.restype = SZ
     lib.railsched_eval.argtypes = [P, P, P, P, P, I32, TP, P, P, P, SZ, P]
+    lib.railsched_schedule_workspace_bytes.argtypes = [I32, TP]
+    lib.railsched_schedule_workspace_bytes.restype = SZ
+    lib.railsched_schedule.argtypes = [P, I32, TP, P, P, P, P, I64, P, P, P, P, P, SZ, P]
     lib.railsched_transpose_matrix.argtypes = [P, I32, TP, P, P]
     lib.railsched_assign_policy.argtypes = [I32, C.c_uint64, P, P, P, I32, TP, P, P, P]
     lib.railsched_port_round_robin_workspace_bytes.argtypes = [I32, TP, I64]
@@ -325,6 +328,32 @@ def assign_policy(policy, seed: int, chunk_off, chunk_w, chunk_flow, batch: int,
 
 
 # ---------------------------------------------------------------------------------- whole path
+def schedule_workspace_bytes(batch: int, topo: Topo) -> int:
+    t = topo.c()
+    return int(load().railsched_schedule_workspace_bytes(batch, C.byref(t)))
+
+
+def schedule(D1: torch.Tensor, topo: Topo, capacity: int, want_perm: bool = True, out=None, ws: Optional[torch.Tensor] = None):
+    """Stages 3-5 in one call: (chunk_off, chunk_w, chunk_flow, perm, rail, S, R, stats)."""
+    _dev(D1, torch.int64, "D1")
+    batch = D1.shape[0]
+    M, N = topo.nodes, topo.rails
+    dev = D1.device
+    if out is None:
+        n = max(capacity, 1)
+        out = (torch.empty(batch * M + 1, dtype=torch.int64, device=dev), torch.empty(n, dtype=torch.int32, device=dev),
+               torch.empty(n, dtype=torch.int32, device=dev), torch.empty(n, dtype=torch.int32, device=dev) if want_perm else None,
+               torch.empty(n, dtype=torch.uint8, device=dev), torch.empty((batch, M, N), dtype=torch.int64, device=dev),
+               torch.empty((batch, M, N), dtype=torch.int64, device=dev), torch.empty((batch, 8), dtype=torch.int64, device=dev))
+    off, w, flow, perm, rail, S, R, stats = out
+    if ws is None:
+        ws = _ws(schedule_workspace_bytes(batch, topo), dev)
+    t = topo.c()
+    _check(load().railsched_schedule(_ptr(D1), batch, C.byref(t), _ptr(off), _ptr(w), _ptr(flow), _ptr(perm), capacity, _ptr(rail),
+                                     _ptr(S), _ptr(R), _ptr(stats), _ptr(ws), ws.numel(), _stream()), "railsched_schedule")
+    return out
+
+
 class Plan:
     """Preallocated buffers for repeated passes of the whole path over same-shaped batches
     (no allocation and no host synchronisation inside step())."""
@@ -345,11 +374,19 @@ class Plan:
         self.stats = torch.empty((batch, 8), dtype=i64, device=device)
         self.ws_sort = _ws(chunk_sort_workspace_bytes(batch, topo), device)
         self.ws_eval = _ws(eval_workspace_bytes(batch, topo), device)
+        self.ws_sched = _ws(schedule_workspace_bytes(batch, topo), device)
 
     def route(self, logits, tokens_per_gpu, expert_gpu, payload_bytes):
         route_topk(logits, self.topk_idx.shape[1], out=self.topk_idx)
         traffic_matrix(self.topk_idx, self.batch, tokens_per_gpu, expert_gpu, payload_bytes, self.topo, out=self.D1)
         return self.D1
+
+    def schedule_one_call(self, D1=None):
+        """Stages 3-5 through railsched_schedule (same outputs as schedule())."""
+        D1 = self.D1 if D1 is None else D1
+        schedule(D1, self.topo, self.capacity, out=(self.chunk_off, self.chunk_w, self.chunk_flow, self.perm, self.rail, self.S,
+                                                   self.R, self.stats), ws=self.ws_sched)
+        return self.stats
 
     def schedule(self, D1=None):
         D1 = self.D1 if D1 is None else D1

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librailsched.so")
-SOURCES = ["api.hip", "route_topk.hip", "traffic_matrix.hip", "route_traffic.hip", "chunk_sort.hip", "lpt_spray.hip", "eval.hip", "extras.hip"]
+SOURCES = ["api.hip", "route_topk.hip", "traffic_matrix.hip", "route_traffic.hip", "chunk_sort.hip", "lpt_spray.hip", "eval.hip", "schedule.hip", "extras.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -1,0 +1,138 @@
+// Device-side pieces of stage 3 (Section 5.1 "Flow Splitting and Atomicity"; Algorithm 2 steps 1-2) shared by
+// the stage-3 kernels and by the one-call scheduler of small batches.
+#pragma once
+
+#include "common.h"
+
+namespace rs {
+
+struct CsArgs {
+    const int64_t *D1;
+    int64_t *chunk_off;
+    uint32_t *chunk_w, *chunk_flow, *perm;
+    int64_t capacity;
+    int64_t *cnt_all, *cnt_full, *tile_off;
+    uint32_t *full_start, *canon_start;
+    int64_t C;
+    int32_t cshift;      // >= 0 when C is a power of two
+    int32_t M, N, G, NF, intra;
+    int32_t n_inst;
+    int32_t tile;        // full-chunk positions per fill tile
+};
+
+__device__ __forceinline__ void split_bytes(const CsArgs &a, int64_t B, uint32_t &q, uint32_t &r)
+{
+    if (B < 0) B = 0;
+    if (a.cshift >= 0) {
+        q = (uint32_t)(B >> a.cshift);
+        r = (uint32_t)(B & (a.C - 1));
+    } else {
+        const uint64_t qq = (uint64_t)B / (uint64_t)a.C;
+        q = (uint32_t)qq;
+        r = (uint32_t)((uint64_t)B - qq * (uint64_t)a.C);
+    }
+}
+
+// bytes of flow f of instance (b, k); 0 for destinations inside node k unless intra-node traffic is kept
+__device__ __forceinline__ int64_t flow_bytes(const CsArgs &a, const int64_t *rows, int k, int f)
+{
+    const int dst = f % a.G;
+    if (!a.intra && dst / a.N == k) return 0;
+    return rows[f];
+}
+
+__device__ __forceinline__ unsigned wave_exscan(unsigned v, unsigned &total)
+{
+    const int lane = threadIdx.x & 63;
+    unsigned inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned o = __shfl_up(inc, d);
+        if (lane >= d) inc += o;
+    }
+    total = __shfl(inc, 63);
+    return inc - v;
+}
+
+// Ordering point between LDS accesses of the lanes of ONE wavefront.  When the wavefront is the whole
+// workgroup a workgroup barrier does; when other wavefronts of the workgroup are busy elsewhere, waiting
+// for the wavefront's own LDS operations is enough (LDS executes a wavefront's operations in order) and
+// the asm statement keeps the compiler from moving LDS accesses across it.
+template <bool ONE_WAVE_BLOCK>
+__device__ __forceinline__ void lds_sync()
+{
+    if constexpr (ONE_WAVE_BLOCK) __syncthreads();
+    else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+
+// Tails (B mod C > 0) of the flows of one instance, sorted by weight descending, ties in canonical (flow) order:
+// stable LSD radix sort by one wavefront in LDS, 8-bit digits over the span of key bits that differ at all,
+// ranks inside a batch of 64 from ballot matching.  rem[NF] receives every flow's tail bytes, hist[256] is
+// scratch, idx_a/idx_b[NF] are ping-pong arrays of flow ids; returns the array that holds the sorted ids and
+// their number in nt.
+template <bool ONE_WAVE_BLOCK>
+__device__ __forceinline__ unsigned short *tail_sort_wave(const CsArgs &a, const int64_t *rows, int k, unsigned *rem, unsigned *hist,
+                                                          unsigned short *idx_a, unsigned short *idx_b, int &nt_out)
+{
+    const int lane = threadIdx.x & 63;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    // tails in canonical order; which key bits differ at all between them
+    int nt = 0;
+    unsigned any1 = 0u, all1 = 0xFFFFFFFFu;
+    for (int f0 = 0; f0 < a.NF; f0 += 64) {
+        const int f = f0 + lane;
+        uint32_t q = 0, r = 0;
+        if (f < a.NF) { split_bytes(a, flow_bytes(a, rows, k, f), q, r); rem[f] = r; }
+        const unsigned long long m = __ballot(r != 0);
+        if (r) { idx_a[nt + __popcll(m & lt)] = (unsigned short)f; any1 |= r; all1 &= r; }
+        nt += __popcll(m);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) { any1 |= (unsigned)__shfl_xor((int)any1, d); all1 &= (unsigned)__shfl_xor((int)all1, d); }
+    lds_sync<ONE_WAVE_BLOCK>();
+    // bits that are equal in every key cannot change the order: sort on the span of differing bits only
+    // (token payloads make tails multiples of some power of two, so the span is usually one digit wide)
+    const unsigned diff = any1 ^ all1;
+    const int lo_bit = diff ? __ffs((int)diff) - 1 : 0;
+    const int n_pass = (nt > 1 && diff) ? (32 - __clz((int)diff) - lo_bit + 7) / 8 : 0;
+
+    for (int pass = 0; pass < n_pass; ++pass) {
+        const int shift = lo_bit + 8 * pass;
+        for (int i = lane; i < 256; i += 64) hist[i] = 0;
+        lds_sync<ONE_WAVE_BLOCK>();
+        for (int i = lane; i < nt; i += 64) atomicAdd(&hist[255u - ((rem[idx_a[i]] >> shift) & 255u)], 1u);
+        lds_sync<ONE_WAVE_BLOCK>();
+        {   // exclusive scan of the 256 buckets: four per lane
+            const unsigned h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+            unsigned tot;
+            const unsigned ex = wave_exscan(h0 + h1 + h2 + h3, tot);
+            lds_sync<ONE_WAVE_BLOCK>();
+            hist[4 * lane] = ex; hist[4 * lane + 1] = ex + h0; hist[4 * lane + 2] = ex + h0 + h1; hist[4 * lane + 3] = ex + h0 + h1 + h2;
+        }
+        lds_sync<ONE_WAVE_BLOCK>();
+        for (int i0 = 0; i0 < nt; i0 += 64) {                            // batches in order keep the sort stable
+            const int i = i0 + lane;
+            const bool act = i < nt;
+            const unsigned short f = act ? idx_a[i] : 0;
+            const unsigned d = act ? 255u - ((rem[f] >> shift) & 255u) : 0u;
+            unsigned long long peers = __ballot(act);
+#pragma unroll
+            for (int bit = 0; bit < 8; ++bit) {
+                const bool one = (d >> bit) & 1u;
+                const unsigned long long bm = __ballot(act && one);
+                peers &= one ? bm : ~bm;
+            }
+            const unsigned base = act ? hist[d] : 0u;
+            if (act) idx_b[base + __popcll(peers & lt)] = f;
+            lds_sync<ONE_WAVE_BLOCK>();
+            if (act && (peers >> lane) == 1ull) hist[d] = base + __popcll(peers);   // highest lane of the peer set
+            lds_sync<ONE_WAVE_BLOCK>();
+        }
+        unsigned short *t = idx_a; idx_a = idx_b; idx_b = t;
+    }
+
+    nt_out = nt;
+    return idx_a;
+}
+
+}  // namespace rs

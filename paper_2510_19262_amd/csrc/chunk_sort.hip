@@ -13,6 +13,7 @@
 // An instance (matrix b, node k) owns the N consecutive rows k*N..k*N+N-1 of D1[b]; read as one
 // array of N*G entries its index is exactly the canonical flow id n*G + dst.
 #include "common.h"
+#include "chunk_core.h"
 
 namespace rs {
 
@@ -21,54 +22,6 @@ constexpr int kTileMax = 16384;     // so that small batches still spread over a
 constexpr int kFillThreads = 256;
 constexpr int kFillStage = 2048;    // flow boundaries staged in LDS per span (16 KiB with the canonical starts: 8 workgroups per CU)
 constexpr int kFillBlocks = 16384;  // most workgroups of one fill launch: several rounds of the chip, which evens out their ends
-
-struct CsArgs {
-    const int64_t *D1;
-    int64_t *chunk_off;
-    uint32_t *chunk_w, *chunk_flow, *perm;
-    int64_t capacity;
-    int64_t *cnt_all, *cnt_full, *tile_off;
-    uint32_t *full_start, *canon_start;
-    int64_t C;
-    int32_t cshift;      // >= 0 when C is a power of two
-    int32_t M, N, G, NF, intra;
-    int32_t n_inst;
-    int32_t tile;        // full-chunk positions per fill tile
-};
-
-__device__ __forceinline__ void split_bytes(const CsArgs &a, int64_t B, uint32_t &q, uint32_t &r)
-{
-    if (B < 0) B = 0;
-    if (a.cshift >= 0) {
-        q = (uint32_t)(B >> a.cshift);
-        r = (uint32_t)(B & (a.C - 1));
-    } else {
-        const uint64_t qq = (uint64_t)B / (uint64_t)a.C;
-        q = (uint32_t)qq;
-        r = (uint32_t)((uint64_t)B - qq * (uint64_t)a.C);
-    }
-}
-
-// bytes of flow f of instance (b, k); 0 for destinations inside node k unless intra-node traffic is kept
-__device__ __forceinline__ int64_t flow_bytes(const CsArgs &a, const int64_t *rows, int k, int f)
-{
-    const int dst = f % a.G;
-    if (!a.intra && dst / a.N == k) return 0;
-    return rows[f];
-}
-
-__device__ __forceinline__ unsigned wave_exscan(unsigned v, unsigned &total)
-{
-    const int lane = threadIdx.x & 63;
-    unsigned inc = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const unsigned o = __shfl_up(inc, d);
-        if (lane >= d) inc += o;
-    }
-    total = __shfl(inc, 63);
-    return inc - v;
-}
 
 // ---- A: per-instance chunk counts and the two exclusive scans over its flows -----------------
 __global__ __launch_bounds__(64) void cs_count_kernel(CsArgs a)
@@ -143,63 +96,11 @@ __global__ __launch_bounds__(64) void cs_tail_kernel(CsArgs a)
     const int inst = blockIdx.x;
     const int b = inst / a.M, k = inst % a.M;
     const int lane = threadIdx.x;
-    const unsigned long long lt = (1ull << lane) - 1ull;
     const int64_t *rows = a.D1 + ((int64_t)b * a.G + (int64_t)k * a.N) * a.G;
 
-    // tails in canonical order; which key bits differ at all between them
     int nt = 0;
-    unsigned any1 = 0u, all1 = 0xFFFFFFFFu;
-    for (int f0 = 0; f0 < a.NF; f0 += 64) {
-        const int f = f0 + lane;
-        uint32_t q = 0, r = 0;
-        if (f < a.NF) { split_bytes(a, flow_bytes(a, rows, k, f), q, r); rem[f] = r; }
-        const unsigned long long m = __ballot(r != 0);
-        if (r) { idx_a[nt + __popcll(m & lt)] = (unsigned short)f; any1 |= r; all1 &= r; }
-        nt += __popcll(m);
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) { any1 |= (unsigned)__shfl_xor((int)any1, d); all1 &= (unsigned)__shfl_xor((int)all1, d); }
-    __syncthreads();
-    // bits that are equal in every key cannot change the order: sort on the span of differing bits only
-    // (token payloads make tails multiples of some power of two, so the span is usually one digit wide)
-    const unsigned diff = any1 ^ all1;
-    const int lo_bit = diff ? __ffs((int)diff) - 1 : 0;
-    const int n_pass = (nt > 1 && diff) ? (32 - __clz((int)diff) - lo_bit + 7) / 8 : 0;
-
-    for (int pass = 0; pass < n_pass; ++pass) {
-        const int shift = lo_bit + 8 * pass;
-        for (int i = lane; i < 256; i += 64) hist[i] = 0;
-        __syncthreads();
-        for (int i = lane; i < nt; i += 64) atomicAdd(&hist[255u - ((rem[idx_a[i]] >> shift) & 255u)], 1u);
-        __syncthreads();
-        {   // exclusive scan of the 256 buckets: four per lane
-            const unsigned h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-            unsigned tot;
-            const unsigned ex = wave_exscan(h0 + h1 + h2 + h3, tot);
-            __syncthreads();
-            hist[4 * lane] = ex; hist[4 * lane + 1] = ex + h0; hist[4 * lane + 2] = ex + h0 + h1; hist[4 * lane + 3] = ex + h0 + h1 + h2;
-        }
-        __syncthreads();
-        for (int i0 = 0; i0 < nt; i0 += 64) {                            // batches in order keep the sort stable
-            const int i = i0 + lane;
-            const bool act = i < nt;
-            const unsigned short f = act ? idx_a[i] : 0;
-            const unsigned d = act ? 255u - ((rem[f] >> shift) & 255u) : 0u;
-            unsigned long long peers = __ballot(act);
-#pragma unroll
-            for (int bit = 0; bit < 8; ++bit) {
-                const bool one = (d >> bit) & 1u;
-                const unsigned long long bm = __ballot(act && one);
-                peers &= one ? bm : ~bm;
-            }
-            const unsigned base = act ? hist[d] : 0u;
-            if (act) idx_b[base + __popcll(peers & lt)] = f;
-            __syncthreads();
-            if (act && (peers >> lane) == 1ull) hist[d] = base + __popcll(peers);   // highest lane of the peer set
-            __syncthreads();
-        }
-        unsigned short *t = idx_a; idx_a = idx_b; idx_b = t;
-    }
+    unsigned short *sorted = tail_sort_wave<true>(a, rows, k, rem, hist, idx_a, idx_b, nt);
+    idx_a = sorted;
 
     const int64_t out0 = a.chunk_off[inst] + a.cnt_full[inst];
     const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
@@ -371,6 +272,13 @@ static void ws_layout(int64_t n_inst, int64_t NF, size_t off[6])
     off[3] = o; o += align_up(sizeof(uint32_t) * (size_t)(n_inst * NF), 256);  // full_start
     off[4] = o; o += align_up(sizeof(uint32_t) * (size_t)(n_inst * NF), 256);  // canon_start
     off[5] = o;
+}
+
+// entry points for the one-call scheduler (schedule.hip)
+void cs_ws_layout(int64_t n_inst, int64_t NF, size_t off[6]) { ws_layout(n_inst, NF, off); }
+void launch_cs_count(const CsArgs &a, hipStream_t st)
+{
+    hipLaunchKernelGGL(cs_count_kernel, dim3((unsigned)a.n_inst), dim3(64), 0, st, a);
 }
 
 }  // namespace rs

@@ -10,30 +10,9 @@
 // Kernel 2: one workgroup per matrix adds the slots and derives the statistics from S (as produced by
 // stage 4) and R.  No global atomics anywhere; all sums are integer, so their order cannot matter.
 #include "common.h"
+#include "eval_core.h"
 
 namespace rs {
-
-constexpr int kEvThreads = 256;
-
-struct EvArgs {
-    const int64_t *chunk_off;
-    const uint32_t *chunk_w, *chunk_flow;
-    const uint8_t *rail;
-    const int64_t *S;
-    int64_t *R, *stats;
-    int64_t *partial;        // [batch][slices][G + 1]
-    int32_t M, N, G, slices;
-    int32_t nshift, gmask;   // >= 0 when N / G are powers of two
-    int32_t wide_ok;         // record arrays aligned for 16-byte (weights, flows) and 4-byte (rails) loads
-    int32_t copies;          // LDS copies of the receive bins (power of two); lanes that would add to one bin use different ones
-};
-
-__device__ __forceinline__ int dst_node(const EvArgs &a, uint32_t flow)
-{
-    // flow = n*G + dst  ->  dst / N
-    if (a.gmask >= 0 && a.nshift >= 0) return (int)((flow & (uint32_t)a.gmask) >> a.nshift);
-    return (int)((flow % (uint32_t)a.G) / (uint32_t)a.N);
-}
 
 __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
 {
@@ -178,6 +157,12 @@ __global__ __launch_bounds__(kRedThreads) void eval_reduce_kernel(EvArgs a)
         st[6] = a.chunk_off[(int64_t)(b + 1) * a.M] - a.chunk_off[(int64_t)b * a.M];
         st[7] = spread;
     }
+}
+
+int launch_eval_reduce(const EvArgs &a, int batch, hipStream_t st)
+{
+    hipLaunchKernelGGL(eval_reduce_kernel, dim3((unsigned)batch), dim3(kRedThreads), 0, st, a);
+    return launch_status();
 }
 
 static int eval_slices(int32_t batch)

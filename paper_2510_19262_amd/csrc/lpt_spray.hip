@@ -30,138 +30,9 @@
 // every lane group, all 64 lanes streaming weights and writing rails - the shape for few instances,
 // where the latency of the chain and of HBM is the limit and more wavefronts hide more of it.
 #include "common.h"
+#include "lpt_core.h"
 
 namespace rs {
-
-constexpr int kBatch = 32;          // packed shape: chunks per period and instance (64 when a group is a whole wave)
-constexpr int kLptWaves = 4;        // wavefronts per workgroup
-constexpr int kWideDepth = 4;       // wide shape: periods of 64 chunks in flight per wavefront
-
-template <int GW> struct GroupBits;
-template <> struct GroupBits<4> { static constexpr int S = 2; };
-template <> struct GroupBits<8> { static constexpr int S = 3; };
-template <> struct GroupBits<16> { static constexpr int S = 4; };
-template <> struct GroupBits<32> { static constexpr int S = 5; };
-template <> struct GroupBits<64> { static constexpr int S = 6; };
-
-template <int CTRL>
-__device__ __forceinline__ unsigned dpp_mov(unsigned v)
-{
-    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
-}
-
-// min(v, v of the partner lane).  The partner value is fetched with "old" = UINT_MAX, the identity
-// of unsigned min, which lets the compiler fold the lane exchange into one v_min_u32 with a DPP operand.
-template <int CTRL>
-__device__ __forceinline__ unsigned dpp_min(unsigned v)
-{
-    return min(v, (unsigned)__builtin_amdgcn_update_dpp((int)0xFFFFFFFF, (int)v, CTRL, 0xF, 0xF, false));
-}
-template <int CTRL>
-__device__ __forceinline__ unsigned dpp_max(unsigned v)
-{
-    return max(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false));
-}
-
-template <int GW>
-__device__ __forceinline__ unsigned group_min_u32(unsigned v)
-{
-    v = dpp_min<0xB1>(v);                           // quad_perm [1,0,3,2]
-    v = dpp_min<0x4E>(v);                           // quad_perm [2,3,0,1]
-    if constexpr (GW >= 8) v = dpp_min<0x141>(v);   // row_half_mirror
-    if constexpr (GW >= 16) v = dpp_min<0x140>(v);  // row_mirror
-    if constexpr (GW >= 32) v = min(v, xlane<16>(v));
-    if constexpr (GW >= 64) v = min(v, xlane<32>(v));
-    return v;
-}
-
-template <int GW>
-__device__ __forceinline__ unsigned group_max_u32(unsigned v)
-{
-    v = dpp_max<0xB1>(v);
-    v = dpp_max<0x4E>(v);
-    if constexpr (GW >= 8) v = dpp_max<0x141>(v);
-    if constexpr (GW >= 16) v = dpp_max<0x140>(v);
-    if constexpr (GW >= 32) v = max(v, xlane<16>(v));
-    if constexpr (GW >= 64) v = max(v, xlane<32>(v));
-    return v;
-}
-
-template <int OFF>
-__device__ __forceinline__ void lexmin_step(unsigned &hi, unsigned &lo, unsigned &q)
-{
-    const unsigned ohi = xlane<OFF>(hi), olo = xlane<OFF>(lo), oq = xlane<OFF>(q);
-    const bool take = (ohi < hi) || (ohi == hi && (olo < lo || (olo == lo && oq < q)));
-    hi = take ? ohi : hi; lo = take ? olo : lo; q = take ? oq : q;
-}
-
-// rail index of the lexicographically smallest (load, rail) pair of the group
-template <int GW>
-__device__ __forceinline__ unsigned group_argmin_u64(unsigned long long load, unsigned q)
-{
-    unsigned hi = (unsigned)(load >> 32), lo = (unsigned)load;
-    lexmin_step<1>(hi, lo, q);
-    lexmin_step<2>(hi, lo, q);
-    if constexpr (GW >= 8) lexmin_step<4>(hi, lo, q);
-    if constexpr (GW >= 16) lexmin_step<8>(hi, lo, q);
-    if constexpr (GW >= 32) lexmin_step<16>(hi, lo, q);
-    if constexpr (GW >= 64) lexmin_step<32>(hi, lo, q);
-    return q;
-}
-
-// f(value held by the lane whose in-group index is q ^ mask, mask) for every mask in 1..GW-1
-template <int GW, int T, typename F>
-__device__ __forceinline__ void partners_shfl(unsigned v, F &f)
-{
-    if constexpr (T < GW) { f((unsigned)__shfl_xor((int)v, T, GW), (unsigned)T); partners_shfl<GW, T + 1>(v, f); }
-}
-template <typename F>
-__device__ __forceinline__ void partners_quad(unsigned x, unsigned mask, F &f)
-{
-    if (mask != 0) f(x, mask);
-    f(dpp_mov<0xB1>(x), mask ^ 1u);                 // quad_perm [1,0,3,2]
-    f(dpp_mov<0x4E>(x), mask ^ 2u);                 // quad_perm [2,3,0,1]
-    f(dpp_mov<0x1B>(x), mask ^ 3u);                 // quad_perm [3,2,1,0]
-}
-template <int GW, typename F>
-__device__ __forceinline__ void for_each_partner(unsigned v, F f)
-{
-    if constexpr (GW <= 16) {
-        partners_quad(v, 0u, f);
-        if constexpr (GW >= 8) partners_quad(dpp_mov<0x141>(v), 7u, f);            // row_half_mirror: q ^ 7
-        if constexpr (GW >= 16) {
-            const unsigned r = dpp_mov<0x140>(v);                                 // row_mirror: q ^ 15
-            partners_quad(r, 15u, f);
-            partners_quad(dpp_mov<0x141>(r), 8u, f);
-        }
-    } else {
-        partners_shfl<GW, 1>(v, f);
-    }
-}
-
-// Closed form for a period of P chunks of one weight w > 0 entered with max - min load < w: with every
-// rail within w of the emptiest one, greedy assignment of equal weights visits the rails round after
-// round in the fixed order "ascending (load, rail)" - each pick lifts the emptiest rail above all
-// others by less than w.  So chunk i of the period goes to the rail of rank i mod N, and the rail of
-// rank s receives floor(P/N) + (s < P mod N) chunks.  Returns this lane's rank; adds its share to key.
-template <int GW>
-__device__ __forceinline__ unsigned closed_period(unsigned &key, bool has_rail, unsigned w, unsigned per_rank, unsigned extra)
-{
-    unsigned rank = 0;
-    const unsigned mine = key;
-    for_each_partner<GW>(mine, [&](unsigned other, unsigned) { rank += other < mine ? 1u : 0u; });
-    if (has_rail) key += (w * (per_rank + (rank < extra ? 1u : 0u))) << GroupBits<GW>::S;
-    return rank;
-}
-
-// in-group index of the lane whose rank equals `want` (ranks of rail lanes are a permutation of 0..N-1)
-template <int GW>
-__device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsigned want)
-{
-    unsigned res = q;
-    for_each_partner<GW>(rank, [&](unsigned other, unsigned mask) { res = (other == want) ? (q ^ mask) : res; });
-    return res;
-}
 
 // ================================================================================ leading run
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -471,24 +342,14 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
     if (has_rail) S_out[(int64_t)inst * N + q] = (int64_t)(exact ? load : base + (unsigned long long)(key >> S));
 }
 
-// ================================================================================ wide shape
-// One instance per wavefront.  Every GW-lane group carries a copy of the N rail loads and runs the
-// same reduction, so all 64 lanes know each decision; lane t keeps the decision for chunk t of the
-// 64-chunk period, and weights reach the chain through v_readlane (a scalar broadcast).
+// ================================================================================ wide shape (loop in lpt_core.h)
 template <int GW, bool RUNS>
 __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t *__restrict__ chunk_off,
                                                                   const uint32_t *__restrict__ chunk_w, int n_inst, int N,
                                                                   uint8_t *__restrict__ rail, int64_t *__restrict__ S_out)
 {
-    constexpr int S = GroupBits<GW>::S;
-    constexpr int P = 64;                           // chunks per period: one per lane
-    constexpr unsigned W_LIMIT = (unsigned)((0xFFFFFFFFu >> S) / (unsigned)(P + 2)) - 1u;
-
-    const int lane = threadIdx.x & 63;
-    const unsigned q = (unsigned)(lane % GW);
     const int inst = (int)((blockIdx.x * (unsigned)kLptWaves) + (threadIdx.x >> 6));
     if (inst >= n_inst) return;                     // whole wavefront leaves; nothing below synchronises across waves
-    const bool has_rail = (int)q < N;
     int64_t beg = chunk_off[inst];
     int64_t len = chunk_off[inst + 1] - beg;
     unsigned long long base = 0;
@@ -497,81 +358,15 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t 
         const unsigned w0 = chunk_w[beg];
         int64_t r0 = S_out[(int64_t)inst * N];
         r0 = r0 < len ? r0 : len;
-        if (w0 != 0u && w0 <= W_LIMIT) {
+        if (w0 != 0u && w0 <= WideLimit<GW>::value) {
             const int64_t skip = r0 - r0 % N;
             base = (unsigned long long)w0 * (unsigned long long)(skip / N);
             beg += skip; len -= skip;
         }
     }
-
-    unsigned key = has_rail ? q : 0xFFFFFFFFu;
-    unsigned long long load = has_rail ? 0ull : ~0ull;
-    bool exact = false;
-
-    const unsigned per_rank = (unsigned)(P / N), extra = (unsigned)(P % N);
-    const unsigned want = (unsigned)lane % (unsigned)N;
-
-    const uint32_t *wsrc = chunk_w + beg;
-    uint8_t *rdst = rail + beg;
-    unsigned ring[kWideDepth];
-#pragma unroll
-    for (int d = 0; d < kWideDepth; ++d) ring[d] = ((int64_t)d * P + lane < len) ? wsrc[(int64_t)d * P + lane] : 0u;
-
-    for (int64_t i0 = 0; i0 < len; i0 += (int64_t)kWideDepth * P) {
-#pragma unroll
-        for (int d = 0; d < kWideDepth; ++d) {
-            const int64_t p0 = i0 + (int64_t)d * P;
-            if (p0 >= len) break;                   // wave-uniform
-            const unsigned wv = ring[d];
-            {
-                const int64_t nx = p0 + (int64_t)kWideDepth * P + lane;   // refill this slot: kWideDepth periods ahead
-                ring[d] = (nx < len) ? wsrc[nx] : 0u;
-            }
-            unsigned won = 0;
-            if (!exact && __ballot(wv > W_LIMIT) != 0ull) {
-                exact = true;
-                if (has_rail) load = base + (unsigned long long)(key >> S);
-            }
-            bool closed = false;
-            unsigned w0 = 0;
-            if (RUNS && !exact) {
-                w0 = (unsigned)__builtin_amdgcn_readfirstlane((int)wv);
-                const unsigned dmin = group_min_u32<GW>(key) >> S;
-                const unsigned dmax = group_max_u32<GW>(has_rail ? (key >> S) : 0u);
-                const bool ok = (wv == w0) && w0 != 0u && (p0 + P <= len) && (dmax - dmin) < w0;
-                closed = __ballot(!ok) == 0ull;
-            }
-            if (closed) {
-                const unsigned rank = closed_period<GW>(key, has_rail, w0, per_rank, extra);
-                won = rail_of_rank<GW>(rank, q, want);
-            } else if (!exact) {
-#pragma unroll 8
-                for (int t = 0; t < P; ++t) {
-                    const unsigned wS = (unsigned)__builtin_amdgcn_readlane((int)wv, t) << S;
-                    const unsigned bumped = key + wS;
-                    const unsigned m = group_min_u32<GW>(key);
-                    won = (lane == t) ? m : won;
-                    key = (key == m) ? bumped : key;
-                }
-                won &= (unsigned)(GW - 1);
-            } else {
-#pragma unroll 2
-                for (int t = 0; t < P; ++t) {
-                    const unsigned w = (unsigned)__builtin_amdgcn_readlane((int)wv, t);
-                    const unsigned js = group_argmin_u64<GW>(load, q);
-                    load += (q == js) ? (unsigned long long)w : 0ull;
-                    won = (lane == t) ? js : won;
-                }
-            }
-            if (!exact) {
-                const unsigned adv = group_min_u32<GW>(key) >> S;
-                if (has_rail) { key -= adv << S; base += adv; }
-            }
-            if (p0 + lane < len) rdst[p0 + lane] = (uint8_t)won;
-        }
-    }
-    if (lane < N) S_out[(int64_t)inst * N + lane] = (int64_t)(exact ? load : base + (unsigned long long)(key >> S));
+    lpt_wide_body<GW, RUNS>(chunk_w + beg, rail + beg, len, base, N, S_out + (int64_t)inst * N);
 }
+
 
 template <int GW, bool RUNS>
 static int launch_lpt(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,

@@ -162,3 +162,24 @@ def test_binding_rejects_host_tensors():
     import torch
     with pytest.raises(ValueError):
         rs.route_topk(torch.zeros((4, 8)), 2)
+
+
+def test_schedule_validation():
+    lib = rs.load()
+    t = _topo()
+    need = lib.railsched_schedule_workspace_bytes(2, C.byref(t))
+    assert need == lib.railsched_chunk_sort_workspace_bytes(2, C.byref(t)) + lib.railsched_eval_workspace_bytes(2, C.byref(t))
+    assert lib.railsched_schedule_workspace_bytes(-1, C.byref(t)) == 0
+    f = lib.railsched_schedule   # (D1, batch, topo, off, w, flow, perm, capacity, rail, S, R, stats, ws, ws_bytes, stream)
+    assert f(FAKE, -1, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, need, None) == -1
+    assert f(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, -1, FAKE, FAKE, FAKE, FAKE, FAKE, need, None) == -1
+    assert f(None, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, need, None) == -2
+    assert f(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, None, FAKE, FAKE, FAKE, FAKE, need, None) == -2
+    assert f(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, None, FAKE, need, None) == -2
+    assert f(FAKE, 2, None, FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, need, None) == -2
+    assert f(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, None, need, None) == -5
+    assert f(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, need - 1, None) == -5
+    assert f(FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, P(0x1001), need, None) == -5
+    assert f(FAKE, 0, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, need, None) == 0
+    big = _topo(M=64, N=32)
+    assert f(FAKE, 1, C.byref(big), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == -3

@@ -33,6 +33,19 @@ def gpu_schedule(D1_np, topo, want_perm=True):
                 S=S.cpu().numpy(), R=R.cpu().numpy(), stats=stats.cpu().numpy())
 
 
+def gpu_schedule_one_call(D1_np, topo, want_perm=True, capacity=None):
+    """Stages 3-5 through railsched_schedule."""
+    D1 = torch.from_numpy(np.ascontiguousarray(D1_np)).to(DEV)
+    if capacity is None:
+        capacity = int(rs.chunk_count(D1, topo)[-1].item())
+    off, w, flow, perm, rail, S, R, stats = rs.schedule(D1, topo, capacity, want_perm=want_perm)
+    torch.cuda.synchronize()
+    total = int(off[-1].item())
+    return dict(off=off.cpu().numpy(), w=_u32(w)[:total], flow=_u32(flow)[:total],
+                perm=None if perm is None else _u32(perm)[:total], rail=rail.cpu().numpy()[:total],
+                S=S.cpu().numpy(), R=R.cpu().numpy(), stats=stats.cpu().numpy())
+
+
 def cpu_schedule(D1_np, M, N, C, intra=0):
     D1_np = np.ascontiguousarray(D1_np, dtype=np.int64)
     B = D1_np.shape[0]
@@ -209,6 +222,67 @@ def _rand_stack(rng, B, G, C, p_zero=0.3, hi=6):
     m[rng.random((B, G, G)) < 0.2] //= C
     m[rng.random((B, G, G)) < 0.2] = 3 * C
     return m
+
+
+# ------------------------------------------------------------------------------ stages 3-5 in one call
+@pytest.mark.parametrize("M,N,C,B,intra,perm", [
+    (4, 4, 65536, 1, 0, True), (3, 2, 100, 4, 0, True), (3, 2, 100, 4, 1, True), (5, 3, 1000, 3, 0, False),
+    (2, 8, 4096, 5, 0, True), (8, 8, 262144, 3, 0, True), (6, 5, 12345, 2, 0, True), (2, 16, 64, 2, 0, True),
+    (3, 20, 512, 2, 0, False), (2, 32, 256, 1, 0, True), (1, 4, 64, 2, 1, True), (7, 1, 64, 3, 0, True),
+    (4, 4, 1, 1, 0, True), (16, 8, 4096, 2, 0, True), (8, 8, 262144, 32, 0, True), (2, 2, 7, 300, 0, True)])
+def test_schedule_one_call_matches_oracle(M, N, C, B, intra, perm):
+    rng = np.random.default_rng(M * 1000 + N * 10 + B + 5)
+    hi = 6 if C > 1 else 40
+    D1 = _rand_stack(rng, B, M * N, C, hi=hi)
+    topo = rs.Topo(M, N, C, include_intra_node=intra)
+    g = gpu_schedule_one_call(D1, topo, want_perm=perm)
+    c = cpu_schedule(D1, M, N, C, intra)
+    if not perm:
+        c["perm"] = None
+    assert_same(g, c)
+
+
+def test_schedule_one_call_degenerate_instances():
+    # instances with no chunks at all, with tails only, with full chunks only, and with fewer full chunks than rails
+    M, N, C = 3, 4, 1000
+    G = M * N
+    D1 = np.zeros((5, G, G), dtype=np.int64)
+    D1[1, :, :] = 999                        # tails only
+    D1[2, :, :] = 3000                       # full chunks only
+    D1[3, 0, 5] = 2000; D1[3, 1, 9] = 1      # two full chunks (< N) and one tail in node 0, nothing elsewhere
+    D1[4, 4, 0] = 123456                     # one flow
+    topo = rs.Topo(M, N, C)
+    assert_same(gpu_schedule_one_call(D1, topo), cpu_schedule(D1, M, N, C))
+
+
+def test_schedule_one_call_large_batches_take_the_three_stages():
+    # more instances than the one-workgroup-per-instance shape accepts, and a generous capacity
+    rng = np.random.default_rng(77)
+    M, N, C, B = 4, 2, 512, 400              # 1600 instances
+    D1 = _rand_stack(rng, B, M * N, C)
+    topo = rs.Topo(M, N, C)
+    assert_same(gpu_schedule_one_call(D1, topo), cpu_schedule(D1, M, N, C))
+    D1b = _rand_stack(rng, 2, M * N, C)
+    total = int(oracle.chunk_count_batch(D1b, M, N, C)[-1])
+    assert_same(gpu_schedule_one_call(D1b, topo, capacity=total + 12345), cpu_schedule(D1b, M, N, C))
+
+
+def test_schedule_one_call_capacity_overflow_leaves_records_alone():
+    rng = np.random.default_rng(78)
+    M, N, C, B = 4, 4, 4096, 2
+    D1n = _rand_stack(rng, B, M * N, C)
+    D1 = torch.from_numpy(D1n).to(DEV)
+    topo = rs.Topo(M, N, C)
+    total = int(oracle.chunk_count_batch(D1n, M, N, C)[-1])
+    cap = total - 1
+    out = (torch.empty(B * M + 1, dtype=torch.int64, device=DEV), torch.full((cap,), -1, dtype=torch.int32, device=DEV),
+           torch.full((cap,), -1, dtype=torch.int32, device=DEV), None, torch.full((cap,), 255, dtype=torch.uint8, device=DEV),
+           torch.empty((B, M, N), dtype=torch.int64, device=DEV), torch.empty((B, M, N), dtype=torch.int64, device=DEV),
+           torch.empty((B, 8), dtype=torch.int64, device=DEV))
+    rs.schedule(D1, topo, cap, out=out)
+    torch.cuda.synchronize()
+    assert int(out[0][-1].item()) == total
+    assert bool((out[1] == -1).all()) and bool((out[2] == -1).all()) and bool((out[4] == 255).all())
 
 
 @pytest.mark.parametrize("M,N,C,B,intra", [(4, 4, 65536, 1, 0), (3, 2, 100, 4, 0), (3, 2, 100, 4, 1), (5, 3, 1000, 3, 0),
