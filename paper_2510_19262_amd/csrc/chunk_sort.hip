@@ -34,17 +34,27 @@ __global__ __launch_bounds__(64) void cs_count_kernel(CsArgs a)
     uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
     unsigned carry_full = 0, carry_all = 0;
     int64_t n_full = 0, n_all = 0;
-    for (int f0 = 0; f0 < a.NF; f0 += 64) {
-        const int f = f0 + lane;
-        uint32_t q = 0, r = 0;
-        if (f < a.NF) split_bytes(a, flow_bytes(a, rows, k, f), q, r);
-        const unsigned c = q + (r ? 1u : 0u);
-        unsigned tq, tc;
-        const unsigned eq = wave_exscan(q, tq);
-        const unsigned ec = wave_exscan(c, tc);
-        if (f < a.NF) { fs[f] = carry_full + eq; cs[f] = carry_all + ec; }
-        carry_full += tq; carry_all += tc;
-        n_full += q; n_all += c;
+    for (int f0 = 0; f0 < a.NF; f0 += 256) {
+        int64_t bytes[4];                           // four rounds of loads in flight before the scans, which chain
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int f = f0 + 64 * u + lane;
+            bytes[u] = f < a.NF ? flow_bytes(a, rows, k, f) : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int f = f0 + 64 * u + lane;
+            if (f0 + 64 * u >= a.NF) break;         // wave-uniform
+            uint32_t q = 0, r = 0;
+            if (f < a.NF) split_bytes(a, bytes[u], q, r);
+            const unsigned c = q + (r ? 1u : 0u);
+            unsigned tq, tc;
+            const unsigned eq = wave_exscan(q, tq);
+            const unsigned ec = wave_exscan(c, tc);
+            if (f < a.NF) { fs[f] = carry_full + eq; cs[f] = carry_all + ec; }
+            carry_full += tq; carry_all += tc;
+            n_full += q; n_all += c;
+        }
     }
     // exact 64-bit totals
     for (int d = 32; d >= 1; d >>= 1) { n_full += __shfl_xor(n_full, d); n_all += __shfl_xor(n_all, d); }

@@ -67,30 +67,16 @@ __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
     if (threadIdx.x == 0) slot[a.G] = (int64_t)ev_wmax;
 }
 
-constexpr int kRedThreads = 1024;
-constexpr int kRedWaves = kRedThreads / 64;
-
-__device__ __forceinline__ int64_t block_reduce(int64_t v, bool take_max, int64_t *sh)   // sh: kRedWaves entries
+// One workgroup of THREADS/64 wavefronts per matrix (1024 threads, or 256 when the matrix is small: fewer
+// wavefronts make cheaper barriers).  Receive bins: a wavefront covers 64 consecutive bins (or, when G < 64,
+// several slices side by side), the wavefronts split the slices, LDS joins them.  The six statistics are
+// reduced together: shuffles inside the wavefronts, one exchange through LDS.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void eval_reduce_kernel(EvArgs a)
 {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        const int64_t o = __shfl_xor(v, d);
-        v = take_max ? (o > v ? o : v) : (v + o);
-    }
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-    __syncthreads();
-    int64_t r = sh[0];
-    for (int w = 1; w < kRedWaves; ++w) r = take_max ? (sh[w] > r ? sh[w] : r) : (r + sh[w]);
-    return r;
-}
-
-// One workgroup of 16 wavefronts per matrix.  Receive bins: a wavefront covers 64 consecutive bins
-// (or, when G < 64, several slices side by side), the 16 wavefronts split the slices, LDS joins them.
-__global__ __launch_bounds__(kRedThreads) void eval_reduce_kernel(EvArgs a)
-{
-    __shared__ int64_t part[kRedWaves][64];
-    __shared__ int64_t sh[kRedWaves];
+    constexpr int WAVES = THREADS / 64;
+    __shared__ int64_t part[WAVES][64];
+    __shared__ int64_t sh[6][WAVES];
     const int b = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t *slots = a.partial + (int64_t)b * a.slices * (a.G + 1);
@@ -105,26 +91,26 @@ __global__ __launch_bounds__(kRedThreads) void eval_reduce_kernel(EvArgs a)
         const int i = base + li;
         int64_t acc = 0;
         if (i < a.G)
-            for (int t = wave * sub + ts; t < a.slices; t += kRedWaves * sub) acc += slots[(int64_t)t * (a.G + 1) + i];
+            for (int t = wave * sub + ts; t < a.slices; t += WAVES * sub) acc += slots[(int64_t)t * (a.G + 1) + i];
         __syncthreads();                              // previous round's readers are done
         part[wave][lane] = acc;
         __syncthreads();
         if (wave == 0 && lane < width && base + lane < a.G) {
             int64_t r = 0;
-            for (int w = 0; w < kRedWaves; ++w)
+            for (int w = 0; w < WAVES; ++w)
                 for (int u = 0; u < sub; ++u) r += part[w][u * width + lane];
             Rb[base + lane] = r;
         }
     }
     int64_t wmax = 0;
-    for (int t = threadIdx.x; t < a.slices; t += kRedThreads) {
+    for (int t = threadIdx.x; t < a.slices; t += THREADS) {
         const int64_t x = slots[(int64_t)t * (a.G + 1) + a.G];
         wmax = x > wmax ? x : wmax;
     }
     __syncthreads();   // R[b] written by this workgroup is read back below
 
     int64_t max_s = 0, max_r = 0, lb = 0, total = 0, spread = 0;
-    for (int k = threadIdx.x; k < a.M; k += kRedThreads) {
+    for (int k = threadIdx.x; k < a.M; k += THREADS) {
         int64_t out = 0, in = 0, smin = INT64_MAX, smax = 0;
         for (int n = 0; n < a.N; ++n) {
             const int64_t s = Sb[k * a.N + n], r = Rb[k * a.N + n];
@@ -140,28 +126,45 @@ __global__ __launch_bounds__(kRedThreads) void eval_reduce_kernel(EvArgs a)
         lb = ci > lb ? ci : lb;
         spread = (smax - smin) > spread ? (smax - smin) : spread;
     }
-    max_s = block_reduce(max_s, true, sh);
-    max_r = block_reduce(max_r, true, sh);
-    lb = block_reduce(lb, true, sh);
-    wmax = block_reduce(wmax, true, sh);
-    spread = block_reduce(spread, true, sh);
-    total = block_reduce(total, false, sh);
+    // five maxima and one sum, together
+    int64_t v[6] = {max_s, max_r, lb, wmax, spread, total};
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            const int64_t o = __shfl_xor(v[j], d);
+            v[j] = j == 5 ? v[j] + o : (o > v[j] ? o : v[j]);
+        }
+    }
+    if (lane == 0)
+#pragma unroll
+        for (int j = 0; j < 6; ++j) sh[j][wave] = v[j];
+    __syncthreads();
     if (threadIdx.x == 0) {
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            int64_t r = sh[j][0];
+            for (int w = 1; w < WAVES; ++w) r = j == 5 ? r + sh[j][w] : (sh[j][w] > r ? sh[j][w] : r);
+            v[j] = r;
+        }
         int64_t *st = a.stats + (int64_t)b * 8;
-        st[0] = max_s > max_r ? max_s : max_r;
-        st[1] = max_s;
-        st[2] = max_r;
-        st[3] = lb > wmax ? lb : wmax;
-        st[4] = total;
-        st[5] = wmax;
+        st[0] = v[0] > v[1] ? v[0] : v[1];
+        st[1] = v[0];
+        st[2] = v[1];
+        st[3] = v[2] > v[3] ? v[2] : v[3];
+        st[4] = v[5];
+        st[5] = v[3];
         st[6] = a.chunk_off[(int64_t)(b + 1) * a.M] - a.chunk_off[(int64_t)b * a.M];
-        st[7] = spread;
+        st[7] = v[4];
     }
 }
 
 int launch_eval_reduce(const EvArgs &a, int batch, hipStream_t st)
 {
-    hipLaunchKernelGGL(eval_reduce_kernel, dim3((unsigned)batch), dim3(kRedThreads), 0, st, a);
+    if ((int64_t)a.slices * a.G <= 16384 && a.M <= 256)
+        hipLaunchKernelGGL(eval_reduce_kernel<256>, dim3((unsigned)batch), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(eval_reduce_kernel<1024>, dim3((unsigned)batch), dim3(1024), 0, st, a);
     return launch_status();
 }
 
@@ -218,6 +221,5 @@ extern "C" int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w,
     }
     hipLaunchKernelGGL(eval_partial_kernel, dim3((unsigned)a.slices, (unsigned)batch), dim3(kEvThreads), lds, st, a);
     if (int rc = launch_status()) return rc;
-    hipLaunchKernelGGL(eval_reduce_kernel, dim3((unsigned)batch), dim3(kRedThreads), 0, st, a);
-    return launch_status();
+    return launch_eval_reduce(a, batch, st);
 }
