@@ -69,25 +69,33 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int N = a.N;
 
-    // ---- offsets: chunks of the instances before this one, and of all
+    // ---- wavefront 0 starts on the tails at once; the others add up the offsets (chunks of the instances before
+    // this one, and of all) and stage this instance's flow starts
+    int nt = 0;
+    const unsigned short *sorted = idx_a;
     int64_t before = 0, total = 0;
-    for (int i = tid; i < a.n_inst; i += kSsThreads) {
-        const int64_t c = a.cnt_all[i];
-        total += c;
-        before += i < inst ? c : 0;
-    }
+    if (wave == 0) {
+        const int64_t *rows = a.D1 + ((int64_t)b * a.G + (int64_t)k * a.N) * a.G;
+        sorted = tail_sort_wave<false>(a, rows, k, rem, hist, idx_a, idx_b, nt);
+    } else {
+        constexpr int T = kSsThreads - 64;
+        const int t = tid - 64;
+        for (int i = t; i < a.n_inst; i += T) {
+            const int64_t c = a.cnt_all[i];
+            total += c;
+            before += i < inst ? c : 0;
+        }
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) { before += __shfl_xor(before, d); total += __shfl_xor(total, d); }
-    if (lane == 0) { sh_red[0][wave] = before; sh_red[1][wave] = total; }
-    for (int i = tid; i < a.G; i += kSsThreads) bins[i] = 0;
-    const uint32_t n_full = (uint32_t)a.cnt_full[inst];
-    const uint32_t n_all = (uint32_t)a.cnt_all[inst];
-    {
+        for (int d = 32; d >= 1; d >>= 1) { before += __shfl_xor(before, d); total += __shfl_xor(total, d); }
+        for (int i = t; i < a.G; i += T) bins[i] = 0;
         const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
         const uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
-        for (int i = tid; i < a.NF; i += kSsThreads) { st_fs[i] = fs[i]; st_cs[i] = cs[i]; }
-        if (tid == 0) st_fs[a.NF] = 0xFFFFFFFFu;                         // nothing starts behind the last flow
+        for (int i = t; i < a.NF; i += T) { st_fs[i] = fs[i]; st_cs[i] = cs[i]; }
+        if (t == 0) st_fs[a.NF] = 0xFFFFFFFFu;                           // nothing starts behind the last flow
     }
+    if (lane == 0) { sh_red[0][wave] = before; sh_red[1][wave] = total; }
+    const uint32_t n_full = (uint32_t)a.cnt_full[inst];
+    const uint32_t n_all = (uint32_t)a.cnt_all[inst];
     __syncthreads();
     before = 0; total = 0;
 #pragma unroll
@@ -105,10 +113,7 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
     const uint32_t late_full = n_full - skip;                            // full chunks left to the chain (< N)
 
     if (wave == 0) {
-        // ---- tails: sort, write, then the serial chain over [late full chunks | sorted tails]
-        const int64_t *rows = a.D1 + ((int64_t)b * a.G + (int64_t)k * a.N) * a.G;
-        int nt = 0;
-        const unsigned short *sorted = tail_sort_wave<false>(a, rows, k, rem, hist, idx_a, idx_b, nt);
+        // ---- tails: write, then the serial chain over [late full chunks | sorted tails]
         const int64_t tail0 = out0 + n_full;
         for (int i = lane; i < nt; i += 64) {
             const int f = sorted[i];
