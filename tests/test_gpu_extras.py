@@ -150,7 +150,8 @@ def test_port_round_robin_long_instances():
         assert np.array_equal(port.cpu().numpy()[:n], oracle.port_round_robin(off.cpu().numpy(), rail.cpu().numpy()[:n], B, M, N, P))
 
 
-def test_whole_path_replays_from_a_hip_graph():
+@pytest.mark.parametrize("fused", [False, True])
+def test_whole_path_replays_from_a_hip_graph(fused):
     # the library enqueues kernels only (no allocation, no host synchronisation, no memset nodes), so a caller
     # may capture a pass into a HIP graph; every replay must equal the eager result for the inputs of that moment
     cfg = W.get_config("c2").scaled(batch=2, tokens_per_gpu=4096)
@@ -166,9 +167,15 @@ def test_whole_path_replays_from_a_hip_graph():
         cap = max(cap, int(rs.chunk_count(D, topo)[-1].item()))
     plan = rs.Plan(topo, B, cap, DEV, rows=rows, k=cfg.k)
 
-    def step():
-        plan.route(logits, cfg.tokens_per_gpu, eg, cfg.payload_bytes)
-        plan.schedule()
+    ws_rt = torch.empty(rs.route_traffic_workspace_bytes(B, cfg.tokens_per_gpu, cfg.E, topo), dtype=torch.uint8, device=DEV)
+
+    def step(eager=False):
+        if fused and not eager:                                     # the two fused calls, checked against the five stages
+            rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, eg, cfg.payload_bytes, topo, out=(plan.topk_idx, plan.D1), ws=ws_rt)
+            plan.schedule_one_call()
+        else:
+            plan.route(logits, cfg.tokens_per_gpu, eg, cfg.payload_bytes)
+            plan.schedule()
 
     step()
     torch.cuda.synchronize()
@@ -180,7 +187,7 @@ def test_whole_path_replays_from_a_hip_graph():
     torch.cuda.synchronize()
     for rnd in range(5):
         logits.copy_(variants[rnd % 3])
-        step()                                                      # eager reference for these inputs
+        step(eager=True)                                            # eager reference for these inputs
         torch.cuda.synchronize()
         want = [t.clone() for t in (plan.topk_idx, plan.D1, plan.chunk_off, plan.S, plan.R, plan.stats)]
         n = int(plan.chunk_off[-1].item())

@@ -128,7 +128,17 @@ def test_c2_full_every_array():
     assert np.array_equal(g["S"].cpu().numpy(), S_c) and np.array_equal(g["R"].cpu().numpy(), R_c)
     assert np.array_equal(g["stats"].cpu().numpy(), stats_c)
     _check_properties(g, D1, cfg.M, cfg.N)
-    del logits, idx, D1, g
+
+    # the same batch through the two fused calls, in the launch configuration the benchmark times
+    idx2, D12 = rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, eg, cfg.payload_bytes, topo)
+    assert torch.equal(idx2, idx) and torch.equal(D12, D1)
+    off2, w2, flow2, perm2, rail2, S2, R2, stats2 = rs.schedule(D12, topo, n)
+    assert np.array_equal(off2.cpu().numpy(), off_c)
+    assert np.array_equal(_u32(w2)[:n], w_c) and np.array_equal(_u32(flow2)[:n], flow_c) and np.array_equal(_u32(perm2)[:n], perm_c)
+    assert np.array_equal(rail2.cpu().numpy()[:n], rail_c)
+    assert np.array_equal(S2.cpu().numpy(), S_c) and np.array_equal(R2.cpu().numpy(), R_c)
+    assert np.array_equal(stats2.cpu().numpy(), stats_c)
+    del logits, idx, D1, g, idx2, D12
     _free()
 
 
