@@ -79,13 +79,23 @@ __device__ __forceinline__ unsigned short *tail_sort_wave(const CsArgs &a, const
     // tails in canonical order; which key bits differ at all between them
     int nt = 0;
     unsigned any1 = 0u, all1 = 0xFFFFFFFFu;
-    for (int f0 = 0; f0 < a.NF; f0 += 64) {
-        const int f = f0 + lane;
-        uint32_t q = 0, r = 0;
-        if (f < a.NF) { split_bytes(a, flow_bytes(a, rows, k, f), q, r); rem[f] = r; }
-        const unsigned long long m = __ballot(r != 0);
-        if (r) { idx_a[nt + __popcll(m & lt)] = (unsigned short)f; any1 |= r; all1 &= r; }
-        nt += __popcll(m);
+    for (int f0 = 0; f0 < a.NF; f0 += 512) {
+        int64_t bytes[8];                           // eight rounds of loads in flight: one memory round trip, not eight
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int f = f0 + 64 * u + lane;
+            bytes[u] = f < a.NF ? flow_bytes(a, rows, k, f) : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int f = f0 + 64 * u + lane;
+            if (f0 + 64 * u >= a.NF) break;         // wave-uniform
+            uint32_t q = 0, r = 0;
+            if (f < a.NF) { split_bytes(a, bytes[u], q, r); rem[f] = r; }
+            const unsigned long long m = __ballot(r != 0);
+            if (r) { idx_a[nt + __popcll(m & lt)] = (unsigned short)f; any1 |= r; all1 &= r; }
+            nt += __popcll(m);
+        }
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) { any1 |= (unsigned)__shfl_xor((int)any1, d); all1 &= (unsigned)__shfl_xor((int)all1, d); }
