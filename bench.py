@@ -5,8 +5,10 @@ A step is one pass of all five stages (route_topk -> traffic_matrix -> chunk_sor
 eval) over one batch of the Mixtral-8x7B-shaped workload, through two calls: railsched_route_traffic
 (stages 1-2 in one pass over the logits) and railsched_schedule (stages 3-5, one workgroup per
 instance).  Both write the same bytes as the separate calls - asserted here on every output array;
-the same step through the five separate calls is timed too and reported as "staged".  Workload: 8 nodes x 8 rails, 8 experts top-2,
-16384 tokens per GPU, 8 KiB tokens, 256 KiB chunks, 32 layers = 32 traffic matrices of 64x64.
+the same step through the five separate calls is timed too and reported as "staged", and the
+throughput with two steps in flight on two streams as "two_steps_in_flight".  Workload: 8 nodes x
+8 rails, 8 experts top-2, 16384 tokens per GPU, 8 KiB tokens, 256 KiB chunks, 32 layers = 32
+traffic matrices of 64x64.
 Inputs (1 GiB of fp32 router logits, synthetic, seeded) are resident in HBM before timing starts.
 Prints ONE JSON line.
 """
@@ -146,6 +148,28 @@ def main():
 
     assert int(plan.chunk_off[-1].item()) == total_chunks
 
+    # ---- supplementary: throughput with two steps in flight (two streams of default priority, outputs double-buffered):
+    # the latency-bound stages 3-5 of one step run beside the bandwidth-bound stages 1-2 of the next
+    plan_b = rs.Plan(topo, B, total_chunks, dev, rows=rows, k=cfg.k, want_perm=True)
+    ws_rt_b = torch.empty_like(ws_rt)
+    lanes = ((plan, ws_rt, torch.cuda.Stream()), (plan_b, ws_rt_b, torch.cuda.Stream()))
+
+    def piped(i):
+        p, w, s_ = lanes[i % 2]
+        with torch.cuda.stream(s_):
+            rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=(p.topk_idx, p.D1), ws=w)
+            p.schedule_one_call()
+    for i in range(2 * max(args.warmup, 1)):
+        piped(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(2 * args.steps):
+        piped(i)
+    torch.cuda.synchronize()
+    piped_ms = (time.perf_counter() - t0) * 1e3 / (2 * args.steps)
+    assert torch.equal(plan_b.stats, plan.stats) and torch.equal(plan_b.rail, plan.rail) and torch.equal(plan_b.R, plan.R)
+    del plan_b, ws_rt_b
+
     # ---- supplementary: the plain per-chunk LPT kernel on the same records (same outputs, no closed-form periods)
     rail2, S2 = torch.empty_like(plan.rail), torch.empty_like(plan.S)
     cw = []
@@ -214,6 +238,8 @@ def main():
         "staged": {"ms_per_step": staged_ms_per_step, "value": total_chunks / (staged_ms_per_step * 1e-3), "stage_ms": staged_ms,
                    "note": "the same step through the five separate calls (indices written, then read back)",
                    "route_topk_GBps": k1_gbps, "routing_to_traffic_matrix_GBps": staged_routing_gbps},
+        "two_steps_in_flight": {"ms_per_step": piped_ms, "value": total_chunks / (piped_ms * 1e-3),
+                                "note": "same two calls per step, consecutive steps alternating between two streams and two sets of outputs"},
         "routing_to_traffic_matrix_GBps": rt_gbps,
         "routing_frac_of_hbm_peak": rt_gbps / HBM_PEAK_GBPS,
         "lpt_spray_chunks_per_s": lpt_rate,
