@@ -128,17 +128,6 @@ __global__ __launch_bounds__(64) void cs_tail_kernel(CsArgs a)
 }
 
 // ---- D: full chunks: tiles of consecutive output positions ------------------------------------
-template <typename T>
-__device__ __forceinline__ int last_le(const T *v, int n, uint32_t x)   // last i in [0,n) with v[i] <= x (v[0] <= x)
-{
-    int lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (v[mid] <= x) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 // Full-chunk region of the instances, cut into tiles of a.tile positions; a workgroup takes a contiguous run of
 // tiles, so the instance and the flow its next tile starts in carry over and only its first tile is searched for.
 // A tile is filled in spans: as many flow boundaries as fit are staged in LDS (in rounds of 512, until they reach
@@ -211,7 +200,7 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec
                 const uint32_t pb = pa + groups * 4;                              // scalar positions from here on
                 const uint32_t g0 = (uint32_t)((uint64_t)groups * wave / kWaves), g1 = (uint32_t)((uint64_t)groups * (wave + 1) / kWaves);
                 if (g0 < g1) {
-                    int j_lo = last_le(st_fs, nf, pa + 4 * g0);          // the same in every lane
+                    int j_lo = last_le<uint32_t>(st_fs, nf, pa + 4 * g0);          // the same in every lane
                     for (uint32_t gb = g0; gb < g1; gb += 64) {
                         const bool active = gb + lane < g1;
                         const uint32_t g = active ? gb + lane : g1 - 1;  // idle lanes shadow the last group
@@ -253,21 +242,21 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec
                 const uint32_t n_edge = (pa - p0) + (p1 - pb);
                 if (threadIdx.x < n_edge) {
                     const uint32_t p = threadIdx.x < pa - p0 ? p0 + threadIdx.x : pb + (threadIdx.x - (pa - p0));
-                    const int j = last_le(st_fs, nf, p);
+                    const int j = last_le<uint32_t>(st_fs, nf, p);
                     a.chunk_w[out0 + p] = cw;
                     a.chunk_flow[out0 + p] = (uint32_t)(fb + j);
                     if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
                 }
             } else {
                 for (uint32_t p = p0 + threadIdx.x; p < p1; p += kFillThreads) {
-                    const int j = last_le(st_fs, nf, p);
+                    const int j = last_le<uint32_t>(st_fs, nf, p);
                     a.chunk_w[out0 + p] = cw;
                     a.chunk_flow[out0 + p] = (uint32_t)(fb + j);
                     if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
                 }
             }
             // the next span starts in the flow that holds position p1 - 1
-            fb += last_le(st_fs, nf, p1 - 1);
+            fb += last_le<uint32_t>(st_fs, nf, p1 - 1);
             p0 = p1;
         }
     }

@@ -62,6 +62,18 @@ __device__ __forceinline__ unsigned xlane(unsigned v) { return (unsigned)xlane<O
 template <int OFF>
 __device__ __forceinline__ float xlane(float v) { return __int_as_float(xlane<OFF>(__float_as_int(v))); }
 
+// last i in [0,n) with v[i] <= x (v[0] <= x): plain binary search by one lane
+template <typename T>
+__device__ __forceinline__ int last_le(const T *v, int n, T x)
+{
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (v[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
 // last i in [0,n) with v[i] <= x (v[0] <= x), searched 64 ways per step by the whole wavefront: lane l probes
 // the l-th of 64 evenly spaced entries and the highest lane that still sees v <= x wins.  Two or three dependent
 // memory round trips instead of log2(n); every lane of the wavefront must call it with the same arguments.

@@ -70,16 +70,6 @@ __device__ __forceinline__ uint32_t policy_rail(const PolArgs &a, int64_t inst, 
     }
 }
 
-__device__ __forceinline__ int pol_last_le(const int64_t *v, int n, int64_t x)
-{
-    int lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (v[mid] <= x) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 __global__ void fill_zero_kernel(int64_t *p, int64_t n)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
@@ -119,7 +109,7 @@ __global__ __launch_bounds__(kPolThreads) void policy_kernel(PolArgs a)
                     fl[e] = (p + e < total) ? a.chunk_flow[p + e] : 0u;
                 }
             }
-            int li = staged ? pol_last_le(s_off, cnt, p) : pol_last_le(a.chunk_off, a.n_inst, p) - inst_lo;
+            int li = staged ? last_le<int64_t>(s_off, cnt, p) : last_le<int64_t>(a.chunk_off, a.n_inst, p) - inst_lo;
             uint32_t packed = 0;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {

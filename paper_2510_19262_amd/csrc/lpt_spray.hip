@@ -47,16 +47,6 @@ __global__ void lpt_prefix_init_kernel(int64_t *run_end, int n_inst, int N)
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_inst; i += gridDim.x * blockDim.x) run_end[(int64_t)i * N] = INT64_MAX;
 }
 
-__device__ __forceinline__ int last_le_i64(const int64_t *v, int n, int64_t x)   // last i in [0,n) with v[i] <= x (v[0] <= x)
-{
-    int lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (v[mid] <= x) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 // Every chunk position p of every instance: rail[p] = (position inside the instance) mod N, and
 // run_end[inst*N] = min(position inside the instance of the first weight that differs from the
 // instance's first weight).  Positions are handled four at a time at multiples of four, so weights
@@ -150,7 +140,7 @@ __global__ __launch_bounds__(kPfThreads) void lpt_prefix_kernel(const int64_t *_
 #pragma unroll
                 for (int e = 0; e < 4; ++e) w[e] = (p + e < total) ? chunk_w[p + e] : 0u;
             }
-            int li = staged ? last_le_i64(s_off, cnt, p) : last_le_i64(chunk_off, n_inst, p) - inst_lo;
+            int li = staged ? last_le<int64_t>(s_off, cnt, p) : last_le<int64_t>(chunk_off, n_inst, p) - inst_lo;
             uint32_t packed = 0;
             int64_t miss_inst = -1, miss_pos = 0;          // first mismatch seen by this thread, per instance
 #pragma unroll

@@ -31,16 +31,6 @@ struct SsArgs {
     int32_t nshift, gmask;  // >= 0 when N / G are powers of two
 };
 
-__device__ __forceinline__ int ss_last_le(const uint32_t *v, int n, uint32_t x)   // last i in [0,n) with v[i] <= x (v[0] <= x)
-{
-    int lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (v[mid] <= x) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 __device__ __forceinline__ int ss_dst_node(const CsArgs &a, const SsArgs &x, uint32_t flow)   // flow = n*G + dst -> dst / N
 {
     if (x.gmask >= 0 && x.nshift >= 0) return (int)((flow & (uint32_t)x.gmask) >> x.nshift);
@@ -137,7 +127,7 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
         for (int i = lane; i < (int)n_late; i += 64) {
             const unsigned r = late_rail[i];
             x.rail[out0 + skip + i] = (uint8_t)r;
-            const uint32_t f = i < (int)late_full ? (uint32_t)ss_last_le(st_fs, a.NF, skip + i) : (uint32_t)sorted[i - late_full];
+            const uint32_t f = i < (int)late_full ? (uint32_t)last_le<uint32_t>(st_fs, a.NF, skip + i) : (uint32_t)sorted[i - late_full];
             atomicAdd(&bins[ss_dst_node(a, x, f) * N + r], (unsigned long long)late_w[i]);
         }
     } else {
@@ -151,7 +141,7 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
             const uint32_t pb = pa + groups * 4;
             for (uint32_t g = t; g < groups; g += T) {
                 const uint32_t p = pa + 4 * g;
-                int j = ss_last_le(st_fs, a.NF, p);
+                int j = last_le<uint32_t>(st_fs, a.NF, p);
                 uint32_t nxt = st_fs[j + 1];
                 uint32_t base = st_cs[j] - st_fs[j];                     // canonical position = base + p
                 uint32_t fl[4], pm[4], rr = 0;
@@ -177,7 +167,7 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
             const uint32_t n_edge = pa + (n_full - pb);                  // at most 6 positions outside the aligned groups
             if ((uint32_t)t < n_edge) {
                 const uint32_t p = (uint32_t)t < pa ? (uint32_t)t : pb + ((uint32_t)t - pa);
-                const int j = ss_last_le(st_fs, a.NF, p);
+                const int j = last_le<uint32_t>(st_fs, a.NF, p);
                 a.chunk_w[out0 + p] = cw;
                 a.chunk_flow[out0 + p] = (uint32_t)j;
                 if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
@@ -185,7 +175,7 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
             }
         } else {
             for (uint32_t p = t; p < n_full; p += T) {
-                const int j = ss_last_le(st_fs, a.NF, p);
+                const int j = last_le<uint32_t>(st_fs, a.NF, p);
                 a.chunk_w[out0 + p] = cw;
                 a.chunk_flow[out0 + p] = (uint32_t)j;
                 if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
