@@ -18,6 +18,8 @@ struct CsArgs {
     int32_t M, N, G, NF, intra;
     int32_t n_inst;
     int32_t tile;        // full-chunk positions per fill tile
+    uint8_t *rail;       // when set, the fill also writes the rails of every instance's leading run (see cs_fill_kernel)
+    int32_t nmask;       // N - 1 when N is a power of two, else -1
 };
 
 __device__ __forceinline__ void split_bytes(const CsArgs &a, int64_t B, uint32_t &q, uint32_t &r)
@@ -144,5 +146,14 @@ __device__ __forceinline__ unsigned short *tail_sort_wave(const CsArgs &a, const
     nt_out = nt;
     return idx_a;
 }
+
+// Host side of stage 3, shared by railsched_chunk_sort and the one-call scheduler (defined in chunk_sort.hip):
+// validates, lays the workspace out and launches count, scan, tail sort and fill.  With `rail` set the fill also
+// writes rail[i] = i mod N for the first n_full - n_full mod N positions of every instance - the greedy
+// allocation of a leading run of equal weights from empty rails (Algorithm 2 step 3) in closed form.
+// *args_out, if given, receives the argument block (workspace pointers included).
+int cs_run(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off, uint32_t *chunk_w,
+           uint32_t *chunk_flow, uint32_t *perm, int64_t capacity, uint8_t *rail, void *ws, size_t ws_bytes, hipStream_t st,
+           CsArgs *args_out);
 
 }  // namespace rs

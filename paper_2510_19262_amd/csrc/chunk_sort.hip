@@ -162,6 +162,7 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec
         const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
         const uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
         const int64_t out0 = a.chunk_off[inst];
+        const uint32_t lead = n_full - n_full % (uint32_t)a.N;          // positions below it go round robin (a.rail)
         if (fb < 0) fb = wave_last_le<uint32_t>(fs, a.NF, t0);
 
         uint32_t p0 = t0;
@@ -230,6 +231,20 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec
                             fl[e] = (uint32_t)(fb + j);
                             pm[e] = base + p + e;
                         }
+                        if (active && a.rail) {                      // leading run: rail = position mod N
+                            uint32_t r = a.nmask >= 0 ? (p & (uint32_t)a.nmask) : p % (uint32_t)a.N, rr = 0;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                rr |= r << (8 * e);
+                                r = (r + 1 == (uint32_t)a.N) ? 0u : r + 1;
+                            }
+                            if (p + 4 <= lead) {
+                                *reinterpret_cast<uint32_t *>(a.rail + out0 + p) = rr;
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) if (p + e < lead) a.rail[out0 + p + e] = (uint8_t)(rr >> (8 * e));
+                            }
+                        }
                         if (active) {
                             *reinterpret_cast<uint4 *>(a.chunk_w + out0 + p) = make_uint4(cw, cw, cw, cw);
                             *reinterpret_cast<uint4 *>(a.chunk_flow + out0 + p) = make_uint4(fl[0], fl[1], fl[2], fl[3]);
@@ -246,6 +261,7 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec
                     a.chunk_w[out0 + p] = cw;
                     a.chunk_flow[out0 + p] = (uint32_t)(fb + j);
                     if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
+                    if (a.rail && p < lead) a.rail[out0 + p] = (uint8_t)(p % (uint32_t)a.N);
                 }
             } else {
                 for (uint32_t p = p0 + threadIdx.x; p < p1; p += kFillThreads) {
@@ -253,6 +269,7 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec
                     a.chunk_w[out0 + p] = cw;
                     a.chunk_flow[out0 + p] = (uint32_t)(fb + j);
                     if (a.perm) a.perm[out0 + p] = st_cs[j] + (p - st_fs[j]);
+                    if (a.rail && p < lead) a.rail[out0 + p] = (uint8_t)(p % (uint32_t)a.N);
                 }
             }
             // the next span starts in the flow that holds position p1 - 1
@@ -292,11 +309,11 @@ extern "C" size_t railsched_chunk_sort_workspace_bytes(int32_t batch, const rail
     return off[5] ? off[5] : 256;
 }
 
-extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo,
-                                    int64_t *chunk_off, uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm,
-                                    int64_t capacity, void *ws, size_t ws_bytes, void *stream)
+namespace rs {
+int cs_run(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off, uint32_t *chunk_w,
+           uint32_t *chunk_flow, uint32_t *perm, int64_t capacity, uint8_t *rail, void *ws, size_t ws_bytes, hipStream_t st,
+           CsArgs *args_out)
 {
-    using namespace rs;
     if (int rc = check_topo(h_topo)) return rc;
     if (batch < 0 || capacity < 0) return RAILSCHED_ERR_INVALID_ARG;
     const int64_t M = h_topo->nodes, N = h_topo->rails, G = M * N, NF = N * G;
@@ -309,8 +326,6 @@ extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const rail
     size_t off[6];
     ws_layout(n_inst, NF, off);
     if (!ws || ws_bytes < off[5] || reinterpret_cast<uintptr_t>(ws) % 256) return RAILSCHED_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-
     char *w8 = static_cast<char *>(ws);
     CsArgs a;
     a.D1 = D1; a.chunk_off = chunk_off; a.chunk_w = chunk_w; a.chunk_flow = chunk_flow; a.perm = perm;
@@ -326,6 +341,9 @@ extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const rail
     a.cshift = is_pow2(a.C) ? ilog2(a.C) : -1;
     a.M = (int32_t)M; a.N = (int32_t)N; a.G = (int32_t)G; a.NF = (int32_t)NF; a.intra = h_topo->include_intra_node;
     a.n_inst = (int32_t)n_inst;
+    a.rail = rail;
+    a.nmask = is_pow2(N) ? (int32_t)N - 1 : -1;
+    if (args_out) *args_out = a;
 
     if (n_inst > 0) {
         hipLaunchKernelGGL(cs_count_kernel, dim3((unsigned)n_inst), dim3(64), 0, st, a);
@@ -344,10 +362,19 @@ extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const rail
     hipLaunchKernelGGL(cs_tail_kernel, dim3((unsigned)n_inst), dim3(64), lds, st, a);
     if (int rc = launch_status()) return rc;
     const int vec_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(chunk_flow) % 16 == 0 &&
-                        reinterpret_cast<uintptr_t>(perm) % 16 == 0) ? 1 : 0;
+                        reinterpret_cast<uintptr_t>(perm) % 16 == 0 && reinterpret_cast<uintptr_t>(rail) % 4 == 0) ? 1 : 0;
     // no launch needs more workgroups than there can be tiles: capacity/tile full ones and one ragged one per instance
     int64_t fill_blocks = capacity / a.tile + n_inst;
     fill_blocks = fill_blocks < 1 ? 1 : fill_blocks > kFillBlocks ? kFillBlocks : fill_blocks;
     hipLaunchKernelGGL(cs_fill_kernel, dim3((unsigned)fill_blocks), dim3(kFillThreads), 0, st, a, vec_ok);
     return launch_status();
+}
+}  // namespace rs
+
+extern "C" int railsched_chunk_sort(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo,
+                                    int64_t *chunk_off, uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm,
+                                    int64_t capacity, void *ws, size_t ws_bytes, void *stream)
+{
+    return rs::cs_run(D1, batch, h_topo, chunk_off, chunk_w, chunk_flow, perm, capacity, nullptr, ws, ws_bytes,
+                      static_cast<hipStream_t>(stream), nullptr);
 }

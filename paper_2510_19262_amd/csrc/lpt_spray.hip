@@ -219,8 +219,10 @@ __device__ __forceinline__ void exact_steps(unsigned long long &load, const unsi
 template <int GW, bool RUNS>
 __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_t *__restrict__ chunk_off,
                                                                     const uint32_t *__restrict__ chunk_w, int n_inst, int N,
-                                                                    uint8_t *__restrict__ rail, int64_t *__restrict__ S_out)
+                                                                    uint8_t *__restrict__ rail, int64_t *__restrict__ S_out,
+                                                                    int64_t capacity)
 {
+    if (chunk_off[n_inst] > capacity) return;       // the record arrays were too small and hold nothing
     constexpr int S = GroupBits<GW>::S;
     constexpr int IPW = 64 / GW;                    // instances per wavefront
     constexpr int STEP = kBatch > GW ? kBatch : GW; // chunks per instance and period
@@ -336,8 +338,10 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
 template <int GW, bool RUNS>
 __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t *__restrict__ chunk_off,
                                                                   const uint32_t *__restrict__ chunk_w, int n_inst, int N,
-                                                                  uint8_t *__restrict__ rail, int64_t *__restrict__ S_out)
+                                                                  uint8_t *__restrict__ rail, int64_t *__restrict__ S_out,
+                                                                  int64_t capacity)
 {
+    if (chunk_off[n_inst] > capacity) return;       // the record arrays were too small and hold nothing
     const int inst = (int)((blockIdx.x * (unsigned)kLptWaves) + (threadIdx.x >> 6));
     if (inst >= n_inst) return;                     // whole wavefront leaves; nothing below synchronises across waves
     int64_t beg = chunk_off[inst];
@@ -358,11 +362,31 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t 
 }
 
 
+// serial kernels only: every instance's S_out[inst*N] must hold the length of its leading run (or less)
+template <int GW, bool RUNS>
+static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
+                             int64_t *S, int64_t capacity, hipStream_t st)
+{
+    constexpr int IPW = 64 / GW;
+    // packed once it yields at least two wavefronts per SIMD (256 CUs x 4 SIMDs); wide below that
+    const bool packed = IPW > 1 && n_inst >= (int64_t)2048 * IPW;
+    if (packed) {
+        const int64_t waves = (n_inst + IPW - 1) / IPW;
+        const int64_t blocks = (waves + kLptWaves - 1) / kLptWaves;
+        hipLaunchKernelGGL((lpt_packed_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
+                           chunk_w, (int)n_inst, N, rail, S, capacity);
+    } else {
+        const int64_t blocks = (n_inst + kLptWaves - 1) / kLptWaves;
+        hipLaunchKernelGGL((lpt_wide_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
+                           chunk_w, (int)n_inst, N, rail, S, capacity);
+    }
+    return launch_status();
+}
+
 template <int GW, bool RUNS>
 static int launch_lpt(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
                       int64_t *S, hipStream_t st)
 {
-    constexpr int IPW = 64 / GW;
     if (RUNS) {
         hipLaunchKernelGGL(lpt_prefix_init_kernel, dim3((unsigned)((n_inst + 255) / 256 > 1024 ? 1024 : (n_inst + 255) / 256)), dim3(256),
                            0, st, S, (int)n_inst, N);
@@ -371,19 +395,18 @@ static int launch_lpt(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t
                            is_pow2(N) ? N - 1 : -1, rail, S, wide_ok);
         if (int rc = launch_status()) return rc;
     }
-    // packed once it yields at least two wavefronts per SIMD (256 CUs x 4 SIMDs); wide below that
-    const bool packed = IPW > 1 && n_inst >= (int64_t)2048 * IPW;
-    if (packed) {
-        const int64_t waves = (n_inst + IPW - 1) / IPW;
-        const int64_t blocks = (waves + kLptWaves - 1) / kLptWaves;
-        hipLaunchKernelGGL((lpt_packed_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
-                           chunk_w, (int)n_inst, N, rail, S);
-    } else {
-        const int64_t blocks = (n_inst + kLptWaves - 1) / kLptWaves;
-        hipLaunchKernelGGL((lpt_wide_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
-                           chunk_w, (int)n_inst, N, rail, S);
-    }
-    return launch_status();
+    return launch_lpt_serial<GW, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, INT64_MAX, st);
+}
+
+// for the one-call scheduler, which knows every leading run from stage 3 and has written its rails
+int lpt_serial_after_leading_runs(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
+                                  int64_t *S, int64_t capacity, hipStream_t st)
+{
+    if (N <= 4) return launch_lpt_serial<4, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    if (N <= 8) return launch_lpt_serial<8, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    if (N <= 16) return launch_lpt_serial<16, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    if (N <= 32) return launch_lpt_serial<32, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    return launch_lpt_serial<64, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
 }
 
 template <bool RUNS>

@@ -2,7 +2,12 @@
 // allocation, send/receive loads and statistics.  Outputs are those of railsched_chunk_sort, railsched_lpt_spray
 // and railsched_eval run one after the other, bit for bit.
 //
-// Large batches simply run the three stages.  Small ones - up to 1024 instances of a few thousand chunks, the
+// Large batches run the kernels of the three stages, minus what stage 3 already knows: every instance starts with
+// a run of n_full chunks of weight C, whose allocation from empty rails is round robin (rail = i mod N, the closed
+// form behind Theorem 4's premise of equal granularity).  So the fill kernel writes those rails with the records,
+// stage 4's streaming scan for the leading runs is skipped (its serial kernels start behind them), and stage 5 gets
+// the leading runs' receive loads flow by flow in closed form and reads only the few chunks behind them - 13 bytes
+// of HBM traffic per chunk in all instead of 27.  Small ones - up to 1024 instances of a few thousand chunks, the
 // shape of one training step's MoE layers - are bound by the latency of nine dependent launches, so they take
 // three: the per-instance counts (stage 3's count kernel), then ONE workgroup per instance that does everything
 // the instance needs, then the per-matrix reduction of stage 5.  Inside the workgroup, wavefront 0 sorts the
@@ -16,6 +21,8 @@
 namespace rs {
 
 void launch_cs_count(const CsArgs &a, hipStream_t st);          // chunk_sort.hip
+int lpt_serial_after_leading_runs(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
+                                  int64_t *S, int64_t capacity, hipStream_t st);   // lpt_spray.hip
 void cs_ws_layout(int64_t n_inst, int64_t NF, size_t off[6]);  // chunk_sort.hip
 
 constexpr int kSsThreads = 256;
@@ -203,6 +210,50 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
     if (tid == 0) slot[a.G] = (int64_t)sh_wmax;
 }
 
+// ---------------------------------------------------------------------------------------------- large batches
+// S[inst*N] = length of the instance's leading run of full chunks, where stage 4's serial kernels look for it
+__global__ void sl_run_end_kernel(CsArgs a, int64_t *S)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.n_inst; i += gridDim.x * blockDim.x) S[(int64_t)i * a.N] = a.cnt_full[i];
+}
+
+// Receive loads of one instance into its workspace slot [G + 1]: the leading run (positions below
+// n_full - n_full mod N, rails i mod N) flow by flow in closed form, the chunks behind it from their records.
+__global__ __launch_bounds__(kSsThreads) void sl_recv_kernel(CsArgs a, SsArgs x)
+{
+    extern __shared__ unsigned long long sl_bins[];
+    if (a.chunk_off[a.n_inst] > a.capacity) return;                      // the record arrays hold nothing
+    const int inst = blockIdx.x, tid = threadIdx.x, N = a.N;
+    for (int i = tid; i < a.G; i += kSsThreads) sl_bins[i] = 0;
+    __syncthreads();
+    const uint32_t n_full = (uint32_t)a.cnt_full[inst], n_all = (uint32_t)a.cnt_all[inst];
+    const uint32_t lead = n_full - n_full % (uint32_t)N;
+    const uint32_t cw = (uint32_t)a.C;
+    const int64_t out0 = a.chunk_off[inst];
+    const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
+    for (int f = tid; f < a.NF; f += kSsThreads) {
+        const uint32_t s = fs[f];
+        uint32_t e = f + 1 < a.NF ? fs[f + 1] : n_full;
+        e = e < lead ? e : lead;
+        if (s >= e) continue;
+        const int node = ss_dst_node(a, x, (uint32_t)f);
+        for (int n = 0; n < N; ++n) {
+            // positions i < v with i mod N == n number (v + N - 1 - n) / N
+            const uint32_t c = (e + (uint32_t)(N - 1 - n)) / (uint32_t)N - (s + (uint32_t)(N - 1 - n)) / (uint32_t)N;
+            if (c) atomicAdd(&sl_bins[node * N + n], (unsigned long long)c * (unsigned long long)cw);
+        }
+    }
+    for (uint32_t p = lead + tid; p < n_all; p += kSsThreads) {
+        const unsigned r = x.rail[out0 + p];
+        const int node = ss_dst_node(a, x, a.chunk_flow[out0 + p]);
+        if (node < a.M && r < (unsigned)N) atomicAdd(&sl_bins[node * N + r], (unsigned long long)a.chunk_w[out0 + p]);
+    }
+    __syncthreads();
+    int64_t *slot = x.partial + (int64_t)inst * (a.G + 1);
+    for (int i = tid; i < a.G; i += kSsThreads) slot[i] = (int64_t)sl_bins[i];
+    if (tid == 0) slot[a.G] = n_all ? (int64_t)a.chunk_w[out0] : 0;      // records are sorted: the first is the largest
+}
+
 template <int GW>
 static int launch_ss(const CsArgs &a, const SsArgs &x, hipStream_t st)
 {
@@ -219,11 +270,22 @@ static int launch_ss(const CsArgs &a, const SsArgs &x, hipStream_t st)
 
 }  // namespace rs
 
+namespace rs {
+// stage 5 part of the workspace: stage 5's own slots, or one slot of G + 1 sums per instance, whichever is larger
+static size_t sched_eval_bytes(int32_t batch, const railsched_topo_t *h_topo)
+{
+    const size_t e = railsched_eval_workspace_bytes(batch, h_topo);
+    const size_t G = (size_t)h_topo->nodes * h_topo->rails;
+    const size_t per_inst = align_up(sizeof(int64_t) * (size_t)batch * h_topo->nodes * (G + 1), 256);
+    return e > per_inst ? e : per_inst;
+}
+}  // namespace rs
+
 extern "C" size_t railsched_schedule_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo)
 {
     const size_t s = railsched_chunk_sort_workspace_bytes(batch, h_topo);
     const size_t e = railsched_eval_workspace_bytes(batch, h_topo);
-    return (s && e) ? s + e : 0;                   // both are multiples of 256
+    return (s && e) ? s + rs::sched_eval_bytes(batch, h_topo) : 0;     // both are multiples of 256
 }
 
 extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off,
@@ -241,7 +303,7 @@ extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsc
     if (batch == 0) return RAILSCHED_OK;
     if (!D1 || !chunk_off || !chunk_w || !chunk_flow || !rail || !S || !R || !stats) return RAILSCHED_ERR_NULL_PTR;
     const size_t ws_sort = railsched_chunk_sort_workspace_bytes(batch, h_topo);
-    const size_t ws_eval = railsched_eval_workspace_bytes(batch, h_topo);
+    const size_t ws_eval = sched_eval_bytes(batch, h_topo);
     if (!ws || ws_bytes < ws_sort + ws_eval || reinterpret_cast<uintptr_t>(ws) % 256) return RAILSCHED_ERR_WORKSPACE;
     char *w8 = static_cast<char *>(ws);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -251,10 +313,32 @@ extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsc
                            : GW == 32 ? WideLimit<32>::value : WideLimit<64>::value;
     const bool small = n_inst <= kSsMaxInst && NF <= kSsMaxFlows && capacity <= n_inst * (int64_t)kSsMaxAvg &&
                        (uint64_t)h_topo->chunk_bytes <= (uint64_t)w_limit;
+    SsArgs x;
+    x.rail = rail; x.S = S; x.partial = reinterpret_cast<int64_t *>(w8 + ws_sort);
+    x.vec_ok = 0;
+    x.nshift = is_pow2(N) ? ilog2(N) : -1;
+    x.gmask = is_pow2(G) ? (int32_t)G - 1 : -1;
+    EvArgs e;
+    e.chunk_off = chunk_off; e.chunk_w = chunk_w; e.chunk_flow = chunk_flow; e.rail = rail; e.S = S;
+    e.R = R; e.stats = stats; e.partial = x.partial;
+    e.M = (int32_t)M; e.N = (int32_t)N; e.G = (int32_t)G; e.slices = (int32_t)M;   // one slot per instance
+    e.nshift = x.nshift; e.gmask = x.gmask; e.wide_ok = 0; e.copies = 1;
+
     if (!small) {
-        if (int rc = railsched_chunk_sort(D1, batch, h_topo, chunk_off, chunk_w, chunk_flow, perm, capacity, w8, ws_sort, stream)) return rc;
-        if (int rc = railsched_lpt_spray(chunk_off, chunk_w, batch, h_topo, rail, S, stream)) return rc;
-        return railsched_eval(chunk_off, chunk_w, chunk_flow, rail, S, batch, h_topo, R, stats, w8 + ws_sort, ws_eval, stream);
+        CsArgs a;
+        if (int rc = cs_run(D1, batch, h_topo, chunk_off, chunk_w, chunk_flow, perm, capacity, rail, w8, ws_sort, st, &a)) return rc;
+        hipLaunchKernelGGL(sl_run_end_kernel, dim3((unsigned)((n_inst + 255) / 256 > 1024 ? 1024 : (n_inst + 255) / 256)), dim3(256), 0, st, a, S);
+        if (int rc = launch_status()) return rc;
+        if (int rc = lpt_serial_after_leading_runs(chunk_off, chunk_w, n_inst, (int)N, rail, S, capacity, st)) return rc;
+        const size_t lds = sizeof(unsigned long long) * (size_t)G;
+        if (lds > 48 * 1024) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(sl_recv_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds) != hipSuccess)
+                return RAILSCHED_ERR_HIP;
+        }
+        hipLaunchKernelGGL(sl_recv_kernel, dim3((unsigned)n_inst), dim3(kSsThreads), lds, st, a, x);
+        if (int rc = launch_status()) return rc;
+        return launch_eval_reduce(e, batch, st);
     }
 
     size_t off[6];
@@ -272,23 +356,14 @@ extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsc
     a.cshift = is_pow2(a.C) ? ilog2(a.C) : -1;
     a.M = (int32_t)M; a.N = (int32_t)N; a.G = (int32_t)G; a.NF = (int32_t)NF; a.intra = h_topo->include_intra_node;
     a.n_inst = (int32_t)n_inst;
+    a.rail = nullptr; a.nmask = -1;                 // unused by the count kernel
     launch_cs_count(a, st);
     if (int rc = launch_status()) return rc;
 
-    SsArgs x;
-    x.rail = rail; x.S = S; x.partial = reinterpret_cast<int64_t *>(w8 + ws_sort);
     x.vec_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(chunk_flow) % 16 == 0 &&
                 reinterpret_cast<uintptr_t>(perm) % 16 == 0 && reinterpret_cast<uintptr_t>(rail) % 4 == 0) ? 1 : 0;
-    x.nshift = is_pow2(N) ? ilog2(N) : -1;
-    x.gmask = is_pow2(G) ? (int32_t)G - 1 : -1;
     int rc = GW == 4 ? launch_ss<4>(a, x, st) : GW == 8 ? launch_ss<8>(a, x, st) : GW == 16 ? launch_ss<16>(a, x, st)
            : GW == 32 ? launch_ss<32>(a, x, st) : launch_ss<64>(a, x, st);
     if (rc) return rc;
-
-    EvArgs e;
-    e.chunk_off = chunk_off; e.chunk_w = chunk_w; e.chunk_flow = chunk_flow; e.rail = rail; e.S = S;
-    e.R = R; e.stats = stats; e.partial = x.partial;
-    e.M = (int32_t)M; e.N = (int32_t)N; e.G = (int32_t)G; e.slices = (int32_t)M;   // one slot per instance
-    e.nshift = x.nshift; e.gmask = x.gmask; e.wide_ok = 0; e.copies = 1;
     return launch_eval_reduce(e, batch, st);
 }

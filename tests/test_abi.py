@@ -168,7 +168,8 @@ def test_schedule_validation():
     lib = rs.load()
     t = _topo()
     need = lib.railsched_schedule_workspace_bytes(2, C.byref(t))
-    assert need == lib.railsched_chunk_sort_workspace_bytes(2, C.byref(t)) + lib.railsched_eval_workspace_bytes(2, C.byref(t))
+    assert need >= lib.railsched_chunk_sort_workspace_bytes(2, C.byref(t)) + lib.railsched_eval_workspace_bytes(2, C.byref(t))
+    assert need % 256 == 0
     assert lib.railsched_schedule_workspace_bytes(-1, C.byref(t)) == 0
     f = lib.railsched_schedule   # (D1, batch, topo, off, w, flow, perm, capacity, rail, S, R, stats, ws, ws_bytes, stream)
     assert f(FAKE, -1, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, need, None) == -1

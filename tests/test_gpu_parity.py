@@ -267,6 +267,22 @@ def test_schedule_one_call_large_batches_take_the_three_stages():
     assert_same(gpu_schedule_one_call(D1b, topo, capacity=total + 12345), cpu_schedule(D1b, M, N, C))
 
 
+@pytest.mark.parametrize("M,N,C,B,intra,perm", [(40, 8, 4096, 2, 0, True), (3, 40, 512, 2, 0, True), (4, 4, 64, 300, 0, False),
+                                               (2, 64, 128, 1, 0, True), (6, 5, 12345, 200, 1, True), (2, 2, 1 << 31, 3, 0, True)])
+def test_schedule_one_call_three_stage_shapes(M, N, C, B, intra, perm):
+    # shapes outside the one-workgroup-per-instance limits: many instances, many flows per instance, huge chunks
+    rng = np.random.default_rng(M * 1000 + N * 10 + B + 9)
+    D1 = _rand_stack(rng, B, M * N, min(C, 1 << 20), hi=9)
+    if C > 1 << 30:
+        D1 = D1 * 5000                                           # bytes of the order of the chunk size
+    topo = rs.Topo(M, N, C, include_intra_node=intra)
+    g = gpu_schedule_one_call(D1, topo, want_perm=perm)
+    c = cpu_schedule(D1, M, N, C, intra)
+    if not perm:
+        c["perm"] = None
+    assert_same(g, c)
+
+
 def test_schedule_one_call_capacity_overflow_leaves_records_alone():
     rng = np.random.default_rng(78)
     M, N, C, B = 4, 4, 4096, 2
@@ -283,6 +299,19 @@ def test_schedule_one_call_capacity_overflow_leaves_records_alone():
     torch.cuda.synchronize()
     assert int(out[0][-1].item()) == total
     assert bool((out[1] == -1).all()) and bool((out[2] == -1).all()) and bool((out[4] == 255).all())
+    # the same through the three-stage shape (more instances than one workgroup each serves)
+    B2 = 300
+    D2n = _rand_stack(rng, B2, M * N, C)
+    total2 = int(oracle.chunk_count_batch(D2n, M, N, C)[-1])
+    cap2 = total2 - 1
+    out2 = (torch.empty(B2 * M + 1, dtype=torch.int64, device=DEV), torch.full((cap2,), -1, dtype=torch.int32, device=DEV),
+            torch.full((cap2,), -1, dtype=torch.int32, device=DEV), None, torch.full((cap2,), 255, dtype=torch.uint8, device=DEV),
+            torch.empty((B2, M, N), dtype=torch.int64, device=DEV), torch.empty((B2, M, N), dtype=torch.int64, device=DEV),
+            torch.empty((B2, 8), dtype=torch.int64, device=DEV))
+    rs.schedule(torch.from_numpy(D2n).to(DEV), topo, cap2, out=out2)
+    torch.cuda.synchronize()
+    assert int(out2[0][-1].item()) == total2
+    assert bool((out2[1] == -1).all()) and bool((out2[2] == -1).all()) and bool((out2[4] == 255).all())
 
 
 @pytest.mark.parametrize("M,N,C,B,intra", [(4, 4, 65536, 1, 0), (3, 2, 100, 4, 0), (3, 2, 100, 4, 1), (5, 3, 1000, 3, 0),
