@@ -39,6 +39,18 @@ def _schedule_dev(D1, topo, want_perm=True):
     return dict(off=off, w=w, flow=flow, perm=perm, rail=rail, S=S, R=R, stats=stats)
 
 
+def _check_one_call(g, D1, topo):
+    """railsched_schedule on the same input: every output equal to the three calls' (which the oracle checks)."""
+    total = int(g["off"][-1].item())
+    off, w, flow, perm, rail, S, R, stats = rs.schedule(D1, topo, total, want_perm=g["perm"] is not None)
+    torch.cuda.synchronize()
+    assert torch.equal(off, g["off"]) and torch.equal(S, g["S"]) and torch.equal(R, g["R"]) and torch.equal(stats, g["stats"])
+    assert torch.equal(w[:total], g["w"][:total]) and torch.equal(flow[:total], g["flow"][:total])
+    assert torch.equal(rail[:total], g["rail"][:total])
+    if perm is not None:
+        assert torch.equal(perm[:total], g["perm"][:total])
+
+
 def _check_instances(g, D1_host_of, M, N, C, insts):
     """Whole instances against the oracle: records, permutation, rails, send loads."""
     off = g["off"].cpu().numpy()
@@ -150,6 +162,7 @@ def test_c3_full_batch_sampled():
     topo = rs.Topo(M, N, C)
     D1 = W.gen_flow_matrices_device(cfg, DEV)                              # 1024 matrices of 256x256, 512 MiB
     g = _schedule_dev(D1, topo)
+    _check_one_call(g, D1, topo)
     D1_h = D1.cpu().numpy()
     assert np.array_equal(g["off"].cpu().numpy(), oracle.chunk_count_batch(D1_h, M, N, C))
     total = int(g["off"][-1].item())
@@ -193,6 +206,7 @@ def test_c4_all_layers_sampled():
     per_gpu = cfg.tokens_per_gpu * cfg.k * cfg.payload_bytes
     assert bool((D1.sum(dim=2) == per_gpu).all())                           # every source GPU routes the same bytes
     g = _schedule_dev(D1, topo)
+    _check_one_call(g, D1, topo)
     D1_h = D1.cpu().numpy()
     assert np.array_equal(g["off"].cpu().numpy(), oracle.chunk_count_batch(D1_h, M, N, C))
     sizes = np.diff(g["off"].cpu().numpy())
@@ -212,6 +226,7 @@ def test_c5_one_matrix_sampled():
     topo = rs.Topo(M, N, C)
     D1 = W.gen_flow_matrices_device(cfg, DEV, first=3, count=1)             # one 1024x1024 matrix: ~4e9 chunks
     g = _schedule_dev(D1, topo, want_perm=False)
+    _check_one_call(g, D1, topo)
     D1_h = D1.cpu().numpy()
     assert np.array_equal(g["off"].cpu().numpy(), oracle.chunk_count_batch(D1_h, M, N, C))
     sizes = np.diff(g["off"].cpu().numpy())
