@@ -180,9 +180,11 @@ int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w, const uint
 /* ---------------------------------------------------------------------------------------------
  * Stages 3-5 in one call (Algorithm 2 steps 1-3 and 6; Section 4.1 S and R; Theorems 2-3): the outputs of
  * railsched_chunk_sort, railsched_lpt_spray and railsched_eval run one after the other on the same
- * arguments, bit for bit.  Batches of at most 1024 instances with N*G <= 2048 flows and
- * capacity <= 32768 chunks per instance take three launches instead of nine (one workgroup per instance
- * does the instance's split, sort, allocation and receive loads); all others run the three stages.
+ * arguments, bit for bit, with less work: stage 3 knows that every instance starts with a run of full chunks,
+ * whose allocation from empty rails is round robin, so their rails are written with the records, stage 4 only
+ * runs behind them and stage 5 takes their receive loads in closed form.  Batches of at most 1024 instances
+ * with N*G <= 2048 flows and capacity <= 32768 chunks per instance are served by one workgroup per instance
+ * (two launches after the counts instead of eight).
  *   D1 [batch][G][G] int64 (in);  chunk_off [batch*M+1];  chunk_w, chunk_flow, perm (perm may be NULL),
  *   rail: `capacity` records each;  S, R [batch][M][N] int64;  stats [batch][8] int64   (out)
  *   ws: railsched_schedule_workspace_bytes(batch, topo) bytes, 256-byte aligned.
