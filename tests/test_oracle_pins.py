@@ -491,3 +491,55 @@ def test_port_round_robin():
     off2 = np.array([0, 50], dtype=np.int64)
     rail2, _ = oracle.lpt(np.full(50, 7, dtype=np.uint32), 4)
     assert np.array_equal(oracle.port_round_robin(off2, rail2, 1, 1, 4, 3), (np.arange(50) // 4) % 3)
+
+
+# ------------------------------------------------------------------ facts the GPU kernels' shortcuts rest on
+@pytest.mark.parametrize("N", [2, 3, 4, 8, 13])
+def test_lpt_run_of_equal_weights_visits_rails_in_load_order(N):
+    """A run of one weight w entered with max - min load < w goes round after round through the rails in
+    ascending (load, rail) order (the premise of Theorem 4's equal-granularity bound, used as a closed form
+    by the kernels).  The entry loads are made by N descending chunks, which land on rails 0..N-1."""
+    rng = np.random.default_rng(N)
+    for trial in range(30):
+        w = int(rng.integers(50, 1000))
+        loads = np.sort(rng.integers(1000, 1000 + w, size=N))[::-1].astype(np.uint32)      # spread < w, descending
+        L = int(rng.integers(1, 5 * N))
+        weights = np.concatenate([loads, np.full(L, w, dtype=np.uint32)])
+        rail, final = oracle.lpt(weights, N)
+        assert list(rail[:N]) == list(range(N))
+        order = sorted(range(N), key=lambda j: (int(loads[j]), j))
+        assert list(rail[N:]) == [order[i % N] for i in range(L)]
+        want = [int(loads[j]) + w * (L // N + (order.index(j) < L % N)) for j in range(N)]
+        assert list(final) == want
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 8, 40])
+def test_round_robin_share_of_a_position_range(N):
+    """Positions s..e-1 of a round-robin run put (e+N-1-n) div N - (s+N-1-n) div N chunks on rail n: the closed
+    form the one-call scheduler uses for the receive loads of an instance's leading run."""
+    rng = np.random.default_rng(100 + N)
+    for trial in range(200):
+        s = int(rng.integers(0, 500))
+        e = s + int(rng.integers(0, 300))
+        for n in range(N):
+            brute = sum(1 for i in range(s, e) if i % N == n)
+            assert (e + N - 1 - n) // N - (s + N - 1 - n) // N == brute
+
+
+def test_leading_run_of_a_sorted_instance_is_round_robin_with_equal_loads():
+    """Stage 3 puts all full chunks (weight C) first; from empty rails their first n_full - n_full mod N go
+    i mod N and leave every rail with C * (n_full div N): what the one-call scheduler starts stage 4 from."""
+    rng = np.random.default_rng(5)
+    M, N, C = 3, 4, 1000
+    G = M * N
+    D1 = rng.integers(0, 7 * C, size=(G, G)).astype(np.int64)
+    for k in range(M):
+        w, flow = oracle.chunk_split(D1, M, N, C, k)
+        sw, sf, _ = oracle.sort_desc(w, flow)
+        n_full = int((sw == C).sum())
+        assert np.all(sw[:n_full] == C) and np.all(sw[n_full:] < C)
+        lead = n_full - n_full % N
+        rail, _ = oracle.lpt(sw, N)
+        assert np.array_equal(rail[:lead], np.arange(lead) % N)
+        _, loads = oracle.lpt(sw[:lead], N)
+        assert np.all(loads == C * (n_full // N))
