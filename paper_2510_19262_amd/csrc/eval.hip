@@ -71,7 +71,32 @@ __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
 // wavefronts make cheaper barriers).  Receive bins: a wavefront covers 64 consecutive bins (or, when G < 64,
 // several slices side by side), the wavefronts split the slices, LDS joins them.  The six statistics are
 // reduced together: shuffles inside the wavefronts, one exchange through LDS.
-template <int THREADS>
+// R[b][base..base+63] = sum over the matrix's slots, for matrices with so many slots that one workgroup per matrix
+// would read megabytes alone: grid (ceil(G/64), batch), four wavefronts split the slots.
+__global__ __launch_bounds__(256) void eval_sum_kernel(EvArgs a)
+{
+    __shared__ int64_t part[4][64];
+    const int b = blockIdx.y, base = blockIdx.x * 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t *slots = a.partial + (int64_t)b * a.slices * (a.G + 1);
+    const int i = base + lane;
+    int64_t acc = 0;
+    if (i < a.G) {
+        int t = wave;
+        for (; t + 12 < a.slices; t += 16) {              // four independent loads in flight
+            const int64_t x0 = slots[(int64_t)t * (a.G + 1) + i], x1 = slots[(int64_t)(t + 4) * (a.G + 1) + i];
+            const int64_t x2 = slots[(int64_t)(t + 8) * (a.G + 1) + i], x3 = slots[(int64_t)(t + 12) * (a.G + 1) + i];
+            acc += (x0 + x1) + (x2 + x3);
+        }
+        for (; t < a.slices; t += 4) acc += slots[(int64_t)t * (a.G + 1) + i];
+    }
+    part[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && i < a.G) a.R[(int64_t)b * a.G + i] = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
+}
+
+// SUM: the receive bins are summed here; otherwise eval_sum_kernel has already written R.
+template <int THREADS, bool SUM>
 __global__ __launch_bounds__(THREADS) void eval_reduce_kernel(EvArgs a)
 {
     constexpr int WAVES = THREADS / 64;
@@ -87,7 +112,7 @@ __global__ __launch_bounds__(THREADS) void eval_reduce_kernel(EvArgs a)
     while (width / 2 >= a.G) width /= 2;
     const int sub = 64 / width;                       // slices a wavefront reads side by side
     const int ts = lane / width, li = lane % width;
-    for (int base = 0; base < a.G; base += 64) {
+    for (int base = 0; SUM && base < a.G; base += 64) {
         const int i = base + li;
         int64_t acc = 0;
         if (i < a.G)
@@ -161,10 +186,15 @@ __global__ __launch_bounds__(THREADS) void eval_reduce_kernel(EvArgs a)
 
 int launch_eval_reduce(const EvArgs &a, int batch, hipStream_t st)
 {
-    if ((int64_t)a.slices * a.G <= 16384 && a.M <= 256)
-        hipLaunchKernelGGL(eval_reduce_kernel<256>, dim3((unsigned)batch), dim3(256), 0, st, a);
-    else
-        hipLaunchKernelGGL(eval_reduce_kernel<1024>, dim3((unsigned)batch), dim3(1024), 0, st, a);
+    if ((int64_t)a.slices * a.G <= 16384 && a.M <= 256) {
+        hipLaunchKernelGGL((eval_reduce_kernel<256, true>), dim3((unsigned)batch), dim3(256), 0, st, a);
+    } else if ((int64_t)a.slices * a.G <= 131072) {
+        hipLaunchKernelGGL((eval_reduce_kernel<1024, true>), dim3((unsigned)batch), dim3(1024), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(eval_sum_kernel, dim3((unsigned)((a.G + 63) / 64), (unsigned)batch), dim3(256), 0, st, a);
+        if (int rc = launch_status()) return rc;
+        hipLaunchKernelGGL((eval_reduce_kernel<1024, false>), dim3((unsigned)batch), dim3(1024), 0, st, a);
+    }
     return launch_status();
 }
 
