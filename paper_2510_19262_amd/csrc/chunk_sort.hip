@@ -64,31 +64,44 @@ __global__ __launch_bounds__(64) void cs_count_kernel(CsArgs a)
 // ---- B: chunk_off = exclusive scan of instance sizes; tile_off = exclusive scan of fill tiles --
 __global__ __launch_bounds__(1024) void cs_scan_kernel(CsArgs a)
 {
-    __shared__ int64_t sh_a[1024], sh_t[1024];
-    __shared__ int64_t carry_a, carry_t;
-    const int tid = threadIdx.x;
-    if (tid == 0) { carry_a = 0; carry_t = 0; }
-    __syncthreads();
-    for (int base = 0; base < a.n_inst; base += 1024) {
-        const int i = base + tid;
-        const int64_t va = i < a.n_inst ? a.cnt_all[i] : 0;
-        const int64_t vt = i < a.n_inst ? (a.cnt_full[i] + a.tile - 1) / a.tile : 0;
-        sh_a[tid] = va; sh_t[tid] = vt;
-        __syncthreads();
-        for (int d = 1; d < 1024; d <<= 1) {
-            const int64_t xa = tid >= d ? sh_a[tid - d] : 0;
-            const int64_t xt = tid >= d ? sh_t[tid - d] : 0;
-            __syncthreads();
-            sh_a[tid] += xa; sh_t[tid] += xt;
-            __syncthreads();
+    constexpr int PER = 4;                            // consecutive instances per thread and round
+    __shared__ int64_t sh_a[16], sh_t[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile_shift = __builtin_ctz((unsigned)a.tile);   // the tile is a power of two
+    int64_t carry_a = 0, carry_t = 0;                 // the same in every thread
+    for (int base = 0; base < a.n_inst; base += 1024 * PER) {
+        int64_t va[PER], vt[PER], sa = 0, st = 0;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int i = base + tid * PER + u;
+            va[u] = i < a.n_inst ? a.cnt_all[i] : 0;
+            vt[u] = i < a.n_inst ? (a.cnt_full[i] + a.tile - 1) >> tile_shift : 0;
+            sa += va[u]; st += vt[u];
         }
-        if (i < a.n_inst) {
-            a.chunk_off[i] = carry_a + sh_a[tid] - va;
-            a.tile_off[i] = carry_t + sh_t[tid] - vt;
+        int64_t ia = sa, it = st;                     // inclusive scans of the thread sums inside the wavefront
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int64_t xa = __shfl_up(ia, d), xt = __shfl_up(it, d);
+            if (lane >= d) { ia += xa; it += xt; }
         }
+        __syncthreads();                              // the round before is done with sh_a / sh_t
+        if (lane == 63) { sh_a[wave] = ia; sh_t[wave] = it; }
         __syncthreads();
-        if (tid == 1023) { carry_a += sh_a[1023]; carry_t += sh_t[1023]; }
-        __syncthreads();
+        int64_t before_a = 0, before_t = 0, tot_a = 0, tot_t = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int64_t xa = sh_a[w], xt = sh_t[w];
+            if (w < wave) { before_a += xa; before_t += xt; }
+            tot_a += xa; tot_t += xt;
+        }
+        int64_t oa = carry_a + before_a + ia - sa, ot = carry_t + before_t + it - st;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int i = base + tid * PER + u;
+            if (i < a.n_inst) { a.chunk_off[i] = oa; a.tile_off[i] = ot; }
+            oa += va[u]; ot += vt[u];
+        }
+        carry_a += tot_a; carry_t += tot_t;
     }
     if (tid == 0) { a.chunk_off[a.n_inst] = carry_a; a.tile_off[a.n_inst] = carry_t; }
 }
