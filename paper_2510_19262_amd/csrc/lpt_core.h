@@ -23,12 +23,13 @@ __device__ __forceinline__ unsigned dpp_mov(unsigned v)
     return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 
-// min(v, v of the partner lane).  The partner value is fetched with "old" = UINT_MAX, the identity
-// of unsigned min, which lets the compiler fold the lane exchange into one v_min_u32 with a DPP operand.
+// min(v, v of the partner lane).  Every lane has a partner under the controls used here, so bound_ctrl changes
+// nothing - but it frees the compiler from tying the destination to an "old" value, and the exchange folds
+// into one v_min_u32 with a DPP operand and no register copy in front of it.
 template <int CTRL>
 __device__ __forceinline__ unsigned dpp_min(unsigned v)
 {
-    return min(v, (unsigned)__builtin_amdgcn_update_dpp((int)0xFFFFFFFF, (int)v, CTRL, 0xF, 0xF, false));
+    return min(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true));
 }
 template <int CTRL>
 __device__ __forceinline__ unsigned dpp_max(unsigned v)
@@ -204,7 +205,8 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
 #pragma unroll 8
                 for (int t = 0; t < P; ++t) {
                     const unsigned wS = (unsigned)__builtin_amdgcn_readlane((int)wv, t) << S;
-                    const unsigned bumped = key + wS;
+                    unsigned bumped = key + wS;
+                    asm volatile("" : "+v"(bumped));   // keep the sum off the chain: stops the rewrite into key + select(w, 0)
                     const unsigned m = group_min_u32<GW>(key);
                     won = (lane == t) ? m : won;
                     key = (key == m) ? bumped : key;

@@ -195,7 +195,8 @@ __device__ __forceinline__ void fast_steps(unsigned &key, const unsigned (&bc)[S
 {
     // chunk T of the period; the serial chain is: group min (log2 GW exchanges), compare, select
     if constexpr (T < STEP) {
-        const unsigned bumped = key + bc[T];        // off the chain: does not need the minimum
+        unsigned bumped = key + bc[T];              // off the chain: does not need the minimum
+        asm volatile("" : "+v"(bumped));           // (stops the rewrite into key + select(w, 0), which puts the add on the chain)
         const unsigned m = group_min_u32<GW>(key);
         won[T / GW] = (q == (unsigned)(T % GW)) ? m : won[T / GW];
         key = (key == m) ? bumped : key;
