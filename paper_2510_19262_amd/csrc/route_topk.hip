@@ -295,17 +295,43 @@ __global__ __launch_bounds__(256) void route_topk_keys_kernel(const float *__res
 // The value cut is validated as in the rounds kernel: neighbouring winners must differ above the index bits, and
 // exactly k keys of the row may reach the cut value of the k-th winner; other row groups are redone exactly.
 // ---------------------------------------------------------------------------------------------
+// max(v, v of the partner lane) with the exchange folded into the v_max_u32 (every lane has a partner under these
+// controls, so bound_ctrl changes nothing but lets the compiler drop the copy in front)
+template <int OFF>
+__device__ __forceinline__ unsigned max_with_partner(unsigned mine, unsigned theirs)
+{
+    constexpr int CTRL = OFF == 1 ? 0xB1 : OFF == 2 ? 0x4E : OFF == 4 ? 0x141 : 0x140;
+    return max(mine, (unsigned)__builtin_amdgcn_update_dpp(0, (int)theirs, CTRL, 0xF, 0xF, true));
+}
+
+// the 8 largest of this lane's and its partner's descending lists; both partners end with the same list
 template <int OFF>
 __device__ __forceinline__ void merge_with_partner(unsigned (&a)[8])
 {
-    unsigned b[8];
+    static_assert(OFF == 1 || OFF == 2 || OFF == 4 || OFF == 8, "exchanges inside a row of 16 lanes");
+    unsigned n[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) b[i] = xlane<OFF>(a[i]);
-    top8_of_two(a, b);
+    for (int i = 0; i < 8; ++i) n[i] = max_with_partner<OFF>(a[i], a[7 - i]);   // the top half, as a bitonic sequence
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = n[i];
+    sort2_desc(a[0], a[4]); sort2_desc(a[1], a[5]); sort2_desc(a[2], a[6]); sort2_desc(a[3], a[7]);
+    sort2_desc(a[0], a[2]); sort2_desc(a[1], a[3]); sort2_desc(a[4], a[6]); sort2_desc(a[5], a[7]);
+    sort2_desc(a[0], a[1]); sort2_desc(a[2], a[3]); sort2_desc(a[4], a[5]); sort2_desc(a[6], a[7]);
+}
+
+// key of a logit for the merge kernel: -0 becomes +0 by adding +0 (exact for every other finite value), the
+// expert's inverted index arrives ready-made
+template <unsigned MASK>
+__device__ __forceinline__ unsigned make_key_inv(float f, unsigned inv_idx)
+{
+    const unsigned b = (unsigned)__float_as_int(f + 0.0f);
+    const unsigned ord = b ^ ((unsigned)((int)b >> 31) | 0x80000000u);  // monotone float -> unsigned
+    return (ord & ~MASK) | inv_idx;
 }
 
 // WAVES: resident wavefronts per SIMD the register allocation is held to (more for short per-lane key arrays).
-template <int LANES, int VPL, int WAVES>
+// FULL: E == LANES * VPL, every load is in range (rows beyond the last repeat the last row and are not stored).
+template <int LANES, int VPL, int WAVES, bool FULL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, 8))) void route_topk_merge_kernel(const float *__restrict__ logits, int64_t rows, int E, int k,
                                                                int32_t *__restrict__ topk_idx)
 {
@@ -325,18 +351,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, 8)))
         const bool live = row < rows;
         // no prefetch of the next row: the registers buy more resident wavefronts, which hide the loads as well
         float4 x[NV];
+        const int64_t lrow = live ? row : rows - 1;
 #pragma unroll
         for (int c = 0; c < NV; ++c) {
             const int e0 = 4 * (q + LANES * c);
-            x[c] = (live && e0 < E) ? load_stream4(logits + row * E + e0) : none;
+            if constexpr (FULL) x[c] = load_stream4(logits + lrow * E + e0);
+            else x[c] = (live && e0 < E) ? load_stream4(logits + row * E + e0) : none;   // -inf ranks below every logit
         }
         unsigned key[VPL];
+        const unsigned inv0 = MASK - 4u * (unsigned)q;                  // inverted index of this lane's first logit
 #pragma unroll
         for (int c = 0; c < NV; ++c) {
-            const int e0 = 4 * (q + LANES * c);
-            const bool has = live && e0 < E;
-            key[4 * c + 0] = has ? make_key<MASK>(x[c].x, e0 + 0) : 0u; key[4 * c + 1] = has ? make_key<MASK>(x[c].y, e0 + 1) : 0u;
-            key[4 * c + 2] = has ? make_key<MASK>(x[c].z, e0 + 2) : 0u; key[4 * c + 3] = has ? make_key<MASK>(x[c].w, e0 + 3) : 0u;
+            const unsigned inv = inv0 - (unsigned)(4 * LANES * c);
+            key[4 * c + 0] = make_key_inv<MASK>(x[c].x, inv); key[4 * c + 1] = make_key_inv<MASK>(x[c].y, inv - 1u);
+            key[4 * c + 2] = make_key_inv<MASK>(x[c].z, inv - 2u); key[4 * c + 3] = make_key_inv<MASK>(x[c].w, inv - 3u);
         }
         unsigned lst[8];                                                // descending: the best 8 seen so far
 #pragma unroll
@@ -355,7 +383,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, 8)))
         if constexpr (LANES >= 8) merge_with_partner<4>(lst);
         if constexpr (LANES >= 16) merge_with_partner<8>(lst);
 
-        // lst[j] = j-th largest key of the row (0 where the row has fewer than 8 logits), the same in all its lanes
+        // lst[j] = j-th largest key of the row, the same in all its lanes
         unsigned kth = lst[0];
         bool bad = false;
 #pragma unroll
@@ -423,7 +451,10 @@ static int launch_topk_merge(const float *logits, int64_t rows, int E, int k, in
     int64_t blocks = (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
     const int64_t cap = 1 << 22;    // one row group per wavefront measured fastest; only absurd sizes loop
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL((route_topk_merge_kernel<LANES, VPL, WAVES>), dim3((unsigned)blocks), dim3(256), 0, st, logits, rows, E, k, out);
+    if (E == LANES * VPL)
+        hipLaunchKernelGGL((route_topk_merge_kernel<LANES, VPL, WAVES, true>), dim3((unsigned)blocks), dim3(256), 0, st, logits, rows, E, k, out);
+    else
+        hipLaunchKernelGGL((route_topk_merge_kernel<LANES, VPL, WAVES, false>), dim3((unsigned)blocks), dim3(256), 0, st, logits, rows, E, k, out);
     return launch_status();
 }
 

@@ -117,6 +117,18 @@ def test_topk_rows_full_of_exact_ties(E, k, rows):
     assert np.array_equal(got, oracle.route_topk(x, k))
 
 
+@pytest.mark.parametrize("E,k", [(64, 8), (128, 5), (256, 8), (8, 2), (200, 8)])
+def test_topk_denormals_and_signed_zeros(E, k):
+    # denormal logits of both signs, +0 and -0 (which tie), tiny normals: order must be the IEEE one
+    rng = np.random.default_rng(E + 3 * k)
+    rows = 2000
+    pool = np.array([0.0, -0.0, 1e-45, -1e-45, 3e-39, -3e-39, 1.1754944e-38, -1.1754944e-38, 1e-30, -1e-30, 2e-45, -2e-45],
+                    dtype=np.float32)
+    x = rng.choice(pool, size=(rows, E)).astype(np.float32)
+    got = rs.route_topk(torch.from_numpy(x).to(DEV), k).cpu().numpy()
+    assert np.array_equal(got, oracle.route_topk(x, k))
+
+
 def test_topk_unaligned_rows_and_empty():
     x = torch.randn(1001 * 8 + 1, device=DEV)[1:].view(1001, 8)   # base pointer off 16-byte alignment
     assert np.array_equal(rs.route_topk(x.contiguous(), 2).cpu().numpy(), oracle.route_topk(x.cpu().numpy(), 2))
