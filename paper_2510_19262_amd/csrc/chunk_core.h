@@ -20,6 +20,7 @@ struct CsArgs {
     int32_t tile;        // full-chunk positions per fill tile
     uint8_t *rail;       // when set, the fill also writes the rails of every instance's leading run (see cs_fill_kernel)
     int32_t nmask;       // N - 1 when N is a power of two, else -1
+    int32_t gmask, nshift;   // G - 1 and log2 N when G / N are powers of two, else -1
 };
 
 __device__ __forceinline__ void split_bytes(const CsArgs &a, int64_t B, uint32_t &q, uint32_t &r)
@@ -38,21 +39,32 @@ __device__ __forceinline__ void split_bytes(const CsArgs &a, int64_t B, uint32_t
 // bytes of flow f of instance (b, k); 0 for destinations inside node k unless intra-node traffic is kept
 __device__ __forceinline__ int64_t flow_bytes(const CsArgs &a, const int64_t *rows, int k, int f)
 {
-    const int dst = f % a.G;
-    if (!a.intra && dst / a.N == k) return 0;
+    if (!a.intra) {
+        const int node = (a.gmask >= 0 && a.nshift >= 0) ? ((f & a.gmask) >> a.nshift) : (f % a.G) / a.N;   // of the destination
+        if (node == k) return 0;
+    }
     return rows[f];
 }
 
+// v of the lane the DPP control points at, 0 where there is none (or where row_mask switches the row off)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ unsigned dpp_or_zero(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+
+// Exclusive prefix sum over the 64 lanes (and the total), all in the vector ALU: four shifted adds inside the
+// rows of 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.
 __device__ __forceinline__ unsigned wave_exscan(unsigned v, unsigned &total)
 {
-    const int lane = threadIdx.x & 63;
     unsigned inc = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const unsigned o = __shfl_up(inc, d);
-        if (lane >= d) inc += o;
-    }
-    total = __shfl(inc, 63);
+    inc += dpp_or_zero<0x111, 0xF>(inc);            // row_shr:1
+    inc += dpp_or_zero<0x112, 0xF>(inc);            // row_shr:2
+    inc += dpp_or_zero<0x114, 0xF>(inc);            // row_shr:4
+    inc += dpp_or_zero<0x118, 0xF>(inc);            // row_shr:8
+    inc += dpp_or_zero<0x142, 0xA>(inc);            // row_bcast15 into rows 1 and 3
+    inc += dpp_or_zero<0x143, 0xC>(inc);            // row_bcast31 into rows 2 and 3
+    total = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
     return inc - v;
 }
 

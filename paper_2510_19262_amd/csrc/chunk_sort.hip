@@ -126,17 +126,14 @@ __global__ __launch_bounds__(64) void cs_tail_kernel(CsArgs a)
     idx_a = sorted;
 
     const int64_t out0 = a.chunk_off[inst] + a.cnt_full[inst];
-    const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
     const uint32_t *cs = a.canon_start + (int64_t)inst * a.NF;
-    const uint32_t n_full = (uint32_t)a.cnt_full[inst];
+    const uint32_t n_all = (uint32_t)a.cnt_all[inst];
     for (int i = lane; i < nt; i += 64) {
         const int f = idx_a[i];
         a.chunk_w[out0 + i] = rem[f];
         a.chunk_flow[out0 + i] = (uint32_t)f;
-        if (a.perm) {
-            const uint32_t qf = (f + 1 < a.NF ? fs[f + 1] : n_full) - fs[f];
-            a.perm[out0 + i] = cs[f] + qf;                               // the tail is the flow's last chunk
-        }
+        // the tail is its flow's last chunk: one before the canonical start of the next flow
+        if (a.perm) a.perm[out0 + i] = (f + 1 < a.NF ? cs[f + 1] : n_all) - 1u;
     }
 }
 
@@ -356,6 +353,8 @@ int cs_run(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int
     a.n_inst = (int32_t)n_inst;
     a.rail = rail;
     a.nmask = is_pow2(N) ? (int32_t)N - 1 : -1;
+    a.gmask = is_pow2(G) ? (int32_t)G - 1 : -1;
+    a.nshift = is_pow2(N) ? ilog2(N) : -1;
     if (args_out) *args_out = a;
 
     if (n_inst > 0) {

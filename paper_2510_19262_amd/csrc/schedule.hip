@@ -357,6 +357,8 @@ extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsc
     a.M = (int32_t)M; a.N = (int32_t)N; a.G = (int32_t)G; a.NF = (int32_t)NF; a.intra = h_topo->include_intra_node;
     a.n_inst = (int32_t)n_inst;
     a.rail = nullptr; a.nmask = -1;                 // unused by the count kernel
+    a.gmask = is_pow2(G) ? (int32_t)G - 1 : -1;
+    a.nshift = is_pow2(N) ? ilog2(N) : -1;
     launch_cs_count(a, st);
     if (int rc = launch_status()) return rc;
 
