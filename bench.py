@@ -41,6 +41,9 @@ def parse():
                     help="c3/c5: matrices per step (0 = all of c3, one of c5: a c5 matrix alone is 3.9e9 chunks)")
     ap.add_argument("--cpu-layers", type=int, default=-1,
                     help="layers of the workload the CPU oracle is timed on (-1 = all, 0 = skip)")
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="only the two timed regions (fused and staged step): no supplementary measurements; used for profiles, "
+                         "so that a kernel's average duration is that of the timed region")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device copy first: a kernel of known traffic to scale profiler byte counters by")
     return ap.parse_args()
@@ -148,65 +151,70 @@ def main():
 
     assert int(plan.chunk_off[-1].item()) == total_chunks
 
-    # ---- supplementary: throughput with two steps in flight (two streams of default priority, outputs double-buffered):
-    # the latency-bound stages 3-5 of one step run beside the bandwidth-bound stages 1-2 of the next
-    plan_b = rs.Plan(topo, B, total_chunks, dev, rows=rows, k=cfg.k, want_perm=True)
-    ws_rt_b = torch.empty_like(ws_rt)
-    lanes = ((plan, ws_rt, torch.cuda.Stream()), (plan_b, ws_rt_b, torch.cuda.Stream()))
-
-    def piped(i):
-        p, w, s_ = lanes[i % 2]
-        with torch.cuda.stream(s_):
-            rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=(p.topk_idx, p.D1), ws=w)
-            p.schedule_one_call()
-    for i in range(2 * max(args.warmup, 1)):
-        piped(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(2 * args.steps):
-        piped(i)
-    torch.cuda.synchronize()
-    piped_ms = (time.perf_counter() - t0) * 1e3 / (2 * args.steps)
-    assert torch.equal(plan_b.stats, plan.stats) and torch.equal(plan_b.rail, plan.rail) and torch.equal(plan_b.R, plan.R)
-    del plan_b, ws_rt_b
-
-    # ---- supplementary: the plain per-chunk LPT kernel on the same records (same outputs, no closed-form periods)
-    rail2, S2 = torch.empty_like(plan.rail), torch.empty_like(plan.S)
-    cw = []
-    for i in range(3 + min(args.steps, 10)):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(rail2, S2), chunkwise=True)
-        e1.record()
-        cw.append((e0, e1))
-    torch.cuda.synchronize()
-    chunkwise_ms = sum(a.elapsed_time(b) for a, b in cw[3:]) / max(len(cw) - 3, 1)
-    assert torch.equal(rail2[:total_chunks], plan.rail[:total_chunks]) and torch.equal(S2, plan.S)
+    piped_ms = chunkwise_ms = None
+    schemes = combine = None
     stats = plan.stats.cpu().numpy()
     ratio = stats[:, 0] / np.maximum(stats[:, 3], 1)
+    if not args.skip_extras:
+        # ---- supplementary: throughput with two steps in flight (two streams of default priority, outputs double-buffered):
+        # the latency-bound stages 3-5 of one step run beside the bandwidth-bound stages 1-2 of the next
+        plan_b = rs.Plan(topo, B, total_chunks, dev, rows=rows, k=cfg.k, want_perm=True)
+        ws_rt_b = torch.empty_like(ws_rt)
+        lanes = ((plan, ws_rt, torch.cuda.Stream()), (plan_b, ws_rt_b, torch.cuda.Stream()))
 
-    # ---- supplementary: the comparison schemes on the same chunk records, and the second all-to-all (transposed traffic)
-    def timed(fn):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        fn(); e0.record(); fn(); e1.record(); torch.cuda.synchronize()
-        return e0.elapsed_time(e1)
-    R2, stats2 = torch.empty_like(plan.R), torch.empty_like(plan.stats)
-    schemes = {"lpt": {"makespan_over_lb_max": float(ratio.max()), "makespan_over_lb_mean": float(ratio.mean())}}
-    for pol in ("nic_direct", "flow_hash", "random_spray", "round_robin"):
-        ms = timed(lambda: rs.assign_policy(pol, 1, plan.chunk_off, plan.chunk_w, plan.chunk_flow, B, topo, out=(rail2, S2)))
-        rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, rail2, S2, B, topo, out=(R2, stats2), ws=plan.ws_eval)
-        st2 = stats2.cpu().numpy()
-        r2 = st2[:, 0] / np.maximum(st2[:, 3], 1)
-        schemes[pol] = {"makespan_over_lb_max": float(r2.max()), "makespan_over_lb_mean": float(r2.mean()), "assign_ms": ms}
-    D1T = torch.empty_like(plan.D1)
-    tr_ms = timed(lambda: rs.transpose_matrix(plan.D1, topo, out=D1T))
-    n_comb = int(rs.chunk_count(D1T, topo, plan.ws_sort)[-1].item())
-    plan_c = rs.Plan(topo, B, n_comb, dev, want_perm=True)
-    comb_ms = timed(lambda: plan_c.schedule_one_call(D1T))
-    st_c = plan_c.stats.cpu().numpy()
-    r_c = st_c[:, 0] / np.maximum(st_c[:, 3], 1)
-    combine = {"transpose_ms": tr_ms, "schedule_ms": comb_ms, "chunks": n_comb, "makespan_over_lb_max": float(r_c.max())}
-    rs.chunk_sort(plan.D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
+        def piped(i):
+            p, w, s_ = lanes[i % 2]
+            with torch.cuda.stream(s_):
+                rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=(p.topk_idx, p.D1), ws=w)
+                p.schedule_one_call()
+        for i in range(2 * max(args.warmup, 1)):
+            piped(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(2 * args.steps):
+            piped(i)
+        torch.cuda.synchronize()
+        piped_ms = (time.perf_counter() - t0) * 1e3 / (2 * args.steps)
+        assert torch.equal(plan_b.stats, plan.stats) and torch.equal(plan_b.rail, plan.rail) and torch.equal(plan_b.R, plan.R)
+        del plan_b, ws_rt_b
+
+        # ---- supplementary: the plain per-chunk LPT kernel on the same records (same outputs, no closed-form periods)
+        rail2, S2 = torch.empty_like(plan.rail), torch.empty_like(plan.S)
+        cw = []
+        for i in range(3 + min(args.steps, 10)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(rail2, S2), chunkwise=True)
+            e1.record()
+            cw.append((e0, e1))
+        torch.cuda.synchronize()
+        chunkwise_ms = sum(a.elapsed_time(b) for a, b in cw[3:]) / max(len(cw) - 3, 1)
+        assert torch.equal(rail2[:total_chunks], plan.rail[:total_chunks]) and torch.equal(S2, plan.S)
+        stats = plan.stats.cpu().numpy()
+        ratio = stats[:, 0] / np.maximum(stats[:, 3], 1)
+
+        # ---- supplementary: the comparison schemes on the same chunk records, and the second all-to-all (transposed traffic)
+        def timed(fn):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn(); e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+            return e0.elapsed_time(e1)
+        R2, stats2 = torch.empty_like(plan.R), torch.empty_like(plan.stats)
+        schemes = {"lpt": {"makespan_over_lb_max": float(ratio.max()), "makespan_over_lb_mean": float(ratio.mean())}}
+        for pol in ("nic_direct", "flow_hash", "random_spray", "round_robin"):
+            ms = timed(lambda: rs.assign_policy(pol, 1, plan.chunk_off, plan.chunk_w, plan.chunk_flow, B, topo, out=(rail2, S2)))
+            rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, rail2, S2, B, topo, out=(R2, stats2), ws=plan.ws_eval)
+            st2 = stats2.cpu().numpy()
+            r2 = st2[:, 0] / np.maximum(st2[:, 3], 1)
+            schemes[pol] = {"makespan_over_lb_max": float(r2.max()), "makespan_over_lb_mean": float(r2.mean()), "assign_ms": ms}
+        D1T = torch.empty_like(plan.D1)
+        tr_ms = timed(lambda: rs.transpose_matrix(plan.D1, topo, out=D1T))
+        n_comb = int(rs.chunk_count(D1T, topo, plan.ws_sort)[-1].item())
+        plan_c = rs.Plan(topo, B, n_comb, dev, want_perm=True)
+        comb_ms = timed(lambda: plan_c.schedule_one_call(D1T))
+        st_c = plan_c.stats.cpu().numpy()
+        r_c = st_c[:, 0] / np.maximum(st_c[:, 3], 1)
+        combine = {"transpose_ms": tr_ms, "schedule_ms": comb_ms, "chunks": n_comb, "makespan_over_lb_max": float(r_c.max())}
+        rs.chunk_sort(plan.D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
 
     # ---- roofline of the dominant kernel (route_traffic streams the logits once and writes the indices once)
     k1_bytes = rows * (4 * cfg.E + 4 * cfg.k)
@@ -238,8 +246,9 @@ def main():
         "staged": {"ms_per_step": staged_ms_per_step, "value": total_chunks / (staged_ms_per_step * 1e-3), "stage_ms": staged_ms,
                    "note": "the same step through the five separate calls (indices written, then read back)",
                    "route_topk_GBps": k1_gbps, "routing_to_traffic_matrix_GBps": staged_routing_gbps},
-        "two_steps_in_flight": {"ms_per_step": piped_ms, "value": total_chunks / (piped_ms * 1e-3),
-                                "note": "same two calls per step, consecutive steps alternating between two streams and two sets of outputs"},
+        "two_steps_in_flight": None if piped_ms is None else {
+            "ms_per_step": piped_ms, "value": total_chunks / (piped_ms * 1e-3),
+            "note": "same two calls per step, consecutive steps alternating between two streams and two sets of outputs"},
         "routing_to_traffic_matrix_GBps": rt_gbps,
         "routing_frac_of_hbm_peak": rt_gbps / HBM_PEAK_GBPS,
         "lpt_spray_chunks_per_s": lpt_rate,
