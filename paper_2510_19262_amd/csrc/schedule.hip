@@ -50,6 +50,7 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
     extern __shared__ unsigned long long ss_lds64[];
     __shared__ int64_t sh_red[2][kSsThreads / 64];
     __shared__ unsigned sh_wmax;
+    __shared__ int sh_nt, sh_sorted_in_b;                                // wavefront 0's sort result, for the others
     // LDS: bins[G] u64 | st_fs[NF+1] | st_cs[NF] | rem[NF] | hist[256] | late_w[NF+64] | idx_a[NF] idx_b[NF] u16 | late_rail[NF+64] u8
     unsigned long long *bins = ss_lds64;
     unsigned *st_fs = reinterpret_cast<unsigned *>(bins + a.G);
@@ -74,6 +75,7 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
     if (wave == 0) {
         const int64_t *rows = a.D1 + ((int64_t)b * a.G + (int64_t)k * a.N) * a.G;
         sorted = tail_sort_wave<false>(a, rows, k, rem, hist, idx_a, idx_b, nt);
+        if (lane == 0) { sh_nt = nt; sh_sorted_in_b = sorted == idx_b ? 1 : 0; }
     } else {
         constexpr int T = kSsThreads - 64;
         const int t = tid - 64;
@@ -98,6 +100,8 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
 #pragma unroll
     for (int w = 0; w < kSsThreads / 64; ++w) { before += sh_red[0][w]; total += sh_red[1][w]; }
     const int64_t out0 = before;
+    nt = sh_nt;
+    sorted = sh_sorted_in_b ? idx_b : idx_a;
     if (tid == 0) {
         a.chunk_off[inst] = out0;
         if (inst == a.n_inst - 1) a.chunk_off[a.n_inst] = total;
@@ -110,19 +114,8 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
     const uint32_t late_full = n_full - skip;                            // full chunks left to the chain (< N)
 
     if (wave == 0) {
-        // ---- tails: write, then the serial chain over [late full chunks | sorted tails]
-        const int64_t tail0 = out0 + n_full;
-        for (int i = lane; i < nt; i += 64) {
-            const int f = sorted[i];
-            const uint32_t w = rem[f];
-            late_w[late_full + i] = w;
-            a.chunk_w[tail0 + i] = w;
-            a.chunk_flow[tail0 + i] = (uint32_t)f;
-            if (a.perm) {
-                const uint32_t qf = (f + 1 < a.NF ? st_fs[f + 1] : n_full) - st_fs[f];
-                a.perm[tail0 + i] = st_cs[f] + qf;                       // the tail is the flow's last chunk
-            }
-        }
+        // ---- the serial chain over [late full chunks | sorted tails]; the others write the tails' records
+        for (int i = lane; i < nt; i += 64) late_w[late_full + i] = rem[sorted[i]];
         if (lane < (int)late_full) late_w[lane] = cw;
         if (lane == 0) sh_wmax = n_full ? cw : (nt ? rem[sorted[0]] : 0u);
         lds_sync<false>();
@@ -141,6 +134,14 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
         // ---- full chunks: records, rails of the leading run, receive loads of the leading run
         const int t = tid - 64;
         constexpr int T = kSsThreads - 64;
+        const int64_t tail0 = out0 + n_full;
+        for (int i = t; i < nt; i += T) {
+            const int f = sorted[i];
+            a.chunk_w[tail0 + i] = rem[f];
+            a.chunk_flow[tail0 + i] = (uint32_t)f;
+            // the tail is its flow's last chunk: one before the canonical start of the next flow
+            if (a.perm) a.perm[tail0 + i] = (f + 1 < a.NF ? st_cs[f + 1] : n_all) - 1u;
+        }
         if (x.vec_ok) {
             const uint32_t head = (uint32_t)((4 - (out0 & 3)) & 3);      // scalar positions before the first aligned group
             const uint32_t pa = n_full < head ? n_full : head;
@@ -204,7 +205,6 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
         }
     }
     __syncthreads();
-    (void)n_all;
     int64_t *slot = x.partial + (int64_t)inst * (a.G + 1);               // [b][k][G + 1]
     for (int i = tid; i < a.G; i += kSsThreads) slot[i] = (int64_t)bins[i];
     if (tid == 0) slot[a.G] = (int64_t)sh_wmax;
