@@ -120,6 +120,28 @@ def test_lpt_beats_the_comparison_schemes_on_config2_shape():
         assert np.all(st[:, 1] >= st_lpt[:, 1])                      # LPT's worst send NIC is never worse
 
 
+def test_policy_and_ports_on_record_arrays_off_16_byte_alignment():
+    # records 4 bytes, rails and ports 1 byte past an aligned address: the scalar paths of the comparison schemes
+    M, N, C, B, P = 4, 8, 4096, 3, 5
+    rng = np.random.default_rng(99)
+    D1 = _rand_stack(rng, B, M * N, C)
+    topo = rs.Topo(M, N, C)
+    off, w0, flow0 = _records_dev(D1, topo)
+    n = int(off[-1].item())
+    w = torch.empty(n + 8, dtype=torch.int32, device=DEV)[1:n + 1].copy_(w0[:n])
+    flow = torch.empty(n + 8, dtype=torch.int32, device=DEV)[1:n + 1].copy_(flow0[:n])
+    off_h, w_h, flow_h = off.cpu().numpy(), _u32(w0)[:n], _u32(flow0)[:n]
+    for policy in ("nic_direct", "flow_hash", "random_spray", "round_robin"):
+        rail = torch.empty(n + 8, dtype=torch.uint8, device=DEV)[1:n + 1]
+        S = torch.empty((B, M, N), dtype=torch.int64, device=DEV)
+        rs.assign_policy(policy, 11, off, w, flow, B, topo, out=(rail, S))
+        rail_c, S_c = oracle.assign_policy(policy, 11, off_h, w_h, flow_h, B, M, N)
+        assert np.array_equal(rail.cpu().numpy(), rail_c) and np.array_equal(S.cpu().numpy(), S_c), policy
+        port = torch.empty(n + 8, dtype=torch.uint8, device=DEV)[1:n + 1]
+        rs.port_round_robin(off, rail, B, topo, P, capacity=n, out=port)
+        assert np.array_equal(port.cpu().numpy(), oracle.port_round_robin(off_h, rail_c, B, M, N, P)), policy
+
+
 @pytest.mark.parametrize("M,N,C,B,P", [(4, 4, 4096, 2, 4), (3, 5, 1000, 3, 3), (8, 8, 65536, 2, 256), (2, 33, 256, 1, 1), (2, 64, 128, 1, 7)])
 def test_port_round_robin_matches_oracle(M, N, C, B, P):
     rng = np.random.default_rng(M + N + P)

@@ -565,3 +565,41 @@ def test_config4_shape_reduced_tokens():
     D1_c = oracle.traffic_matrix(idx_c, 1, cfg.tokens_per_gpu, W.expert_gpu_table(cfg), cfg.payload_bytes, cfg.M, cfg.N)
     assert np.array_equal(D1.cpu().numpy(), D1_c)
     assert_same(gpu_schedule(D1_c, topo), cpu_schedule(D1_c, cfg.M, cfg.N, cfg.chunk_bytes), "c4 ")
+
+
+# ------------------------------------------------------------------------------ record arrays off their natural alignment
+@pytest.mark.parametrize("M,N,C,B", [(4, 4, 4096, 2), (8, 8, 262144, 3), (4, 2, 512, 400), (3, 20, 512, 2)])
+def test_record_arrays_off_16_byte_alignment(M, N, C, B):
+    # chunk_w / chunk_flow / perm start 4 bytes, rail 1 byte past an aligned address: the scalar paths of every kernel
+    rng = np.random.default_rng(M * 31 + N * 7 + B)
+    D1n = _rand_stack(rng, B, M * N, C)
+    c = cpu_schedule(D1n, M, N, C)
+    n = int(c["off"][-1])
+    topo = rs.Topo(M, N, C)
+    D1 = torch.from_numpy(D1n).to(DEV)
+
+    def bufs():
+        w = torch.empty(n + 8, dtype=torch.int32, device=DEV)[1:n + 1]
+        flow = torch.empty(n + 8, dtype=torch.int32, device=DEV)[1:n + 1]
+        perm = torch.empty(n + 8, dtype=torch.int32, device=DEV)[1:n + 1]
+        rail = torch.empty(n + 8, dtype=torch.uint8, device=DEV)[1:n + 1]
+        return w, flow, perm, rail
+
+    def same(off, w, flow, perm, rail, S, R, stats, what):
+        g = dict(off=off.cpu().numpy(), w=_u32(w)[:n], flow=_u32(flow)[:n], perm=_u32(perm)[:n], rail=rail.cpu().numpy()[:n],
+                 S=S.cpu().numpy(), R=R.cpu().numpy(), stats=stats.cpu().numpy())
+        assert_same(g, c, what)
+
+    w, flow, perm, rail = bufs()
+    off = torch.empty(B * M + 1, dtype=torch.int64, device=DEV)
+    S = torch.empty((B, M, N), dtype=torch.int64, device=DEV)
+    rs.chunk_sort(D1, topo, capacity=n, out=(off, w, flow, perm))
+    rs.lpt_spray(off, w, B, topo, out=(rail, S))
+    R, stats = rs.eval(off, w, flow, rail, S, B, topo)
+    same(off, w, flow, perm, rail, S, R, stats, "three calls")
+
+    w, flow, perm, rail = bufs()
+    out = (torch.empty(B * M + 1, dtype=torch.int64, device=DEV), w, flow, perm, rail, torch.empty_like(S), torch.empty_like(S),
+           torch.empty((B, 8), dtype=torch.int64, device=DEV))
+    rs.schedule(D1, topo, n, out=out)
+    same(*out, "one call")
