@@ -144,6 +144,7 @@ __device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsi
 //
 // lpt_wide_body schedules the `len` chunks whose weights start at wsrc (rails to rdst) from rails that
 // all hold `base` bytes, and leaves the final loads in S_row[0..N).  Called by a whole wavefront.
+// `spare` points at one readable word in the same kind of memory as wsrc (see the ring of weights below).
 constexpr int kWideDepth = 4;       // periods of 64 chunks in flight per wavefront
 
 template <int GW> struct WideLimit {
@@ -154,7 +155,8 @@ template <int GW> struct WideLimit {
 
 template <int GW, bool RUNS>
 __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc, uint8_t *__restrict__ rdst, int64_t len,
-                                              unsigned long long base, int N, int64_t *__restrict__ S_row)
+                                              unsigned long long base, int N, int64_t *__restrict__ S_row,
+                                              const uint32_t *__restrict__ spare)
 {
     constexpr int S = GroupBits<GW>::S;
     constexpr int P = 64;                           // chunks per period: one per lane
@@ -170,20 +172,21 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
     const unsigned per_rank = (unsigned)(P / N), extra = (unsigned)(P % N);
     const unsigned want = (unsigned)lane % (unsigned)N;
 
+    // Lanes past the end load *spare (any word that exists, in the memory wsrc points into) instead of skipping the
+    // load, and the value is masked where it is used: with no branch around the loads the compiler can count them,
+    // so the wait before a period's chain covers that period's weights only and kWideDepth - 1 loads stay in flight.
+    auto weight_at = [&](int64_t i) { const uint32_t *src = (i < len) ? wsrc + i : spare; return *src; };
     unsigned ring[kWideDepth];
 #pragma unroll
-    for (int d = 0; d < kWideDepth; ++d) ring[d] = ((int64_t)d * P + lane < len) ? wsrc[(int64_t)d * P + lane] : 0u;
+    for (int d = 0; d < kWideDepth; ++d) ring[d] = weight_at((int64_t)d * P + lane);
 
     for (int64_t i0 = 0; i0 < len; i0 += (int64_t)kWideDepth * P) {
 #pragma unroll
         for (int d = 0; d < kWideDepth; ++d) {
             const int64_t p0 = i0 + (int64_t)d * P;
             if (p0 >= len) break;                   // wave-uniform
-            const unsigned wv = ring[d];
-            {
-                const int64_t nx = p0 + (int64_t)kWideDepth * P + lane;   // refill this slot: kWideDepth periods ahead
-                ring[d] = (nx < len) ? wsrc[nx] : 0u;
-            }
+            const unsigned wv = (p0 + lane < len) ? ring[d] : 0u;
+            ring[d] = weight_at(p0 + (int64_t)kWideDepth * P + lane);     // refill this slot: kWideDepth periods ahead
             unsigned won = 0;
             if (!exact && __ballot(wv > W_LIMIT) != 0ull) {
                 exact = true;
@@ -202,14 +205,18 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
                 const unsigned rank = closed_period<GW>(key, has_rail, w0, per_rank, extra);
                 won = rail_of_rank<GW>(rank, q, want);
             } else if (!exact) {
-#pragma unroll 8
-                for (int t = 0; t < P; ++t) {
-                    const unsigned wS = (unsigned)__builtin_amdgcn_readlane((int)wv, t) << S;
-                    unsigned bumped = key + wS;
-                    asm volatile("" : "+v"(bumped));   // keep the sum off the chain: stops the rewrite into key + select(w, 0)
-                    const unsigned m = group_min_u32<GW>(key);
-                    won = (lane == t) ? m : won;
-                    key = (key == m) ? bumped : key;
+                const int left = (len - p0 < P) ? (int)(len - p0) : P;   // the last period stops where the chunks do
+                for (int t0 = 0; t0 < left; t0 += 8) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int t = t0 + u;
+                        const unsigned wS = (unsigned)__builtin_amdgcn_readlane((int)wv, t) << S;
+                        unsigned bumped = key + wS;
+                        asm volatile("" : "+v"(bumped));   // keep the sum off the chain: stops the rewrite into key + select(w, 0)
+                        const unsigned m = group_min_u32<GW>(key);
+                        won = (lane == t) ? m : won;
+                        key = (key == m) ? bumped : key;
+                    }
                 }
                 won &= (unsigned)(GW - 1);
             } else {

@@ -266,21 +266,36 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
 #pragma unroll
     for (int r = 0; r < REGS; ++r) want[r] = (unsigned)(r * GW + q) % (unsigned)N;
 
-    // weights of period p: lane q of a group holds chunks p*STEP + r*GW + q; past the end weight 0 (changes nothing)
-    auto fetch = [&](int64_t i0, unsigned (&wv)[REGS]) {
+    // Weights of period p: lane q of a group holds chunks p*STEP + r*GW + q; past the end weight 0 (changes nothing).
+    // The weights of period p + 2 are requested before the chain of period p and taken in behind it, before the
+    // rails are stored.  Lanes past the end of their instance load a word that always exists instead of skipping
+    // the load: a branch around the loads made the compiler wait for everything in flight - the request just
+    // issued and the stores of the period before - in front of every chain.
+    const uint32_t *const spare = reinterpret_cast<const uint32_t *>(chunk_off);
+    auto request = [&](int64_t i0, unsigned (&wv)[REGS]) {
 #pragma unroll
         for (int r = 0; r < REGS; ++r) {
             const int64_t i = i0 + r * GW + q;
-            wv[r] = (i < len) ? chunk_w[beg + i] : 0u;
+            const uint32_t *src = (i < len) ? chunk_w + beg + i : spare;
+            wv[r] = *src;
+        }
+    };
+    auto take_in = [&](int64_t i0, unsigned (&wv)[REGS]) {
+#pragma unroll
+        for (int r = 0; r < REGS; ++r) {
+            asm volatile("" : "+v"(wv[r]) : : "memory");    // nothing below (the stores least of all) moves above the wait
+            wv[r] = (i0 + r * GW + q < len) ? wv[r] : 0u;
         }
     };
     unsigned wv_cur[REGS], wv_nxt[REGS];
-    fetch(0, wv_cur);
-    fetch(STEP, wv_nxt);
+    request(0, wv_cur);
+    request(STEP, wv_nxt);
+    take_in(0, wv_cur);
+    take_in(STEP, wv_nxt);
 
     for (int64_t i0 = 0; i0 < max_len; i0 += STEP) {
         unsigned wv_far[REGS], won[REGS];
-        fetch(i0 + 2 * STEP, wv_far);               // two periods ahead: HBM/L2 latency
+        request(i0 + 2 * STEP, wv_far);
 #pragma unroll
         for (int r = 0; r < REGS; ++r) won[r] = 0;
         if (!exact) {
@@ -324,6 +339,7 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
             const unsigned adv = group_min_u32<GW>(key) >> S;
             if (has_rail) { key -= adv << S; base += adv; }
         }
+        take_in(i0 + 2 * STEP, wv_far);
 #pragma unroll
         for (int r = 0; r < REGS; ++r) {
             const int64_t i = i0 + r * GW + q;
@@ -359,7 +375,8 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t 
             beg += skip; len -= skip;
         }
     }
-    lpt_wide_body<GW, RUNS>(chunk_w + beg, rail + beg, len, base, N, S_out + (int64_t)inst * N);
+    lpt_wide_body<GW, RUNS>(chunk_w + beg, rail + beg, len, base, N, S_out + (int64_t)inst * N,
+                            reinterpret_cast<const uint32_t *>(chunk_off));
 }
 
 

@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
         lds_sync<false>();
         const int64_t n_late = (int64_t)late_full + nt;
         lpt_wide_body<GW, true>(late_w, late_rail, n_late, (unsigned long long)cw * (unsigned long long)(skip / (uint32_t)N), N,
-                                x.S + (int64_t)inst * N);
+                                x.S + (int64_t)inst * N, late_w);
         lds_sync<false>();
         // rails of the late chunks to memory, and their bytes to the receive bins
         for (int i = lane; i < (int)n_late; i += 64) {
