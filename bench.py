@@ -152,7 +152,7 @@ def main():
     assert int(plan.chunk_off[-1].item()) == total_chunks
 
     piped_ms = chunkwise_ms = None
-    schemes = combine = None
+    schemes = combine = sweep = None
     stats = plan.stats.cpu().numpy()
     ratio = stats[:, 0] / np.maximum(stats[:, 3], 1)
     if not args.skip_extras:
@@ -214,6 +214,21 @@ def main():
         st_c = plan_c.stats.cpu().numpy()
         r_c = st_c[:, 0] / np.maximum(st_c[:, 3], 1)
         combine = {"transpose_ms": tr_ms, "schedule_ms": comb_ms, "chunks": n_comb, "makespan_over_lb_max": float(r_c.max())}
+        # ---- chunk granularity (Theorem 4): the same traffic matrices cut at other chunk sizes
+        sweep = []
+        for cb in (16384, 65536, 262144, 1048576, 4194304):
+            topo_g = rs.Topo(cfg.M, cfg.N, cb, cfg.rail_bw_Bps)
+            n_g = int(rs.chunk_count(plan.D1, topo_g)[-1].item())
+            plan_g = rs.Plan(topo_g, B, n_g, dev, want_perm=True)
+            ms_g = timed(lambda: plan_g.schedule_one_call(plan.D1))
+            st_g, S_g = plan_g.stats.cpu().numpy(), plan_g.S.cpu().numpy().astype(np.float64)
+            mse = ((S_g - S_g.mean(axis=2, keepdims=True)) ** 2).mean(axis=2).max(axis=1)      # worst node of each matrix
+            wmax = np.maximum(st_g[:, 5], 1).astype(np.float64)
+            sweep.append({"chunk_bytes": cb, "chunks": n_g, "schedule_ms": ms_g,
+                          "makespan_over_lb_max": float((st_g[:, 0] / np.maximum(st_g[:, 3], 1)).max()),
+                          "send_spread_over_wmax_max": float((st_g[:, 7] / wmax).max()),
+                          "mse_over_wmax2_max": float((mse / (wmax * wmax)).max())})
+            del plan_g
         rs.chunk_sort(plan.D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
 
     # ---- roofline of the dominant kernel (route_traffic streams the logits once and writes the indices once)
@@ -258,6 +273,7 @@ def main():
         "lpt_spray_chunkwise_ms": chunkwise_ms,
         "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
         "schemes": schemes,
+        "granularity_sweep": sweep,
         "second_all_to_all": combine,
         "completion_time_us_max": float(stats[:, 0].max() / cfg.rail_bw_Bps * 1e6),
         "roofline": {"kernel": "route_traffic_kernel (with rt_reduce_kernel, the sum of its slice counts, in the same call)",
