@@ -152,7 +152,7 @@ def main():
     assert int(plan.chunk_off[-1].item()) == total_chunks
 
     piped_ms = chunkwise_ms = None
-    schemes = combine = sweep = None
+    schemes = combine = sweep = placement = None
     stats = plan.stats.cpu().numpy()
     ratio = stats[:, 0] / np.maximum(stats[:, 3], 1)
     if not args.skip_extras:
@@ -229,6 +229,19 @@ def main():
                           "send_spread_over_wmax_max": float((st_g[:, 7] / wmax).max()),
                           "mse_over_wmax2_max": float((mse / (wmax * wmax)).max())})
             del plan_g
+        # ---- expert placement (Section 6.3, sparse against dense): the first R replica groups of the placement table only
+        placement = []
+        for R_ in sorted({1, 2, max(cfg.replicas // 2, 1), cfg.replicas}):
+            eg_R = torch.from_numpy(np.ascontiguousarray(eg_np[:, :R_])).to(dev)
+            _, D1_R = rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, eg_R, cfg.payload_bytes, topo, out=(plan.topk_idx, D1T), ws=ws_rt)
+            n_R = int(rs.chunk_count(D1_R, topo)[-1].item())
+            plan_R = rs.Plan(topo, B, n_R, dev, want_perm=True)
+            ms_R = timed(lambda: plan_R.schedule_one_call(D1_R))
+            st_R = plan_R.stats.cpu().numpy()
+            placement.append({"replicas": R_, "gpus_with_experts": R_ * (cfg.E // cfg.experts_per_gpu), "chunks": n_R, "schedule_ms": ms_R,
+                              "makespan_over_lb_max": float((st_R[:, 0] / np.maximum(st_R[:, 3], 1)).max()),
+                              "completion_time_us_max": float(st_R[:, 0].max() / cfg.rail_bw_Bps * 1e6)})
+            del plan_R
         rs.chunk_sort(plan.D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
 
     # ---- roofline of the dominant kernel (route_traffic streams the logits once and writes the indices once)
@@ -274,6 +287,7 @@ def main():
         "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
         "schemes": schemes,
         "granularity_sweep": sweep,
+        "placement_sweep": placement,
         "second_all_to_all": combine,
         "completion_time_us_max": float(stats[:, 0].max() / cfg.rail_bw_Bps * 1e6),
         "roofline": {"kernel": "route_traffic_kernel (with rt_reduce_kernel, the sum of its slice counts, in the same call)",
