@@ -381,6 +381,29 @@ def bench_flows(cfg, args, rs, W, torch, np):
     step_ms = one_ms
     st = plan.stats.cpu().numpy()
     ratio = st[:, 0] / np.maximum(st[:, 3], 1)
+    per_chunk = None
+    if not args.skip_extras:
+        # the per-chunk kernel (every chunk through the cross-lane argmin) on the same records, against the VALU issue rate
+        rail2, S2 = torch.empty_like(plan.rail), torch.empty_like(plan.S)
+        t = []
+        for _ in range(3):
+            e0, e1 = _events(torch), None
+            rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(rail2, S2), chunkwise=True)
+            e1 = _events(torch)
+            torch.cuda.synchronize()
+            t.append(e0.elapsed_time(e1))
+        assert torch.equal(rail2, plan.rail) and torch.equal(S2, plan.S)
+        del rail2, S2
+        gw = 4 if cfg.N <= 4 else 8 if cfg.N <= 8 else 16 if cfg.N <= 16 else 32 if cfg.N <= 32 else 64
+        ipw = 64 // gw if B * cfg.M >= 2048 * 64 // gw else 1                      # instances per wavefront (packed or wide shape)
+        instr = (gw.bit_length() - 1) + 4                                         # cross-lane mins + add, compare, two selects
+        valu_peak = 256 * 4 * 2.4e9 / 4
+        per_chunk = {"ms": min(t[1:]), "chunks_per_s": total / (min(t[1:]) * 1e-3), "instances_per_wavefront": ipw,
+                     "roofline": {"bound": "alu", "unit": "G wave-instr/s", "peak": valu_peak / 1e9,
+                                  "achieved": total / ipw * instr / (min(t[1:]) * 1e-3) / 1e9,
+                                  "frac": total / ipw * instr / (min(t[1:]) * 1e-3) / valu_peak,
+                                  "note": f"{instr} VALU instructions per greedy step and wavefront, {ipw} instance(s) per wavefront; "
+                                          "256 CUs x 4 SIMDs x 2.4 GHz / 4 clocks per wave64 instruction"}}
     roof = _stage_rooflines(total, B * cfg.M, topo, ms, want_perm)
     one_bytes = 8 * topo.rails * topo.G * B * cfg.M + (13 if want_perm else 9) * total
     slow = max(ms, key=ms.get)
@@ -395,6 +418,7 @@ def bench_flows(cfg, args, rs, W, torch, np):
         "stage_ms": {"schedule": one_ms},
         "staged": {"ms_per_step": sum(ms.values()), "stage_ms": ms, "stage_rooflines": roof},
         "lpt_spray_chunks_per_s": total / (ms["lpt_spray"] * 1e-3),
+        "lpt_spray_per_chunk_kernel": per_chunk,
         "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
         "roofline": {"kernel": "railsched_schedule (cs_fill_kernel dominates: records and leading-run rails written once)",
                      "bound": "hbm", "achieved": one_bytes / (one_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

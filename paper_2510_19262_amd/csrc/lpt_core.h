@@ -10,6 +10,18 @@ namespace rs {
 constexpr int kBatch = 32;          // packed shape: chunks per period and instance (64 when a group is a whole wave)
 constexpr int kLptWaves = 4;        // wavefronts per workgroup
 
+// Issue priority of a wavefront by the length of its chain against the mean over all instances (len and mean are
+// wave-uniform).  All wavefronts of a launch are resident together and the launch lasts as long as its longest
+// chain; with equal priorities that chain shares its SIMD's issue slots evenly with shorter ones, which then finish
+// early and leave the SIMD to it - with a higher priority it runs at its own pace from the start.
+__device__ __forceinline__ void prioritise_long_chain(int64_t len, int64_t mean)
+{
+    const int64_t l = __builtin_amdgcn_readfirstlane((int)(len >> 8)), m = __builtin_amdgcn_readfirstlane((int)(mean >> 8));
+    if (l > 2 * m) __builtin_amdgcn_s_setprio(3);
+    else if (2 * l > 3 * m) __builtin_amdgcn_s_setprio(2);
+    else if (4 * l > 5 * m) __builtin_amdgcn_s_setprio(1);
+}
+
 template <int GW> struct GroupBits;
 template <> struct GroupBits<4> { static constexpr int S = 2; };
 template <> struct GroupBits<8> { static constexpr int S = 3; };
@@ -147,6 +159,15 @@ __device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsi
 // `spare` points at one readable word in the same kind of memory as wsrc (see the ring of weights below).
 constexpr int kWideDepth = 4;       // periods of 64 chunks in flight per wavefront
 
+// The decisions of a period, one per step, collect in a shift register across the 64 lanes: every lane takes its
+// upper neighbour's value and lane 63 takes the new one (a DPP wavefront shift with the new value as the "old"
+// operand that lanes without a source keep), so after 64 steps lane t holds the decision of step t.  One
+// instruction per step, beside the chain, where a compare of the lane index with t and a select took two.
+__device__ __forceinline__ unsigned shift_in(unsigned reg, unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)reg, 0x130, 0xF, 0xF, false);   // wave_shl:1
+}
+
 template <int GW> struct WideLimit {
     // packing limit: inside a period no delta exceeds (64 + 2) maximal weights, and the largest
     // packed key must stay below the all-ones key of lanes that hold no rail
@@ -180,12 +201,30 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
 #pragma unroll
     for (int d = 0; d < kWideDepth; ++d) ring[d] = weight_at((int64_t)d * P + lane);
 
+    // The rails of kWideDepth periods are stored together, right behind the point where the loop waits for the
+    // weights of the next period anyway: stored at the end of each period they were the newest thing in flight at
+    // that wait, which then lasted a store's round trip to memory.
+    unsigned held[kWideDepth];
+    auto store_rails = [&](int64_t i0) {
+#pragma unroll
+        for (int d = 0; d < kWideDepth; ++d) {
+            const int64_t i = i0 + (int64_t)d * P + lane;
+            if (i < len) rdst[i] = (uint8_t)held[d];
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < kWideDepth; ++d) held[d] = 0;
+
     for (int64_t i0 = 0; i0 < len; i0 += (int64_t)kWideDepth * P) {
 #pragma unroll
         for (int d = 0; d < kWideDepth; ++d) {
             const int64_t p0 = i0 + (int64_t)d * P;
             if (p0 >= len) break;                   // wave-uniform
-            const unsigned wv = (p0 + lane < len) ? ring[d] : 0u;
+            unsigned wv = (p0 + lane < len) ? ring[d] : 0u;
+            if (d == 0) {
+                asm volatile("" : "+v"(wv) : : "memory");                 // the stores stay behind the wait for wv
+                if (i0 > 0) store_rails(i0 - (int64_t)kWideDepth * P);
+            }
             ring[d] = weight_at(p0 + (int64_t)kWideDepth * P + lane);     // refill this slot: kWideDepth periods ahead
             unsigned won = 0;
             if (!exact && __ballot(wv > W_LIMIT) != 0ull) {
@@ -205,19 +244,20 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
                 const unsigned rank = closed_period<GW>(key, has_rail, w0, per_rank, extra);
                 won = rail_of_rank<GW>(rank, q, want);
             } else if (!exact) {
-                const int left = (len - p0 < P) ? (int)(len - p0) : P;   // the last period stops where the chunks do
-                for (int t0 = 0; t0 < left; t0 += 8) {
+                const int left = __builtin_amdgcn_readfirstlane((len - p0 < P) ? (int)(len - p0) : P);   // the last period stops where the chunks do
+                int t0 = 0;
+                for (; t0 < left; t0 += 8) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
-                        const int t = t0 + u;
-                        const unsigned wS = (unsigned)__builtin_amdgcn_readlane((int)wv, t) << S;
+                        const unsigned wS = (unsigned)__builtin_amdgcn_readlane((int)wv, t0 + u) << S;
                         unsigned bumped = key + wS;
                         asm volatile("" : "+v"(bumped));   // keep the sum off the chain: stops the rewrite into key + select(w, 0)
                         const unsigned m = group_min_u32<GW>(key);
-                        won = (lane == t) ? m : won;
+                        won = shift_in(won, m);
                         key = (key == m) ? bumped : key;
                     }
                 }
+                if (t0 < P) won = (unsigned)__shfl((int)won, lane + (P - t0));   // a short period leaves step t in lane t + P - t0
                 won &= (unsigned)(GW - 1);
             } else {
 #pragma unroll 2
@@ -225,16 +265,17 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
                     const unsigned w = (unsigned)__builtin_amdgcn_readlane((int)wv, t);
                     const unsigned js = group_argmin_u64<GW>(load, q);
                     load += (q == js) ? (unsigned long long)w : 0ull;
-                    won = (lane == t) ? js : won;
+                    won = shift_in(won, js);
                 }
             }
             if (!exact) {
                 const unsigned adv = group_min_u32<GW>(key) >> S;
                 if (has_rail) { key -= adv << S; base += adv; }
             }
-            if (p0 + lane < len) rdst[p0 + lane] = (uint8_t)won;
+            held[d] = won;
         }
     }
+    if (len > 0) store_rails((len - 1) / ((int64_t)kWideDepth * P) * ((int64_t)kWideDepth * P));
     if (lane < N) S_row[lane] = (int64_t)(exact ? load : base + (unsigned long long)(key >> S));
 }
 

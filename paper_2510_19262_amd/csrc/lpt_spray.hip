@@ -257,6 +257,8 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) { const int64_t o = __shfl_xor(max_len, d); max_len = o > max_len ? o : max_len; }
 
+    if (!RUNS) prioritise_long_chain(max_len, chunk_off[n_inst] / n_inst);
+
     unsigned key = has_rail ? q : 0xFFFFFFFFu;
     unsigned long long load = has_rail ? 0ull : ~0ull;
     bool exact = false;                             // wave-uniform
@@ -375,6 +377,7 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t 
             beg += skip; len -= skip;
         }
     }
+    if (!RUNS) prioritise_long_chain(len, chunk_off[n_inst] / n_inst);
     lpt_wide_body<GW, RUNS>(chunk_w + beg, rail + beg, len, base, N, S_out + (int64_t)inst * N,
                             reinterpret_cast<const uint32_t *>(chunk_off));
 }
