@@ -157,7 +157,7 @@ __device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsi
 // lpt_wide_body schedules the `len` chunks whose weights start at wsrc (rails to rdst) from rails that
 // all hold `base` bytes, and leaves the final loads in S_row[0..N).  Called by a whole wavefront.
 // `spare` points at one readable word in the same kind of memory as wsrc (see the ring of weights below).
-constexpr int kWideDepth = 4;       // periods of 64 chunks in flight per wavefront
+constexpr int kWideDepth = 2;       // periods of 64 chunks in flight per wavefront
 
 // The decisions of a period, one per step, collect in a shift register across the 64 lanes: every lane takes its
 // upper neighbour's value and lane 63 takes the new one (a DPP wavefront shift with the new value as the "old"
@@ -193,18 +193,14 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
     const unsigned per_rank = (unsigned)(P / N), extra = (unsigned)(P % N);
     const unsigned want = (unsigned)lane % (unsigned)N;
 
-    // Lanes past the end load *spare (any word that exists, in the memory wsrc points into) instead of skipping the
-    // load, and the value is masked where it is used: with no branch around the loads the compiler can count them,
-    // so the wait before a period's chain covers that period's weights only and kWideDepth - 1 loads stay in flight.
+    // Weights move in requests of kWideDepth periods: the request for the next periods is issued before the chains of
+    // the current ones and taken in behind them, so its loads have kWideDepth chains (about 3 us) to arrive.  Lanes
+    // past the end load *spare (any word that exists, in the memory wsrc points into) instead of skipping the load,
+    // and the value is masked where it is used: a branch around the loads made the compiler wait for everything in
+    // flight in front of every chain.  The rails of the periods just done are stored right behind the point where
+    // the request is taken in, so they are never the newest thing in flight at a wait.
     auto weight_at = [&](int64_t i) { const uint32_t *src = (i < len) ? wsrc + i : spare; return *src; };
-    unsigned ring[kWideDepth];
-#pragma unroll
-    for (int d = 0; d < kWideDepth; ++d) ring[d] = weight_at((int64_t)d * P + lane);
-
-    // The rails of kWideDepth periods are stored together, right behind the point where the loop waits for the
-    // weights of the next period anyway: stored at the end of each period they were the newest thing in flight at
-    // that wait, which then lasted a store's round trip to memory.
-    unsigned held[kWideDepth];
+    unsigned cur[kWideDepth], nxt[kWideDepth], held[kWideDepth];
     auto store_rails = [&](int64_t i0) {
 #pragma unroll
         for (int d = 0; d < kWideDepth; ++d) {
@@ -213,19 +209,22 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
         }
     };
 #pragma unroll
-    for (int d = 0; d < kWideDepth; ++d) held[d] = 0;
+    for (int d = 0; d < kWideDepth; ++d) { nxt[d] = weight_at((int64_t)d * P + lane); held[d] = 0; }
 
     for (int64_t i0 = 0; i0 < len; i0 += (int64_t)kWideDepth * P) {
 #pragma unroll
         for (int d = 0; d < kWideDepth; ++d) {
+            asm volatile("" : "+v"(nxt[d]) : : "memory");                 // loads and stores below stay behind this wait
+            cur[d] = nxt[d];
+        }
+#pragma unroll
+        for (int d = 0; d < kWideDepth; ++d) nxt[d] = weight_at(i0 + (int64_t)(kWideDepth + d) * P + lane);
+        if (i0 > 0) store_rails(i0 - (int64_t)kWideDepth * P);
+#pragma unroll
+        for (int d = 0; d < kWideDepth; ++d) {
             const int64_t p0 = i0 + (int64_t)d * P;
             if (p0 >= len) break;                   // wave-uniform
-            unsigned wv = (p0 + lane < len) ? ring[d] : 0u;
-            if (d == 0) {
-                asm volatile("" : "+v"(wv) : : "memory");                 // the stores stay behind the wait for wv
-                if (i0 > 0) store_rails(i0 - (int64_t)kWideDepth * P);
-            }
-            ring[d] = weight_at(p0 + (int64_t)kWideDepth * P + lane);     // refill this slot: kWideDepth periods ahead
+            const unsigned wv = (p0 + lane < len) ? cur[d] : 0u;
             unsigned won = 0;
             if (!exact && __ballot(wv > W_LIMIT) != 0ull) {
                 exact = true;
@@ -245,8 +244,11 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
                 won = rail_of_rank<GW>(rank, q, want);
             } else if (!exact) {
                 const int left = __builtin_amdgcn_readfirstlane((len - p0 < P) ? (int)(len - p0) : P);   // the last period stops where the chunks do
-                int t0 = 0;
-                for (; t0 < left; t0 += 8) {
+                // unrolled over the whole period, so that every weight is read out of a fixed lane (a lane index in
+                // a register costs the chain a quarter more per step); left in blocks of 8 steps when the chunks end
+#pragma unroll
+                for (int t0 = 0; t0 < P; t0 += 8) {
+                    if (t0 >= left) break;          // wave-uniform
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
                         const unsigned wS = (unsigned)__builtin_amdgcn_readlane((int)wv, t0 + u) << S;
@@ -257,7 +259,8 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
                         key = (key == m) ? bumped : key;
                     }
                 }
-                if (t0 < P) won = (unsigned)__shfl((int)won, lane + (P - t0));   // a short period leaves step t in lane t + P - t0
+                const int ran = (left + 7) & ~7;
+                if (ran < P) won = (unsigned)__shfl((int)won, lane + (P - ran));   // a short period leaves step t in lane t + P - ran
                 won &= (unsigned)(GW - 1);
             } else {
 #pragma unroll 2
