@@ -252,10 +252,12 @@ def main():
     k1_gbps = k1_bytes / (staged_ms["route_topk"] * 1e-3) / 1e9
     staged_routing_gbps = (k1_bytes + k2_bytes) / ((staged_ms["route_topk"] + staged_ms["traffic_matrix"]) * 1e-3) / 1e9
     dominant = max(stage_ms, key=stage_ms.get)
-    # LPT against the VALU issue rate: ceil(log2 N) cross-lane mins + compare + select + add per chunk and lane group,
-    # 64/GW lane groups per wavefront instruction; 256 CUs x 4 SIMDs issue one wave64 VALU instruction per 4 cycles at 2.4 GHz
+    # the per-chunk LPT kernel against the VALU issue rate: ceil(log2 N) cross-lane mins + add, compare, select and the
+    # shift that files the decision, per greedy step and wavefront (one instance per wavefront at this instance count);
+    # 256 CUs x 4 SIMDs issue one wave64 VALU instruction per 4 cycles at 2.4 GHz
     gw = 4 if cfg.N <= 4 else 8 if cfg.N <= 8 else 16 if cfg.N <= 16 else 32 if cfg.N <= 32 else 64
-    instr_per_chunk = (gw.bit_length() - 1 + 3) / (64 // gw)
+    ipw = 64 // gw if B * cfg.M >= 2048 * 64 // gw else 1
+    instr_per_step = gw.bit_length() - 1 + 5
     valu_peak = 256 * 4 * 2.4e9 / 4 / 1e9            # G wave-instructions/s
     lpt_rate = total_chunks / (staged_ms["lpt_spray"] * 1e-3)
 
@@ -280,9 +282,12 @@ def main():
         "routing_to_traffic_matrix_GBps": rt_gbps,
         "routing_frac_of_hbm_peak": rt_gbps / HBM_PEAK_GBPS,
         "lpt_spray_chunks_per_s": lpt_rate,
-        "lpt_roofline": {"bound": "alu", "achieved": lpt_rate * instr_per_chunk / 1e9, "peak": valu_peak,
-                         "unit": "G wave-instr/s", "frac": lpt_rate * instr_per_chunk / 1e9 / valu_peak,
-                         "note": f"{B * cfg.M} instances cannot fill 1024 SIMDs: the serial chain's latency, not issue rate, bounds this workload"},
+        "lpt_roofline": None if chunkwise_ms is None else {
+            "kernel": "railsched_lpt_spray_chunkwise", "bound": "alu", "unit": "G wave-instr/s", "peak": valu_peak,
+            "achieved": total_chunks / ipw * instr_per_step / (chunkwise_ms * 1e-3) / 1e9,
+            "frac": total_chunks / ipw * instr_per_step / (chunkwise_ms * 1e-3) / 1e9 / valu_peak,
+            "note": f"{B * cfg.M} instances are {B * cfg.M // ipw} wavefronts on 1024 SIMDs: the latency of the serial chain "
+                    f"({instr_per_step} instructions per step), not the issue rate, bounds this workload"},
         "lpt_spray_chunkwise_ms": chunkwise_ms,
         "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
         "schemes": schemes,
@@ -396,7 +401,7 @@ def bench_flows(cfg, args, rs, W, torch, np):
         del rail2, S2
         gw = 4 if cfg.N <= 4 else 8 if cfg.N <= 8 else 16 if cfg.N <= 16 else 32 if cfg.N <= 32 else 64
         ipw = 64 // gw if B * cfg.M >= 2048 * 64 // gw else 1                      # instances per wavefront (packed or wide shape)
-        instr = (gw.bit_length() - 1) + 4                                         # cross-lane mins + add, compare, two selects
+        instr = (gw.bit_length() - 1) + (4 if ipw > 1 else 5)                     # cross-lane mins + add, compare, select, decision filed (+ weight broadcast)
         valu_peak = 256 * 4 * 2.4e9 / 4
         per_chunk = {"ms": min(t[1:]), "chunks_per_s": total / (min(t[1:]) * 1e-3), "instances_per_wavefront": ipw,
                      "roofline": {"bound": "alu", "unit": "G wave-instr/s", "peak": valu_peak / 1e9,
