@@ -7,7 +7,7 @@
 
 namespace rs {
 
-constexpr int kBatch = 32;          // packed shape: chunks per period and instance (64 when a group is a whole wave)
+constexpr int kBatch = 64;          // packed shape: chunks per period and instance
 constexpr int kLptWaves = 4;        // wavefronts per workgroup
 
 // Issue priority of a wavefront by the length of its chain against the mean over all instances (len and mean are

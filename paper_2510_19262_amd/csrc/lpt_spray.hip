@@ -179,41 +179,58 @@ __device__ __forceinline__ unsigned group_bcast(unsigned v)
     else return (unsigned)__builtin_amdgcn_ds_swizzle((int)v, ((0x1F & ~(GW - 1)) | (T << 5)));   // lane = (lane & ~(GW-1)) | T
 }
 
-// Broadcast every weight of a period to its whole group, already shifted into key position, before the
-// chain starts, so that the exchange latency is paid once per period and not once per chunk.
-template <int GW, int STEP, int T>
-__device__ __forceinline__ void bcast_steps(const unsigned (&wv)[STEP / GW], unsigned (&bc)[STEP])
+// Broadcast CNT weights of a period (chunks BASE .. BASE + CNT) to their whole group, already shifted into key
+// position, before their chain starts, so that the exchange latency is paid once and not once per chunk.
+template <int GW, int STEP, int BASE, int CNT, int T>
+__device__ __forceinline__ void bcast_steps(const unsigned (&wv)[STEP / GW], unsigned (&bc)[CNT])
 {
-    if constexpr (T < STEP) {
-        bc[T] = group_bcast<GW, T % GW>(wv[T / GW]) << GroupBits<GW>::S;
-        bcast_steps<GW, STEP, T + 1>(wv, bc);
+    if constexpr (T < CNT) {
+        bc[T] = group_bcast<GW, (BASE + T) % GW>(wv[(BASE + T) / GW]) << GroupBits<GW>::S;
+        bcast_steps<GW, STEP, BASE, CNT, T + 1>(wv, bc);
     }
 }
 
-template <int GW, int STEP, int T>
-__device__ __forceinline__ void fast_steps(unsigned &key, const unsigned (&bc)[STEP], unsigned (&won)[STEP / GW], unsigned q)
+template <int GW, int STEP, int BASE, int CNT, int T>
+__device__ __forceinline__ void fast_steps(unsigned &key, const unsigned (&bc)[CNT], unsigned (&won)[STEP / GW], unsigned q)
 {
-    // chunk T of the period; the serial chain is: group min (log2 GW exchanges), compare, select
-    if constexpr (T < STEP) {
+    // chunk BASE + T of the period; the serial chain is: group min (log2 GW exchanges), compare, select
+    if constexpr (T < CNT) {
         unsigned bumped = key + bc[T];              // off the chain: does not need the minimum
         asm volatile("" : "+v"(bumped));           // (stops the rewrite into key + select(w, 0), which puts the add on the chain)
         const unsigned m = group_min_u32<GW>(key);
-        won[T / GW] = (q == (unsigned)(T % GW)) ? m : won[T / GW];
+        won[(BASE + T) / GW] = (q == (unsigned)((BASE + T) % GW)) ? m : won[(BASE + T) / GW];
         key = (key == m) ? bumped : key;
-        fast_steps<GW, STEP, T + 1>(key, bc, won, q);
+        fast_steps<GW, STEP, BASE, CNT, T + 1>(key, bc, won, q);
     }
 }
 
-template <int GW, int STEP, int T>
+// the period in blocks of CNT chunks: CNT broadcast weights are held at a time
+template <int GW, int STEP, int CNT, int BASE>
+__device__ __forceinline__ void fast_period(unsigned &key, const unsigned (&wv)[STEP / GW], unsigned (&won)[STEP / GW], unsigned q)
+{
+    if constexpr (BASE < STEP) {
+        unsigned bc[CNT];
+        bcast_steps<GW, STEP, BASE, CNT, 0>(wv, bc);
+        fast_steps<GW, STEP, BASE, CNT, 0>(key, bc, won, q);
+        fast_period<GW, STEP, CNT, BASE + CNT>(key, wv, won, q);
+    }
+}
+
+// Weights beyond the packing limit: exact 64-bit loads, (load, rail) reductions.  Rare, so kept small: the chunks
+// of one register are walked by a loop, the weight fetched from the lane that the loop counter names.
+template <int GW, int STEP>
 __device__ __forceinline__ void exact_steps(unsigned long long &load, const unsigned (&wv)[STEP / GW], unsigned (&won)[STEP / GW],
                                             unsigned q)
 {
-    if constexpr (T < STEP) {
-        const unsigned w = group_bcast<GW, T % GW>(wv[T / GW]);
-        const unsigned js = group_argmin_u64<GW>(load, q);
-        load += (q == js) ? (unsigned long long)w : 0ull;
-        won[T / GW] = (q == (unsigned)(T % GW)) ? js : won[T / GW];
-        exact_steps<GW, STEP, T + 1>(load, wv, won, q);
+#pragma unroll
+    for (int r = 0; r < STEP / GW; ++r) {
+#pragma unroll 1
+        for (int j = 0; j < GW; ++j) {
+            const unsigned w = (unsigned)__shfl((int)wv[r], j, GW);
+            const unsigned js = group_argmin_u64<GW>(load, q);
+            load += (q == js) ? (unsigned long long)w : 0ull;
+            won[r] = (q == (unsigned)j) ? js : won[r];
+        }
     }
 }
 
@@ -226,7 +243,7 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
     if (chunk_off[n_inst] > capacity) return;       // the record arrays were too small and hold nothing
     constexpr int S = GroupBits<GW>::S;
     constexpr int IPW = 64 / GW;                    // instances per wavefront
-    constexpr int STEP = kBatch > GW ? kBatch : GW; // chunks per instance and period
+    constexpr int STEP = GW <= 4 ? kBatch / 2 : kBatch;   // chunks per instance and period (GW = 4 holds 8 weights per lane and period already)
     constexpr int REGS = STEP / GW;
     // packing limit: inside a period no delta exceeds (STEP + 2) maximal weights, and the largest
     // packed key must stay below the all-ones key of lanes that hold no rail
@@ -328,13 +345,11 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
 #pragma unroll
             for (int r = 0; r < REGS; ++r) won[r] = rail_of_rank<GW>(rank, q, want[r]);
         } else if (!exact) {
-            unsigned bc[STEP];
-            bcast_steps<GW, STEP, 0>(wv_cur, bc);
-            fast_steps<GW, STEP, 0>(key, bc, won, q);
+            fast_period<GW, STEP, (STEP > 32 ? 32 : STEP), 0>(key, wv_cur, won, q);
 #pragma unroll
             for (int r = 0; r < REGS; ++r) won[r] &= (unsigned)(GW - 1);
         } else {
-            exact_steps<GW, STEP, 0>(load, wv_cur, won, q);
+            exact_steps<GW, STEP>(load, wv_cur, won, q);
         }
         if (!exact) {
             // advance the base to the current minimum so deltas stay below the packing limit
