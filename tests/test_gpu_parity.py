@@ -505,6 +505,14 @@ def test_lpt_packed_shape_many_instances(N):
             w = rng.integers(0, 1 << 20, size=n)
         insts.append(w)
     insts[7] = np.concatenate([[5_000_000_00], rng.integers(0, 1 << 30, size=40)])   # drags its wavefront onto the exact path
+    # weights at, one above and around the packing limit of this shape (periods of 64 chunks, 32 for groups of 4 lanes),
+    # in wavefronts of their own, with loads that pass 2^32
+    lim = ((0xFFFFFFFF >> (gw.bit_length() - 1)) // ((32 if gw == 4 else 64) + 2)) - 1
+    per_wave = 64 // gw
+    insts[20 * per_wave] = np.full(700, lim)
+    insts[30 * per_wave + 1] = np.full(700, lim + 1)
+    insts[40 * per_wave] = np.concatenate([np.full(300, lim), np.arange(300, 0, -1)])
+    insts[50 * per_wave] = np.concatenate([np.full(130, lim), [lim + 1], np.full(130, lim - 1)])   # leaves the packed form mid-way
     _lpt_case(insts, 1, N, batch=n_inst)                      # one node per matrix, n_inst matrices
 
 
