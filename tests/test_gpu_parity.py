@@ -483,7 +483,7 @@ def test_lpt_chunk_lists_from_stage3_shapes():
     _lpt_case(insts, 8, 8, batch=5)
 
 
-@pytest.mark.parametrize("N", [3, 4, 7, 8, 13, 16, 20, 32])
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 7, 8, 13, 16, 20, 32])
 def test_lpt_packed_shape_many_instances(N):
     # enough instances that several share a wavefront (one per lane group): ragged lengths, runs, mixed weights
     gw = 4 if N <= 4 else 8 if N <= 8 else 16 if N <= 16 else 32
