@@ -434,7 +434,8 @@ def test_lpt_large_weights_take_the_exact_path(N):
 def test_lpt_weights_at_the_packing_limit():
     # weights just below / at / above the switch-over, many chunks so the loads pass 2^32
     for N, lim in ((8, ((0xFFFFFFFF >> 3) // 34) - 1), (8, ((0xFFFFFFFF >> 3) // 66) - 1), (64, ((0xFFFFFFFF >> 6) // 66) - 1),
-                   (4, ((0xFFFFFFFF >> 2) // 66) - 1), (16, ((0xFFFFFFFF >> 4) // 66) - 1)):
+                   (4, ((0xFFFFFFFF >> 2) // 66) - 1), (16, ((0xFFFFFFFF >> 4) // 66) - 1),
+                   (1, ((0xFFFFFFFF >> 2) // 66) - 1), (2, ((0xFFFFFFFF >> 2) // 66) - 1), (5, ((0xFFFFFFFF >> 3) // 66) - 1)):
         insts = [np.full(400, lim, dtype=np.uint32), np.full(400, lim + 1, dtype=np.uint32),
                  np.concatenate([np.full(200, lim), np.arange(200, 0, -1)]).astype(np.uint32)]
         _lpt_case(insts, 3, N)
