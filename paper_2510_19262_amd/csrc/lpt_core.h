@@ -156,7 +156,7 @@ __device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsi
 //
 // lpt_wide_body schedules the `len` chunks whose weights start at wsrc (rails to rdst) from rails that
 // all hold `base` bytes, and leaves the final loads in S_row[0..N).  Called by a whole wavefront.
-// `spare` points at one readable word in the same kind of memory as wsrc (see the ring of weights below).
+// `spare` points at one readable word in the same kind of memory as wsrc (lanes past the end load it).
 constexpr int kWideDepth = 2;       // periods of 64 chunks in flight per wavefront
 
 // The decisions of a period, one per step, collect in a shift register across the 64 lanes: every lane takes its
@@ -245,7 +245,7 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
             } else if (!exact) {
                 const int left = __builtin_amdgcn_readfirstlane((len - p0 < P) ? (int)(len - p0) : P);   // the last period stops where the chunks do
                 // unrolled over the whole period, so that every weight is read out of a fixed lane (a lane index in
-                // a register costs the chain a quarter more per step); left in blocks of 8 steps when the chunks end
+                // a register costs the chain an eighth more per step); left in blocks of 8 steps when the chunks end
 #pragma unroll
                 for (int t0 = 0; t0 < P; t0 += 8) {
                     if (t0 >= left) break;          // wave-uniform
