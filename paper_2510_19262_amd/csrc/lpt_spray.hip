@@ -40,7 +40,8 @@ constexpr int kPfThreads = 256;
 constexpr int kPfTile = 16384;      // most chunk positions per workgroup iteration (16 x uint4 per thread)
 constexpr int kPfPass = kPfThreads * 4;   // positions one pass of the workgroup covers
 constexpr int kPfStage = 1024;      // instance boundaries staged in LDS per tile
-constexpr int kPfBlocks = 2048;
+constexpr int kPfBlocks = 16384;   // short-lived workgroups stream best (2048: 12 % slower on long lists); more cost short lists their empty launches
+constexpr int kPfRun = 4;           // consecutive tiles a workgroup takes at a time
 
 __global__ void lpt_prefix_init_kernel(int64_t *run_end, int n_inst, int N)
 {
@@ -63,108 +64,127 @@ __global__ __launch_bounds__(kPfThreads) void lpt_prefix_kernel(const int64_t *_
     // tile: the share of one workgroup when the whole grid takes one tile each, in whole passes, at most kPfTile
     int64_t tile = ((total + gridDim.x - 1) / gridDim.x + kPfPass - 1) / kPfPass * kPfPass;
     tile = tile < kPfPass ? kPfPass : tile > kPfTile ? kPfTile : tile;
-    for (int64_t t0 = (int64_t)blockIdx.x * tile; t0 < total; t0 += (int64_t)gridDim.x * tile) {
-        const int64_t t1 = t0 + tile < total ? t0 + tile : total;
-        const int inst_lo = wave_last_le<int64_t>(chunk_off, n_inst, t0);
-        const int inst_hi = wave_last_le<int64_t>(chunk_off, n_inst, t1 - 1);
-        const int cnt = inst_hi - inst_lo + 1;
-        const bool staged = cnt <= kPfStage;
-        __syncthreads();                                   // previous tile is done with the stage
-        if (staged) {
-            for (int i = threadIdx.x; i <= cnt; i += kPfThreads) s_off[i] = chunk_off[inst_lo + i];
-            for (int i = threadIdx.x; i < cnt; i += kPfThreads) {
-                const int64_t b = chunk_off[inst_lo + i];
-                s_w0[i] = b < total ? chunk_w[b] : 0u;      // an empty instance's value is never used
+    // A workgroup takes up to kPfRun consecutive tiles at a time: the instance a tile starts in is searched for once per run
+    // and carried from tile to tile (each search is two or three dependent trips to memory, a fifth of the time a
+    // workgroup spent on a tile when every tile searched for both of its ends).
+    int64_t run = total / ((int64_t)gridDim.x * tile);     // short lists keep one tile per workgroup: parallelism first
+    run = run < 1 ? 1 : run > kPfRun ? kPfRun : run;
+    const int64_t span = tile * run;
+    for (int64_t s0 = (int64_t)blockIdx.x * span; s0 < total; s0 += (int64_t)gridDim.x * span) {
+        const int64_t s1 = s0 + span < total ? s0 + span : total;
+        int inst_lo = wave_last_le<int64_t>(chunk_off, n_inst, s0);
+        for (int64_t t0 = s0; t0 < s1; t0 += tile) {
+            const int64_t t1 = t0 + tile < s1 ? t0 + tile : s1;
+            int64_t next_off = chunk_off[inst_lo + 1];
+            for (int hops = 0; next_off <= t0; ++hops) {       // on to the instance that holds t0 (empty ones are skipped)
+                if (hops == 8) { inst_lo = wave_last_le<int64_t>(chunk_off, n_inst, t0); next_off = chunk_off[inst_lo + 1]; break; }
+                ++inst_lo;
+                next_off = chunk_off[inst_lo + 1];
             }
-        }
-        __syncthreads();
-        if (cnt == 1 && wide_ok && ((t1 - t0) & 3) == 0) {
-            // The tile lies inside one instance (the common case when instances are long): four 16-byte loads
-            // in flight per thread, one comparison per weight, and one atomic per wavefront at most.
-            const int64_t b = s_off[0];
-            const uint32_t w0 = s_w0[0];
-            int64_t miss = INT64_MAX;
-            constexpr int U = 4;
-            // memory operations of a wavefront complete in order, so the loads of the next step are issued ahead of
-            // this step's stores instead of behind them
-            int64_t p = t0 + (int64_t)threadIdx.x * 4;
-            u32x4 v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t pu = p + (int64_t)u * kPfThreads * 4;
-                v[u] = pu < t1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(chunk_w + pu)) : u32x4{w0, w0, w0, w0};
-            }
-            while (p < t1) {
-                uint32_t packed[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t i = p + (int64_t)u * kPfThreads * 4 - b;
-                    uint32_t r0 = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
-                    packed[u] = r0;
-#pragma unroll
-                    for (int e = 1; e < 4; ++e) {
-                        r0 = (r0 + 1 == (uint32_t)N) ? 0u : r0 + 1;
-                        packed[u] |= r0 << (8 * e);
+            const bool one = next_off >= t1;                   // the tile lies inside instance inst_lo
+            const int inst_hi = one ? inst_lo : wave_last_le<int64_t>(chunk_off, n_inst, t1 - 1);
+            const int cnt = inst_hi - inst_lo + 1;
+            const bool fast = one && wide_ok && ((t1 - t0) & 3) == 0;
+            const bool staged = cnt <= kPfStage;
+            if (!fast) {
+                __syncthreads();                               // previous tile is done with the stage
+                if (staged) {
+                    for (int i = threadIdx.x; i <= cnt; i += kPfThreads) s_off[i] = chunk_off[inst_lo + i];
+                    for (int i = threadIdx.x; i < cnt; i += kPfThreads) {
+                        const int64_t b = chunk_off[inst_lo + i];
+                        s_w0[i] = b < total ? chunk_w[b] : 0u;  // an empty instance's value is never used
                     }
-                    const int first = v[u].x != w0 ? 0 : v[u].y != w0 ? 1 : v[u].z != w0 ? 2 : v[u].w != w0 ? 3 : -1;
-                    if (first >= 0 && i + first < miss) miss = i + first;          // padded lanes hold w0: never a miss
                 }
-                const int64_t pn = p + (int64_t)kPfThreads * 4 * U;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t pu = pn + (int64_t)u * kPfThreads * 4;
-                    v[u] = pu < t1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(chunk_w + pu)) : u32x4{w0, w0, w0, w0};
-                }
+                __syncthreads();
+            }
+            if (fast) {
+                // The tile lies inside one instance (the common case when instances are long): four 16-byte loads
+                // in flight per thread, one comparison per weight, and one atomic per wavefront at most.
+                const int64_t b = chunk_off[inst_lo];
+                const uint32_t w0 = chunk_w[b];
+                int64_t miss = INT64_MAX;
+                constexpr int U = 4;
+                // memory operations of a wavefront complete in order, so the loads of the next step are issued ahead of
+                // this step's stores instead of behind them
+                int64_t p = t0 + (int64_t)threadIdx.x * 4;
+                u32x4 v[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int64_t pu = p + (int64_t)u * kPfThreads * 4;
-                    if (pu < t1) __builtin_nontemporal_store(packed[u], reinterpret_cast<uint32_t *>(rail + pu));
+                    v[u] = pu < t1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(chunk_w + pu)) : u32x4{w0, w0, w0, w0};
                 }
-                p = pn;
-            }
+                while (p < t1) {
+                    uint32_t packed[U];
 #pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) { const int64_t o = __shfl_xor(miss, d); miss = o < miss ? o : miss; }
-            if ((threadIdx.x & 63) == 0 && miss != INT64_MAX) {
-                const int64_t slot = (int64_t)inst_lo * N;
-                if (run_end[slot] > miss) atomicMin((long long *)&run_end[slot], (long long)miss);
-            }
-            continue;
-        }
-        for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPfThreads * 4) {
-            uint32_t w[4];
-            const bool full = p + 4 <= total;
-            if (full && wide_ok) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(chunk_w + p);
-                w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-            } else {
+                    for (int u = 0; u < U; ++u) {
+                        const int64_t i = p + (int64_t)u * kPfThreads * 4 - b;
+                        uint32_t r0 = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
+                        packed[u] = r0;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = (p + e < total) ? chunk_w[p + e] : 0u;
-            }
-            int li = staged ? last_le<int64_t>(s_off, cnt, p) : last_le<int64_t>(chunk_off, n_inst, p) - inst_lo;
-            uint32_t packed = 0;
-            int64_t miss_inst = -1, miss_pos = 0;          // first mismatch seen by this thread, per instance
+                        for (int e = 1; e < 4; ++e) {
+                            r0 = (r0 + 1 == (uint32_t)N) ? 0u : r0 + 1;
+                            packed[u] |= r0 << (8 * e);
+                        }
+                        const int first = v[u].x != w0 ? 0 : v[u].y != w0 ? 1 : v[u].z != w0 ? 2 : v[u].w != w0 ? 3 : -1;
+                        if (first >= 0 && i + first < miss) miss = i + first;          // padded lanes hold w0: never a miss
+                    }
+                    const int64_t pn = p + (int64_t)kPfThreads * 4 * U;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (p + e >= total) break;
-                int64_t nxt = staged ? s_off[li + 1] : chunk_off[inst_lo + li + 1];
-                while (p + e >= nxt) { ++li; nxt = staged ? s_off[li + 1] : chunk_off[inst_lo + li + 1]; }
-                const int64_t b = staged ? s_off[li] : chunk_off[inst_lo + li];
-                const uint32_t w0 = staged ? s_w0[li] : chunk_w[b];
-                const int64_t i = p + e - b;
-                const uint32_t r = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
-                packed |= r << (8 * e);
-                if (w[e] != w0 && miss_inst != inst_lo + li) {
-                    if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
-                    miss_inst = inst_lo + li; miss_pos = i;
+                    for (int u = 0; u < U; ++u) {
+                        const int64_t pu = pn + (int64_t)u * kPfThreads * 4;
+                        v[u] = pu < t1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(chunk_w + pu)) : u32x4{w0, w0, w0, w0};
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int64_t pu = p + (int64_t)u * kPfThreads * 4;
+                        if (pu < t1) __builtin_nontemporal_store(packed[u], reinterpret_cast<uint32_t *>(rail + pu));
+                    }
+                    p = pn;
                 }
-            }
-            // most positions behind the run's end find a smaller value already there and skip the atomic
-            if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
-            if (full && wide_ok) {
-                *reinterpret_cast<uint32_t *>(rail + p) = packed;
-            } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) if (p + e < total) rail[p + e] = (uint8_t)(packed >> (8 * e));
+                for (int d = 32; d >= 1; d >>= 1) { const int64_t o = __shfl_xor(miss, d); miss = o < miss ? o : miss; }
+                if ((threadIdx.x & 63) == 0 && miss != INT64_MAX) {
+                    const int64_t slot = (int64_t)inst_lo * N;
+                    if (run_end[slot] > miss) atomicMin((long long *)&run_end[slot], (long long)miss);
+                }
+                continue;
+            }
+            for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPfThreads * 4) {
+                uint32_t w[4];
+                const bool full = p + 4 <= total;
+                if (full && wide_ok) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(chunk_w + p);
+                    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (p + e < total) ? chunk_w[p + e] : 0u;
+                }
+                int li = staged ? last_le<int64_t>(s_off, cnt, p) : last_le<int64_t>(chunk_off, n_inst, p) - inst_lo;
+                uint32_t packed = 0;
+                int64_t miss_inst = -1, miss_pos = 0;          // first mismatch seen by this thread, per instance
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (p + e >= total) break;
+                    int64_t nxt = staged ? s_off[li + 1] : chunk_off[inst_lo + li + 1];
+                    while (p + e >= nxt) { ++li; nxt = staged ? s_off[li + 1] : chunk_off[inst_lo + li + 1]; }
+                    const int64_t b = staged ? s_off[li] : chunk_off[inst_lo + li];
+                    const uint32_t w0 = staged ? s_w0[li] : chunk_w[b];
+                    const int64_t i = p + e - b;
+                    const uint32_t r = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
+                    packed |= r << (8 * e);
+                    if (w[e] != w0 && miss_inst != inst_lo + li) {
+                        if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
+                        miss_inst = inst_lo + li; miss_pos = i;
+                    }
+                }
+                // most positions behind the run's end find a smaller value already there and skip the atomic
+                if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
+                if (full && wide_ok) {
+                    *reinterpret_cast<uint32_t *>(rail + p) = packed;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) if (p + e < total) rail[p + e] = (uint8_t)(packed >> (8 * e));
+                }
             }
         }
     }
