@@ -209,14 +209,27 @@ __global__ __launch_bounds__(kFillThreads) void cs_fill_kernel(CsArgs a, int vec
                 const uint32_t pa = (p1 - p0 < head) ? p1 : p0 + head;
                 const uint32_t groups = (p1 - pa) / 4;
                 const uint32_t pb = pa + groups * 4;                              // scalar positions from here on
-                const uint32_t g0 = (uint32_t)((uint64_t)groups * wave / kWaves), g1 = (uint32_t)((uint64_t)groups * (wave + 1) / kWaves);
+                // The wavefronts' shares and their steps end on 1 KiB boundaries of the record arrays (64 groups), so all
+                // steps but the span's first and last store whole, aligned kilobytes: 10 % more write rate than
+                // kilobytes that start 16 bytes off.
+                const uint32_t G0 = (uint32_t)(((out0 + pa) >> 2) & 63);           // global group index of group 0, mod 64
+                auto share = [&](int w) {
+                    if (w <= 0) return 0u;
+                    if (w >= kWaves) return groups;
+                    const uint32_t cut = ((G0 + (uint32_t)((uint64_t)groups * w / kWaves)) & ~63u);
+                    return cut > G0 ? cut - G0 : 0u;
+                };
+                const uint32_t g0 = share(wave), g1 = share(wave + 1);
                 if (g0 < g1) {
                     int j_lo = last_le<uint32_t>(st_fs, nf, pa + 4 * g0);          // the same in every lane
-                    for (uint32_t gb = g0; gb < g1; gb += 64) {
-                        const bool active = gb + lane < g1;
-                        const uint32_t g = active ? gb + lane : g1 - 1;  // idle lanes shadow the last group
+                    uint32_t cnt = 0;
+                    for (uint32_t gb = g0; gb < g1; gb += cnt) {
+                        cnt = 64u - ((G0 + gb) & 63u);
+                        cnt = cnt < g1 - gb ? cnt : g1 - gb;
+                        const bool active = (uint32_t)lane < cnt;
+                        const uint32_t g = active ? gb + lane : gb + cnt - 1;      // idle lanes shadow the step's last group
                         const uint32_t p = pa + 4 * g;
-                        const uint32_t g_last = gb + 63 < g1 ? gb + 63 : g1 - 1;
+                        const uint32_t g_last = gb + cnt - 1;
                         const uint32_t p_last = pa + 4 * g_last + 3;
                         // boundaries j_lo+1 .. j_lo+64: those at or below the step's last position form a prefix
                         const int probe = j_lo + 1 + lane;
