@@ -37,8 +37,9 @@ __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
         if (f < a.M && r < (unsigned)a.N) atomicAdd(&ev_bins[f * a.N + r], (unsigned long long)w);   // LDS, workgroup-private
         wmax = w > wmax ? w : wmax;
     };
-    // whole groups of four records at multiples of four: 16-byte loads of weight and flow, 4 bytes of rails
-    const int64_t alo = a.wide_ok ? ((lo + 3) & ~int64_t(3)) : hi, ahi = a.wide_ok ? (hi & ~int64_t(3)) : hi;
+    // whole groups of four records: 16-byte loads of weight and flow, 4 bytes of rails; the first group sits on a
+    // 1 KiB boundary of the weight array (256 records), so every wavefront loads whole aligned kilobytes
+    const int64_t alo = a.wide_ok ? ((lo + 255) & ~int64_t(255)) : hi, ahi = a.wide_ok ? (hi & ~int64_t(3)) : hi;
     if (alo < ahi) {
         const int64_t round = (int64_t)a.slices * kEvThreads * 4;
         for (int64_t i = alo + ((int64_t)t * kEvThreads + threadIdx.x) * 4; i < ahi; i += round) {
@@ -47,11 +48,12 @@ __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
             const uint32_t rr = *reinterpret_cast<const uint32_t *>(a.rail + i);
             one(w.x, fl.x, rr & 255u); one(w.y, fl.y, (rr >> 8) & 255u); one(w.z, fl.z, (rr >> 16) & 255u); one(w.w, fl.w, rr >> 24);
         }
-        const int64_t n_edge = (alo - lo) + (hi - ahi);                 // at most 6 records outside the aligned span
-        if (t == 0 && (int64_t)threadIdx.x < n_edge) {
-            const int64_t i = (int64_t)threadIdx.x < alo - lo ? lo + threadIdx.x : ahi + (threadIdx.x - (alo - lo));
-            one(a.chunk_w[i], a.chunk_flow[i], a.rail[i]);
-        }
+        const int64_t n_edge = (alo - lo) + (hi - ahi);                 // at most 258 records outside the aligned span
+        if (t == 0)
+            for (int64_t e = threadIdx.x; e < n_edge; e += kEvThreads) {
+                const int64_t i = e < alo - lo ? lo + e : ahi + (e - (alo - lo));
+                one(a.chunk_w[i], a.chunk_flow[i], a.rail[i]);
+            }
     } else {
         for (int64_t i = lo + (int64_t)t * kEvThreads + threadIdx.x; i < hi; i += (int64_t)a.slices * kEvThreads)
             one(a.chunk_w[i], a.chunk_flow[i], a.rail[i]);
