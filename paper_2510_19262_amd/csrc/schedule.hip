@@ -147,7 +147,12 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
             const uint32_t pa = n_full < head ? n_full : head;
             const uint32_t groups = (n_full - pa) / 4;
             const uint32_t pb = pa + groups * 4;
-            for (uint32_t g = t; g < groups; g += T) {
+            // lane l of a wavefront takes a group whose global index is l mod 64, so the 64 lanes store one whole
+            // kilobyte on a 1 KiB boundary of each record array
+            const uint32_t lead_in = (uint32_t)(((out0 + pa) >> 2) & 63);
+            for (uint32_t gs = t; gs < groups + lead_in; gs += T) {
+                if (gs < lead_in) continue;
+                const uint32_t g = gs - lead_in;
                 const uint32_t p = pa + 4 * g;
                 int j = last_le<uint32_t>(st_fs, a.NF, p);
                 uint32_t nxt = st_fs[j + 1];
