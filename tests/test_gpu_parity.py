@@ -577,9 +577,11 @@ def test_config4_shape_reduced_tokens():
 
 
 # ------------------------------------------------------------------------------ record arrays off their natural alignment
+@pytest.mark.parametrize("skew", [1, 4, 68])
 @pytest.mark.parametrize("M,N,C,B", [(4, 4, 4096, 2), (8, 8, 262144, 3), (4, 2, 512, 400), (3, 20, 512, 2)])
-def test_record_arrays_off_16_byte_alignment(M, N, C, B):
-    # chunk_w / chunk_flow / perm start 4 bytes, rail 1 byte past an aligned address: the scalar paths of every kernel
+def test_record_arrays_off_16_byte_alignment(M, N, C, B, skew):
+    # chunk_w / chunk_flow / perm start 4 bytes, rail 1 byte past an aligned address (the scalar paths of every kernel),
+    # or 16 / 272 bytes past one (vector paths whose kilobytes do not sit on the boundaries the kernels cut their steps at)
     rng = np.random.default_rng(M * 31 + N * 7 + B)
     D1n = _rand_stack(rng, B, M * N, C)
     c = cpu_schedule(D1n, M, N, C)
@@ -588,10 +590,10 @@ def test_record_arrays_off_16_byte_alignment(M, N, C, B):
     D1 = torch.from_numpy(D1n).to(DEV)
 
     def bufs():
-        w = torch.empty(n + 8, dtype=torch.int32, device=DEV)[1:n + 1]
-        flow = torch.empty(n + 8, dtype=torch.int32, device=DEV)[1:n + 1]
-        perm = torch.empty(n + 8, dtype=torch.int32, device=DEV)[1:n + 1]
-        rail = torch.empty(n + 8, dtype=torch.uint8, device=DEV)[1:n + 1]
+        w = torch.empty(n + 80, dtype=torch.int32, device=DEV)[skew:n + skew]
+        flow = torch.empty(n + 80, dtype=torch.int32, device=DEV)[skew:n + skew]
+        perm = torch.empty(n + 80, dtype=torch.int32, device=DEV)[skew:n + skew]
+        rail = torch.empty(n + 80, dtype=torch.uint8, device=DEV)[skew:n + skew]
         return w, flow, perm, rail
 
     def same(off, w, flow, perm, rail, S, R, stats, what):
