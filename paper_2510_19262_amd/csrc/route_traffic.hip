@@ -80,10 +80,12 @@ __device__ __forceinline__ void rt_load_row(const RtArgs &a, int64_t row, bool l
     }
 }
 
-// picks of one row, largest first, lowest index on ties; counts each pick's destination GPU
+// picks of one row, largest first, lowest index on ties; counts each pick's destination GPU.  With k = 2 the two
+// winners come back in `pair` and the caller stores them once all its rows are picked: a store between two rows
+// made the second row's table lookups wait for it (memory operations of a wavefront complete in order).
 template <int VPL>
 __device__ __forceinline__ void rt_pick_row(const RtArgs &a, const int32_t *table, unsigned *bins, int64_t row, int64_t t_local,
-                                            float (&v)[VPL])
+                                            float (&v)[VPL], rt_i32x2 &pair)
 {
     const int rho = a.rmask >= 0 ? (int)(t_local & a.rmask) : (int)(t_local % a.R);
     int keep0 = 0;
@@ -102,21 +104,16 @@ __device__ __forceinline__ void rt_pick_row(const RtArgs &a, const int32_t *tabl
             const int32_t d = table[bi * a.R + rho];
             if ((unsigned)d < (unsigned)a.G) atomicAdd(&bins[d], 1u);
         }
-        if (a.topk_idx) {
-            if (a.k == 2) {                                   // both winners leave in one 8-byte store
-                if (sel == 0) keep0 = bi;
-                else {
-                    rt_i32x2 o; o.x = keep0; o.y = bi;
-                    __builtin_nontemporal_store(o, reinterpret_cast<rt_i32x2 *>(a.topk_idx + row * 2));
-                }
-            } else {
-                a.topk_idx[row * a.k + sel] = bi;
-            }
+        if (a.k == 2) {                                       // both winners leave in one 8-byte store, issued by the caller
+            if (sel == 0) keep0 = bi;
+            else { pair.x = keep0; pair.y = bi; }
+        } else if (a.topk_idx) {
+            a.topk_idx[row * a.k + sel] = bi;
         }
     }
 }
 
-template <int VPL, bool VEC4>
+template <int VPL, bool VEC4, bool TABLE_LDS>
 __global__ __launch_bounds__(kRtThreads) void route_traffic_kernel(RtArgs a)
 {
     extern __shared__ unsigned rt_lds[];
@@ -144,16 +141,29 @@ __global__ __launch_bounds__(kRtThreads) void route_traffic_kernel(RtArgs a)
     }
 
     for (int i = threadIdx.x; i < a.bin_stride * a.copies; i += kRtThreads) all_bins[i] = 0;
-    if (a.table_in_lds)
+    if (TABLE_LDS)
         for (int i = threadIdx.x; i < a.E * a.R; i += kRtThreads) lds_table[i] = a.expert_gpu[i];
     __syncthreads();
-    const int32_t *table = a.table_in_lds ? lds_table : a.expert_gpu;
 
     while (t < hi) {
+        rt_i32x2 pairs[kRtUnroll];
 #pragma unroll
         for (int u = 0; u < kRtUnroll; ++u) {
             const int64_t tu = t + (int64_t)u * kRtThreads;
-            if (tu < hi) rt_pick_row<VPL>(a, table, bins, row0 + tu, tu, v[u]);
+            pairs[u].x = 0; pairs[u].y = 0;
+            // two calls, so that the table is read with LDS instructions where it is in LDS: through one pointer
+            // that may be either, every lookup waited for all of the wavefront's memory traffic
+            if (tu < hi) {
+                if (TABLE_LDS) rt_pick_row<VPL>(a, lds_table, bins, row0 + tu, tu, v[u], pairs[u]);
+                else rt_pick_row<VPL>(a, a.expert_gpu, bins, row0 + tu, tu, v[u], pairs[u]);
+            }
+        }
+        if (a.topk_idx && a.k == 2) {
+#pragma unroll
+            for (int u = 0; u < kRtUnroll; ++u) {
+                const int64_t tu = t + (int64_t)u * kRtThreads;
+                if (tu < hi) __builtin_nontemporal_store(pairs[u], reinterpret_cast<rt_i32x2 *>(a.topk_idx + (row0 + tu) * 2));
+            }
         }
         t += round;
         if (t >= hi) break;
@@ -179,8 +189,10 @@ static int launch_route_traffic(const RtArgs &a, int64_t pairs, size_t lds, hipS
 {
     const bool vec4 = (a.E % 4 == 0) && (reinterpret_cast<uintptr_t>(a.logits) % 16 == 0);
     const dim3 grid((unsigned)(pairs * a.splits));
-    if (vec4) hipLaunchKernelGGL((route_traffic_kernel<VPL, true>), grid, dim3(kRtThreads), lds, st, a);
-    else hipLaunchKernelGGL((route_traffic_kernel<VPL, false>), grid, dim3(kRtThreads), lds, st, a);
+    if (vec4 && a.table_in_lds) hipLaunchKernelGGL((route_traffic_kernel<VPL, true, true>), grid, dim3(kRtThreads), lds, st, a);
+    else if (vec4) hipLaunchKernelGGL((route_traffic_kernel<VPL, true, false>), grid, dim3(kRtThreads), lds, st, a);
+    else if (a.table_in_lds) hipLaunchKernelGGL((route_traffic_kernel<VPL, false, true>), grid, dim3(kRtThreads), lds, st, a);
+    else hipLaunchKernelGGL((route_traffic_kernel<VPL, false, false>), grid, dim3(kRtThreads), lds, st, a);
     return launch_status();
 }
 
