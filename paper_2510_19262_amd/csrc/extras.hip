@@ -94,43 +94,50 @@ __global__ __launch_bounds__(kPolThreads) void policy_kernel(PolArgs a)
             for (int i = threadIdx.x; i <= cnt; i += kPolThreads) s_off[i] = a.chunk_off[inst_lo + i];
         for (int i = threadIdx.x; i < kPolSlots * kMaxRails; i += kPolThreads) (&bins[0][0])[i] = 0ull;
         __syncthreads();
-        for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPolThreads * 4) {
-            uint32_t w[4], fl[4];
-            const bool full = p + 4 <= total;
-            if (full && a.wide_ok) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(a.chunk_w + p);
-                const uint4 f = *reinterpret_cast<const uint4 *>(a.chunk_flow + p);
-                w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-                fl[0] = f.x; fl[1] = f.y; fl[2] = f.z; fl[3] = f.w;
-            } else {
+        // one sweep for instance boundaries staged in LDS and one for boundaries read from memory (through a pointer that
+        // may be either, every lookup is a flat load, which waits for all of the wavefront's memory traffic);
+        // offs[i] = start of instance inst_lo + i
+        auto sweep = [&](const int64_t *offs, int n_offs) {
+            for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPolThreads * 4) {
+                uint32_t w[4], fl[4];
+                const bool full = p + 4 <= total;
+                if (full && a.wide_ok) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(a.chunk_w + p);
+                    const uint4 f = *reinterpret_cast<const uint4 *>(a.chunk_flow + p);
+                    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+                    fl[0] = f.x; fl[1] = f.y; fl[2] = f.z; fl[3] = f.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        w[e] = (p + e < total) ? a.chunk_w[p + e] : 0u;
+                        fl[e] = (p + e < total) ? a.chunk_flow[p + e] : 0u;
+                    }
+                }
+                int li = last_le<int64_t>(offs, n_offs, p);
+                uint32_t packed = 0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    w[e] = (p + e < total) ? a.chunk_w[p + e] : 0u;
-                    fl[e] = (p + e < total) ? a.chunk_flow[p + e] : 0u;
+                    if (p + e >= total) break;
+                    int64_t nxt = offs[li + 1];
+                    while (p + e >= nxt) { ++li; nxt = offs[li + 1]; }
+                    const int64_t b = offs[li];
+                    const uint32_t r = policy_rail(a, inst_lo + li, p + e, p + e - b, fl[e]);
+                    packed |= r << (8 * e);
+                    if (r < (uint32_t)a.N) {
+                        if (li < kPolSlots) atomicAdd(&bins[li][r], (unsigned long long)w[e]);
+                        else atomicAdd(reinterpret_cast<unsigned long long *>(a.S + (int64_t)(inst_lo + li) * a.N + r), (unsigned long long)w[e]);
+                    }
+                }
+                if (full && a.wide_ok) {
+                    *reinterpret_cast<uint32_t *>(a.rail + p) = packed;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) if (p + e < total) a.rail[p + e] = (uint8_t)(packed >> (8 * e));
                 }
             }
-            int li = staged ? last_le<int64_t>(s_off, cnt, p) : last_le<int64_t>(a.chunk_off, a.n_inst, p) - inst_lo;
-            uint32_t packed = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (p + e >= total) break;
-                int64_t nxt = staged ? s_off[li + 1] : a.chunk_off[inst_lo + li + 1];
-                while (p + e >= nxt) { ++li; nxt = staged ? s_off[li + 1] : a.chunk_off[inst_lo + li + 1]; }
-                const int64_t b = staged ? s_off[li] : a.chunk_off[inst_lo + li];
-                const uint32_t r = policy_rail(a, inst_lo + li, p + e, p + e - b, fl[e]);
-                packed |= r << (8 * e);
-                if (r < (uint32_t)a.N) {
-                    if (li < kPolSlots) atomicAdd(&bins[li][r], (unsigned long long)w[e]);
-                    else atomicAdd(reinterpret_cast<unsigned long long *>(a.S + (int64_t)(inst_lo + li) * a.N + r), (unsigned long long)w[e]);
-                }
-            }
-            if (full && a.wide_ok) {
-                *reinterpret_cast<uint32_t *>(a.rail + p) = packed;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) if (p + e < total) a.rail[p + e] = (uint8_t)(packed >> (8 * e));
-            }
-        }
+        };
+        if (staged) sweep(s_off, cnt);
+        else sweep(a.chunk_off + inst_lo, a.n_inst - inst_lo);
         __syncthreads();
         for (int i = threadIdx.x; i < kPolSlots * a.N; i += kPolThreads) {
             const int li = i / a.N, r = i % a.N;

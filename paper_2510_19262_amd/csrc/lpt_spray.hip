@@ -149,43 +149,50 @@ __global__ __launch_bounds__(kPfThreads) void lpt_prefix_kernel(const int64_t *_
                 }
                 continue;
             }
-            for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPfThreads * 4) {
-                uint32_t w[4];
-                const bool full = p + 4 <= total;
-                if (full && wide_ok) {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(chunk_w + p);
-                    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-                } else {
+            // The general sweep, once for boundaries staged in LDS and once for boundaries read from memory: through
+            // one pointer that may be either, every lookup was a flat load, which waits for all of the wavefront's
+            // memory traffic.  offs[i] = start of instance inst_lo + i; first_w(i) = its first weight.
+            auto sweep = [&](const int64_t *offs, int n_offs, auto first_w) {
+                for (int64_t p = t0 + (int64_t)threadIdx.x * 4; p < t1; p += (int64_t)kPfThreads * 4) {
+                    uint32_t w[4];
+                    const bool full = p + 4 <= total;
+                    if (full && wide_ok) {
+                        const uint4 v = *reinterpret_cast<const uint4 *>(chunk_w + p);
+                        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) w[e] = (p + e < total) ? chunk_w[p + e] : 0u;
-                }
-                int li = staged ? last_le<int64_t>(s_off, cnt, p) : last_le<int64_t>(chunk_off, n_inst, p) - inst_lo;
-                uint32_t packed = 0;
-                int64_t miss_inst = -1, miss_pos = 0;          // first mismatch seen by this thread, per instance
+                        for (int e = 0; e < 4; ++e) w[e] = (p + e < total) ? chunk_w[p + e] : 0u;
+                    }
+                    int li = last_le<int64_t>(offs, n_offs, p);
+                    uint32_t packed = 0;
+                    int64_t miss_inst = -1, miss_pos = 0;      // first mismatch seen by this thread, per instance
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (p + e >= total) break;
-                    int64_t nxt = staged ? s_off[li + 1] : chunk_off[inst_lo + li + 1];
-                    while (p + e >= nxt) { ++li; nxt = staged ? s_off[li + 1] : chunk_off[inst_lo + li + 1]; }
-                    const int64_t b = staged ? s_off[li] : chunk_off[inst_lo + li];
-                    const uint32_t w0 = staged ? s_w0[li] : chunk_w[b];
-                    const int64_t i = p + e - b;
-                    const uint32_t r = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
-                    packed |= r << (8 * e);
-                    if (w[e] != w0 && miss_inst != inst_lo + li) {
-                        if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
-                        miss_inst = inst_lo + li; miss_pos = i;
+                    for (int e = 0; e < 4; ++e) {
+                        if (p + e >= total) break;
+                        int64_t nxt = offs[li + 1];
+                        while (p + e >= nxt) { ++li; nxt = offs[li + 1]; }
+                        const int64_t b = offs[li];
+                        const uint32_t w0 = first_w(li, b);
+                        const int64_t i = p + e - b;
+                        const uint32_t r = nmask >= 0 ? ((uint32_t)i & (uint32_t)nmask) : (uint32_t)((uint64_t)i % (uint64_t)N);
+                        packed |= r << (8 * e);
+                        if (w[e] != w0 && miss_inst != inst_lo + li) {
+                            if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
+                            miss_inst = inst_lo + li; miss_pos = i;
+                        }
+                    }
+                    // most positions behind the run's end find a smaller value already there and skip the atomic
+                    if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
+                    if (full && wide_ok) {
+                        *reinterpret_cast<uint32_t *>(rail + p) = packed;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) if (p + e < total) rail[p + e] = (uint8_t)(packed >> (8 * e));
                     }
                 }
-                // most positions behind the run's end find a smaller value already there and skip the atomic
-                if (miss_inst >= 0 && run_end[miss_inst * N] > miss_pos) atomicMin((long long *)&run_end[miss_inst * N], (long long)miss_pos);
-                if (full && wide_ok) {
-                    *reinterpret_cast<uint32_t *>(rail + p) = packed;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) if (p + e < total) rail[p + e] = (uint8_t)(packed >> (8 * e));
-                }
-            }
+            };
+            if (staged) sweep(s_off, cnt, [&](int li, int64_t) { return s_w0[li]; });
+            else sweep(chunk_off + inst_lo, n_inst - inst_lo, [&](int, int64_t b) { return chunk_w[b]; });
         }
     }
 }

@@ -45,7 +45,7 @@ __device__ __forceinline__ void tm_count(const TmArgs &a, const int32_t *table, 
 
 constexpr int kTmUnroll = 4;        // 16-byte index loads in flight per thread
 
-template <bool FAST>
+template <bool FAST, bool TABLE_LDS>
 __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
 {
     extern __shared__ unsigned tm_lds[];
@@ -58,10 +58,13 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
     const int part = blockIdx.x % a.splits;
 
     for (int i = threadIdx.x; i < a.bin_stride * a.copies; i += kTmThreads) all_bins[i] = 0;
-    if (a.table_in_lds)
+    if (TABLE_LDS)
         for (int i = threadIdx.x; i < a.E * a.R; i += kTmThreads) lds_table[i] = a.expert_gpu[i];
     __syncthreads();
-    const int32_t *table = a.table_in_lds ? lds_table : a.expert_gpu;
+    // one definite kind of memory per instantiation: through a pointer that may be LDS or global every lookup is a
+    // flat load, which waits for all of the wavefront's memory traffic
+    const int32_t *table;
+    if constexpr (TABLE_LDS) table = lds_table; else table = a.expert_gpu;
 
     // this workgroup's slice of the pair's slots, cut at multiples of 4 slots
     const int64_t quads = (a.slots_per_gpu + 3) / 4;
@@ -144,9 +147,11 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
         if (int rc = launch_status()) return rc;
     }
     const size_t lds = sizeof(unsigned) * (size_t)a.bin_stride * a.copies + (a.table_in_lds ? sizeof(int32_t) * (size_t)E * R : 0);
-    if (a.kshift >= 0 && a.rmask >= 0)
-        hipLaunchKernelGGL(traffic_matrix_kernel<true>, dim3((unsigned)(pairs * splits)), dim3(kTmThreads), lds, st, a);
-    else
-        hipLaunchKernelGGL(traffic_matrix_kernel<false>, dim3((unsigned)(pairs * splits)), dim3(kTmThreads), lds, st, a);
+    const dim3 grid((unsigned)(pairs * splits));
+    const bool fast = a.kshift >= 0 && a.rmask >= 0;
+    if (fast && a.table_in_lds) hipLaunchKernelGGL((traffic_matrix_kernel<true, true>), grid, dim3(kTmThreads), lds, st, a);
+    else if (fast) hipLaunchKernelGGL((traffic_matrix_kernel<true, false>), grid, dim3(kTmThreads), lds, st, a);
+    else if (a.table_in_lds) hipLaunchKernelGGL((traffic_matrix_kernel<false, true>), grid, dim3(kTmThreads), lds, st, a);
+    else hipLaunchKernelGGL((traffic_matrix_kernel<false, false>), grid, dim3(kTmThreads), lds, st, a);
     return launch_status();
 }
