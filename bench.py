@@ -25,8 +25,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes the launches of one route_traffic call (main kernel + reduction of the slice counts) move on this
 # workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy of known traffic (profiles/c2_whole_path.md).
-# route_traffic_kernel 1038.68 MiB read + 272.00 MiB written, rt_reduce_kernel 16.04 MiB read + 1.00 MiB written.
-ROUTE_TRAFFIC_C2_TRAFFIC_BYTES = int((1038.68 + 272.00 + 16.04 + 1.00) * 1024 * 1024)
+# route_traffic_kernel 1043.54 MiB read + 272.00 MiB written, rt_reduce_kernel 16.04 MiB read + 1.00 MiB written.
+ROUTE_TRAFFIC_C2_TRAFFIC_BYTES = int((1043.54 + 272.00 + 16.04 + 1.00) * 1024 * 1024)
 
 
 def parse():
