@@ -314,34 +314,43 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
 
     // Weights of period p: lane q of a group holds chunks p*STEP + r*GW + q; past the end weight 0 (changes nothing).
     // The weights of period p + 2 are requested before the chain of period p and taken in behind it, before the
-    // rails are stored.  Lanes past the end of their instance load a word that always exists instead of skipping
-    // the load: a branch around the loads made the compiler wait for everything in flight - the request just
-    // issued and the stores of the period before - in front of every chain.
+    // rails are stored.  Lanes past the end of their instance load a word that exists (their instance's last
+    // weight, or a spare word once the instance is done) instead of skipping the load: a branch around the loads
+    // made the compiler wait for everything in flight - the request just issued and the stores of the period
+    // before - in front of every chain.  Positions are compared as 32-bit distances to the end of the instance
+    // (`left`, capped far above a period) and addressed from one pointer per period.
     const uint32_t *const spare = reinterpret_cast<const uint32_t *>(chunk_off);
-    auto request = [&](int64_t i0, unsigned (&wv)[REGS]) {
+    unsigned in_period[REGS];                       // position of this lane's chunk r inside a period
 #pragma unroll
-        for (int r = 0; r < REGS; ++r) {
-            const int64_t i = i0 + r * GW + q;
-            const uint32_t *src = (i < len) ? chunk_w + beg + i : spare;
-            wv[r] = *src;
-        }
+    for (int r = 0; r < REGS; ++r) in_period[r] = (unsigned)(r * GW) + q;
+    auto left_at = [&](int64_t i0) {                // chunks of the instance from position i0 on, capped at 2^30
+        const int64_t d = len - i0;
+        return (unsigned)(d < 0 ? 0 : d > (int64_t)(1 << 30) ? (int64_t)(1 << 30) : d);
     };
-    auto take_in = [&](int64_t i0, unsigned (&wv)[REGS]) {
+    auto request = [&](int64_t i0, unsigned left, unsigned (&wv)[REGS]) {
+        const uint32_t *from = left ? chunk_w + beg + i0 : spare;
+        const unsigned last = left ? left - 1u : 0u;
+#pragma unroll
+        for (int r = 0; r < REGS; ++r) wv[r] = from[in_period[r] < last ? in_period[r] : last];
+    };
+    auto take_in = [&](unsigned left, unsigned (&wv)[REGS]) {
 #pragma unroll
         for (int r = 0; r < REGS; ++r) {
             asm volatile("" : "+v"(wv[r]) : : "memory");    // nothing below (the stores least of all) moves above the wait
-            wv[r] = (i0 + r * GW + q < len) ? wv[r] : 0u;
+            wv[r] = in_period[r] < left ? wv[r] : 0u;
         }
     };
     unsigned wv_cur[REGS], wv_nxt[REGS];
-    request(0, wv_cur);
-    request(STEP, wv_nxt);
-    take_in(0, wv_cur);
-    take_in(STEP, wv_nxt);
+    unsigned left = left_at(0), left_nxt = left_at(STEP);   // of the period in hand and of the one after it
+    request(0, left, wv_cur);
+    request(STEP, left_nxt, wv_nxt);
+    take_in(left, wv_cur);
+    take_in(left_nxt, wv_nxt);
 
     for (int64_t i0 = 0; i0 < max_len; i0 += STEP) {
         unsigned wv_far[REGS], won[REGS];
-        request(i0 + 2 * STEP, wv_far);
+        const unsigned left_far = left_at(i0 + 2 * STEP);
+        request(i0 + 2 * STEP, left_far, wv_far);
 #pragma unroll
         for (int r = 0; r < REGS; ++r) won[r] = 0;
         if (!exact) {
@@ -356,14 +365,14 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
         bool closed = false;                        // wave-uniform
         unsigned w0 = 0;
         if (RUNS && !exact) {
-            const bool done = i0 >= len;            // this group's instance is already finished
+            const bool done = left == 0u;           // this group's instance is already finished
             w0 = group_bcast<GW, 0>(wv_cur[0]);
             bool same = true;
 #pragma unroll
             for (int r = 0; r < REGS; ++r) same = same && (wv_cur[r] == w0);
             const unsigned dmin = group_min_u32<GW>(key) >> S;
             const unsigned dmax = group_max_u32<GW>(has_rail ? (key >> S) : 0u);
-            const bool ok = done || (same && w0 != 0u && (i0 + STEP <= len) && (dmax - dmin) < w0);
+            const bool ok = done || (same && w0 != 0u && left >= (unsigned)STEP && (dmax - dmin) < w0);
             closed = __ballot(!ok) == 0ull;
             if (done) w0 = 0;
         }
@@ -383,14 +392,14 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
             const unsigned adv = group_min_u32<GW>(key) >> S;
             if (has_rail) { key -= adv << S; base += adv; }
         }
-        take_in(i0 + 2 * STEP, wv_far);
+        take_in(left_far, wv_far);
+        uint8_t *const to = rail + beg + i0 + q;
 #pragma unroll
-        for (int r = 0; r < REGS; ++r) {
-            const int64_t i = i0 + r * GW + q;
-            if (i < len) rail[beg + i] = (uint8_t)won[r];
-        }
+        for (int r = 0; r < REGS; ++r)
+            if (in_period[r] < left) to[r * GW] = (uint8_t)won[r];
 #pragma unroll
         for (int r = 0; r < REGS; ++r) { wv_cur[r] = wv_nxt[r]; wv_nxt[r] = wv_far[r]; }
+        left = left_nxt; left_nxt = left_far;
     }
     if (has_rail) S_out[(int64_t)inst * N + q] = (int64_t)(exact ? load : base + (unsigned long long)(key >> S));
 }
