@@ -332,20 +332,34 @@ def main():
         import oracle
         L = B if args.cpu_layers < 0 else min(args.cpu_layers, B)
         x = logits[: L * cfg.rows_per_layer].cpu().numpy()
+
+        def cpu_path(xs, layers):
+            idx = oracle.route_topk(xs, cfg.k)
+            D1c = oracle.traffic_matrix(idx, layers, cfg.tokens_per_gpu, eg_np, cfg.payload_bytes, cfg.M, cfg.N)
+            off, w, flow, _ = oracle.chunk_sort_batch(D1c, cfg.M, cfg.N, cfg.chunk_bytes)
+            rail, S = oracle.lpt_batch(off, w, layers, cfg.M, cfg.N)
+            _, R, stats = oracle.eval_batch(off, w, flow, rail, layers, cfg.M, cfg.N)
+            return off, rail, R, stats
         c0 = time.perf_counter()
-        idx_c = oracle.route_topk(x, cfg.k)
-        D1_c = oracle.traffic_matrix(idx_c, L, cfg.tokens_per_gpu, eg_np, cfg.payload_bytes, cfg.M, cfg.N)
-        off_c, w_c, flow_c, perm_c = oracle.chunk_sort_batch(D1_c, cfg.M, cfg.N, cfg.chunk_bytes)
-        rail_c, S_c = oracle.lpt_batch(off_c, w_c, L, cfg.M, cfg.N)
-        _, R_c, stats_c = oracle.eval_batch(off_c, w_c, flow_c, rail_c, L, cfg.M, cfg.N)
+        off_c, rail_c, R_c, stats_c = cpu_path(x, L)
         c1 = time.perf_counter()
         n_c = int(off_c[-1])
+        # the same oracle on one thread, on the first quarter of the sample
+        L1 = max(L // 4, 1)
+        all_threads = oracle.num_threads()
+        oracle.set_threads(1)
+        s0 = time.perf_counter()
+        off_1 = cpu_path(x[: L1 * cfg.rows_per_layer], L1)[0]
+        s1 = time.perf_counter()
+        oracle.set_threads(all_threads)
         same = (np.array_equal(plan.stats[:L].cpu().numpy(), stats_c)
                 and np.array_equal(plan.rail[:n_c].cpu().numpy(), rail_c)
                 and np.array_equal(plan.R[:L].cpu().numpy(), R_c))
-        out["cpu_baseline"] = {"value": n_c / (c1 - c0), "unit": "chunks/s", "cores": oracle.num_threads(), "kind": "oracle",
+        out["cpu_baseline"] = {"value": n_c / (c1 - c0), "unit": "chunks/s", "cores": all_threads, "kind": "oracle",
                                "sample": f"first {L} of {B} layers ({L * cfg.rows_per_layer} rows, {n_c} chunks), whole path, "
-                                         f"{c1 - c0:.2f} s", "matches_gpu": bool(same)}
+                                         f"{c1 - c0:.2f} s", "matches_gpu": bool(same),
+                               "single_thread": {"value": int(off_1[-1]) / (s1 - s0), "unit": "chunks/s", "cores": 1,
+                                                 "sample": f"first {L1} layers, {s1 - s0:.2f} s"}}
     print(json.dumps(out))
 
 

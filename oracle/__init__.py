@@ -52,6 +52,11 @@ def num_threads() -> int:
     return lib().oracle_num_threads()
 
 
+def set_threads(n: int) -> int:
+    """Threads of the oracle's parallel loops from now on (n < 1: all the runtime offers); returns the count in force."""
+    return lib().oracle_set_threads(int(n))
+
+
 def route_topk(logits: np.ndarray, k: int) -> np.ndarray:
     logits = _chk(logits, np.float32)
     rows, E = logits.shape

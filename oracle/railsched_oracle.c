@@ -52,6 +52,18 @@ int oracle_num_threads(void)
 #endif
 }
 
+/* threads the parallel loops use from now on (n < 1: as many as the runtime offers); returns the count in force */
+int oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    omp_set_num_threads(n < 1 ? omp_get_num_procs() : n);
+    return omp_get_max_threads();
+#else
+    (void)n;
+    return 1;
+#endif
+}
+
 /* ------------------------------------------------------------------------
  * Step 1 (Algorithm 1 step 1, "Gate"; Top-K of Section 6.3): for every token
  * row the k experts with the largest router logit, best first.  The j-th
