@@ -120,6 +120,22 @@ def test_lpt_beats_the_comparison_schemes_on_config2_shape():
         assert np.all(st[:, 1] >= st_lpt[:, 1])                      # LPT's worst send NIC is never worse
 
 
+def test_policy_instances_mostly_empty():
+    # thousands of instances of a chunk or two: a streaming tile holds more instance boundaries than it stages in LDS
+    M, N, C, B = 2, 2, 4096, 9000
+    rng = np.random.default_rng(6)
+    D1 = rng.integers(1, 3 * C, size=(B, M * N, M * N)).astype(np.int64)
+    D1[rng.random(D1.shape) < 0.93] = 0
+    topo = rs.Topo(M, N, C)
+    off, w, flow = _records_dev(D1, topo)
+    n = int(off[-1].item())
+    assert n < 4 * B * M                        # fewer than four chunks per instance on average
+    for policy in ("flow_hash", "random_spray", "round_robin", "nic_direct"):
+        rail, S = rs.assign_policy(policy, 3, off, w, flow, B, topo)
+        rail_c, S_c = oracle.assign_policy(policy, 3, off.cpu().numpy(), _u32(w)[:n], _u32(flow)[:n], B, M, N)
+        assert np.array_equal(rail.cpu().numpy()[:n], rail_c) and np.array_equal(S.cpu().numpy(), S_c), policy
+
+
 def test_policy_and_ports_on_record_arrays_off_16_byte_alignment():
     # records 4 bytes, rails and ports 1 byte past an aligned address: the scalar paths of the comparison schemes
     M, N, C, B, P = 4, 8, 4096, 3, 5

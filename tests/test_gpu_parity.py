@@ -525,6 +525,17 @@ def test_lpt_many_instances():
     _lpt_case(insts, M, 8, batch)
 
 
+@pytest.mark.parametrize("N", [4, 8])
+def test_lpt_instances_mostly_empty(N):
+    # tens of thousands of instances of 0-2 chunks: a streaming tile of the leading-run kernel holds more instance
+    # boundaries than it stages in LDS and reads them from memory instead
+    rng = np.random.default_rng(77 + N)
+    n_inst = 60000
+    lens = rng.choice([0, 0, 0, 0, 0, 1, 2], size=n_inst)                 # 0.43 chunks per instance: 2 400 instances per 1 Ki tile
+    insts = [np.sort(rng.integers(1, 9, size=n) * 4096)[::-1] for n in lens]
+    _lpt_case(insts, 1, N, batch=n_inst)
+
+
 # ------------------------------------------------------------------------------ whole path on the paper-shaped configs
 def _moe_pipeline_gpu(cfg, layers):
     topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes, cfg.rail_bw_Bps)
