@@ -93,7 +93,7 @@ def main():
     del idx0, D10
     plan = rs.Plan(topo, B, total_chunks, dev, rows=rows, k=cfg.k, want_perm=True)
 
-    ws_rt = torch.empty(max(rs.route_traffic_workspace_bytes(B, cfg.tokens_per_gpu, cfg.E, topo), 256), dtype=torch.uint8, device=dev)
+    ws_rt = torch.empty(max(rs.route_traffic_workspace_bytes(B, cfg.tokens_per_gpu, cfg.E, cfg.k, topo), 256), dtype=torch.uint8, device=dev)
     names = {True: ("route_traffic", "schedule"),
              False: ("route_topk", "traffic_matrix", "chunk_sort", "lpt_spray", "eval")}
 

@@ -17,10 +17,16 @@
  *     buffer (inputs, outputs, workspace); the library allocates nothing, keeps no state between
  *     calls (LoadState is reset for every all-to-all round, Section 5.2) and never frees anything.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is enqueued
- *     asynchronously on it; no call synchronises the host with the device.
+ *     asynchronously on it; no call but railsched_check_capacity synchronises the host with the device.
  *   - Every function returns 0 (RAILSCHED_OK) or a negative railsched_status.  Arguments are
  *     validated on the host before anything is launched; on an error nothing has been enqueued.
  *   - All outputs are integers and are defined bit-exactly.
+ *   - Capacity.  Every call that reads or writes the per-chunk arrays (chunk_w, chunk_flow, perm, rail, port) takes
+ *     `capacity`, the number of records those arrays hold.  The chunk count chunk_off[batch*M] exists on the device
+ *     only; when it exceeds `capacity` the call touches none of the per-chunk arrays and fills its remaining outputs
+ *     with -1 instead (S for stage 4, R and stats for stage 5, all three for railsched_schedule), so a caller that
+ *     never synchronises still finds the overflow in whatever it reads back; chunk_off is complete either way.
+ *     railsched_check_capacity reports the same condition to the host as RAILSCHED_ERR_CAPACITY.
  *   - Limits: 1 <= N <= 64, 1 <= M, G <= 16384, N*G <= 16384 for chunk_sort, 1 <= k <= E <= 1024,
  *     1 <= C < 2^32, every instance holds fewer than 2^32 chunks and fewer than 2^56 bytes.
  */
@@ -39,7 +45,7 @@ typedef enum railsched_status {
     RAILSCHED_ERR_INVALID_ARG = -1, /* a size or count is out of its documented range           */
     RAILSCHED_ERR_NULL_PTR    = -2, /* a required pointer is NULL                               */
     RAILSCHED_ERR_UNSUPPORTED = -3, /* valid in the paper's model but beyond this build's limits */
-    RAILSCHED_ERR_CAPACITY    = -4, /* reserved: record arrays smaller than the chunk count      */
+    RAILSCHED_ERR_CAPACITY    = -4, /* railsched_check_capacity: more chunks than the arrays hold */
     RAILSCHED_ERR_WORKSPACE   = -5, /* workspace missing or smaller than *_workspace_bytes()     */
     RAILSCHED_ERR_HIP         = -6  /* the HIP runtime refused a launch                          */
 } railsched_status;
@@ -57,6 +63,15 @@ typedef struct railsched_topo {
 
 const char *railsched_version(void);
 const char *railsched_strerror(int status);
+
+/* Waits until `stream` has drained, reads the chunk count chunk_off[batch*M] back and compares it with `capacity`
+ * (Section 5.1: the number of atomic flows depends on the traffic, so record arrays sized ahead of time can turn
+ * out too small).  The only call of the library that synchronises the host with the device.
+ *   chunk_off [batch*M + 1] int64, as written by stage 3        (in)
+ *   h_total   HOST pointer, receives the chunk count            (out, nullable)
+ * Returns RAILSCHED_OK, RAILSCHED_ERR_CAPACITY (count > capacity; *h_total is still set), NULL_PTR, INVALID_ARG, HIP. */
+int railsched_check_capacity(const int64_t *chunk_off, int32_t batch, const railsched_topo_t *h_topo, int64_t capacity,
+                             int64_t *h_total, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Stage 1 - gating decision (Algorithm 1 step 1; Top-K expert selection of Section 6.3).
@@ -79,11 +94,16 @@ int railsched_route_topk(const float *logits, int64_t rows, int32_t E, int32_t k
  *   topk_idx   [batch*G*tokens_per_gpu][k] int32, values in [0,E)  (in; out-of-range values are ignored)
  *   expert_gpu [E][R] int32, values in [0,G)                        (in; same rule)
  *   D1         [batch][G][G] int64                                  (out, fully overwritten)
- * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (G > 16384).
+ *   ws         railsched_traffic_matrix_workspace_bytes(...) bytes of device memory, 4-byte aligned
+ *              (scratch: destination counts of the slices a (matrix, source GPU) pair is cut into; summed in a
+ *              fixed order by a second kernel, so no atomics leave the workgroups; contents undefined afterwards)
+ * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (G > 16384), WORKSPACE.
  * ------------------------------------------------------------------------------------------- */
+size_t railsched_traffic_matrix_workspace_bytes(int32_t batch, int64_t tokens_per_gpu, int32_t k,
+                                                const railsched_topo_t *h_topo);
 int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, int64_t tokens_per_gpu, int32_t k,
                              const int32_t *expert_gpu, int32_t E, int32_t R, int64_t payload_bytes,
-                             const railsched_topo_t *h_topo, int64_t *D1, void *stream);
+                             const railsched_topo_t *h_topo, int64_t *D1, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Stages 1 and 2 in one call (Algorithm 1 steps 1-2: gate, then selection of input slices by gate
@@ -100,7 +120,7 @@ int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, int64_t tok
  * Errors: NULL_PTR (also topk_idx == NULL with E > 8), INVALID_ARG, UNSUPPORTED (E > 1024, G > 16384),
  * WORKSPACE (ws missing, misaligned or smaller than the query's answer).
  * ------------------------------------------------------------------------------------------- */
-size_t railsched_route_traffic_workspace_bytes(int32_t batch, int64_t tokens_per_gpu, int32_t E,
+size_t railsched_route_traffic_workspace_bytes(int32_t batch, int64_t tokens_per_gpu, int32_t E, int32_t k,
                                                const railsched_topo_t *h_topo);
 int railsched_route_traffic(const float *logits, int32_t batch, int64_t tokens_per_gpu, int32_t E, int32_t k,
                             const int32_t *expert_gpu, int32_t R, int64_t payload_bytes,
@@ -120,10 +140,9 @@ int railsched_route_traffic(const float *logits, int32_t batch, int64_t tokens_p
  *   chunk_flow [capacity] uint32: n*G + destination GPU              (out)
  *   perm       [capacity] uint32: canonical position inside the instance of the chunk now at this
  *              sorted position                                      (out, nullable)
- * With chunk_w == NULL only chunk_off is produced (a count query: read chunk_off[batch*M] to size
- * the record arrays).  If the total chunk count exceeds `capacity` the record arrays are left
- * untouched and chunk_off is still complete: compare chunk_off[batch*M] with capacity after the
- * stream has drained.
+ * With chunk_w == NULL only chunk_off is produced (a count query: railsched_check_capacity then
+ * returns the total to size the record arrays with).  If the total chunk count exceeds `capacity`
+ * the record arrays are left untouched and chunk_off is still complete.
  * Workspace: railsched_chunk_sort_workspace_bytes(batch, topo) bytes, 256-byte aligned.
  * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (N*G > 16384, C >= 2^32), WORKSPACE.
  * ------------------------------------------------------------------------------------------- */
@@ -139,13 +158,14 @@ int railsched_chunk_sort(const int64_t *D1, int32_t batch, const railsched_topo_
  * (Section 4.1, load matrix S).  Weights need not come from stage 3: any sequence is scheduled in
  * the order given (the guarantees of Theorem 4 need it non-increasing).
  *   chunk_off [batch*M + 1] int64   (in)
- *   chunk_w   [chunk_off[batch*M]]  (in)
- *   rail      [chunk_off[batch*M]] uint8, values in [0,N)  (out)
- *   S         [batch][M][N] int64                          (out)
+ *   chunk_w   [capacity] uint32     (in; the first chunk_off[batch*M] are read)
+ *   rail      [capacity] uint8, values in [0,N)            (out; the first chunk_off[batch*M] are written)
+ *   S         [batch][M][N] int64                          (out; every entry -1 if chunk_off[batch*M] > capacity,
+ *                                                           and then chunk_w is not read and rail not written)
  * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (N > 64).
  * ------------------------------------------------------------------------------------------- */
 int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
-                        const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream);
+                        const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S, void *stream);
 
 /* Same function, same arguments, same outputs bit for bit (Algorithm 2 step 3), but every single chunk
  * goes through the cross-lane argmin; railsched_lpt_spray above additionally assigns whole periods of
@@ -153,7 +173,7 @@ int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32
  * bound L_max <= L_opt + w_max of the Theorem 4 proof is what makes that state the common one).
  * Kept as the plain reference kernel for measurements and cross-checks. */
 int railsched_lpt_spray_chunkwise(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
-                                  const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream);
+                                  const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Stage 5 - load evaluation (Section 4.1 load matrices S and R; Theorem 2; Theorem 3).
@@ -167,15 +187,18 @@ int railsched_lpt_spray_chunkwise(const int64_t *chunk_off, const uint32_t *chun
  *         (uniform split of Theorem 3; one chunk is indivisible, Theorem 4 proof)
  *     [4] total bytes scheduled  [5] w_max  [6] chunk count
  *     [7] max over nodes k of (max_n S[b][k][n] - min_n S[b][k][n])
- * S is read as produced by stage 4.  No global atomics are used: every workgroup writes its
- * partial receive loads to the workspace and a second kernel adds them in a fixed order.
+ * S is read as produced by stage 4.  No global atomics are used (the bins of a workgroup are
+ * LDS-private integer atomics): every workgroup writes its partial receive loads to the workspace
+ * and a second kernel adds them in a fixed order.
+ * chunk_w, chunk_flow, rail hold `capacity` records; if chunk_off[batch*M] > capacity none of them is
+ * read and every entry of R and stats is -1.
  * Workspace: railsched_eval_workspace_bytes(batch, topo) bytes, 256-byte aligned.
  * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED, WORKSPACE.
  * ------------------------------------------------------------------------------------------- */
 size_t railsched_eval_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo);
 int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w, const uint32_t *chunk_flow,
                    const uint8_t *rail, const int64_t *S, int32_t batch, const railsched_topo_t *h_topo,
-                   int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream);
+                   int64_t capacity, int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Stages 3-5 in one call (Algorithm 2 steps 1-3 and 6; Section 4.1 S and R; Theorems 2-3): the outputs of
@@ -188,7 +211,7 @@ int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w, const uint
  *   D1 [batch][G][G] int64 (in);  chunk_off [batch*M+1];  chunk_w, chunk_flow, perm (perm may be NULL),
  *   rail: `capacity` records each;  S, R [batch][M][N] int64;  stats [batch][8] int64   (out)
  *   ws: railsched_schedule_workspace_bytes(batch, topo) bytes, 256-byte aligned.
- * If chunk_off[batch*M] > capacity the record arrays are left alone and S, R, stats are undefined.
+ * If chunk_off[batch*M] > capacity the record arrays are left alone and every entry of S, R and stats is -1.
  * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (as the three stages), WORKSPACE.
  * ------------------------------------------------------------------------------------------- */
 size_t railsched_schedule_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo);
@@ -213,24 +236,24 @@ int railsched_transpose_matrix(const int64_t *D1, int32_t batch, const railsched
  *   RAILSCHED_POLICY_RANDOM_SPRAY per chunk: hash(index of the chunk in the record arrays) mod N
  *   RAILSCHED_POLICY_ROUND_ROBIN  chunk i of the instance, in stored order, takes rail i mod N
  * hash(x) = splitmix64 finaliser of (seed + 0x9E3779B97F4A7C15 * (x + 1)), 64-bit wrapping.
- *   rail [chunks] uint8 (out), S [batch][M][N] int64 send loads (out); feed both to railsched_eval.
+ *   rail [capacity] uint8 (out), S [batch][M][N] int64 send loads (out); feed both to railsched_eval.
+ * If chunk_off[batch*M] > capacity the per-chunk arrays are left alone and every entry of S is -1.
  * Errors: NULL_PTR, INVALID_ARG (unknown policy), UNSUPPORTED.
  * ------------------------------------------------------------------------------------------- */
 enum { RAILSCHED_POLICY_NIC_DIRECT = 0, RAILSCHED_POLICY_FLOW_HASH = 1, RAILSCHED_POLICY_RANDOM_SPRAY = 2,
        RAILSCHED_POLICY_ROUND_ROBIN = 3 };
 int railsched_assign_policy(int32_t policy, uint64_t seed, const int64_t *chunk_off, const uint32_t *chunk_w,
                             const uint32_t *chunk_flow, int32_t batch, const railsched_topo_t *h_topo,
-                            uint8_t *rail, int64_t *S, void *stream);
+                            int64_t capacity, uint8_t *rail, int64_t *S, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Spraying execution, port choice (Algorithm 2 step 4: "select port p from NIC j* by round-robin"):
+ * Spraying execution, port choice (Algorithm 2 step 4: round-robin port choice inside the chosen NIC):
  * each rail of a node hands its chunks to its `ports` queue pairs in turn; the chunk that is the c-th
  * one (c = 0, 1, ...) put on its rail inside its instance, in stored order, takes port c mod ports.
  *   rail [chunks] uint8 (in), port [chunks] uint8 (out), 1 <= ports <= 256.
- * `capacity` is an upper bound of the chunk count (the size of the record arrays) and sizes the
- * workspace: railsched_port_round_robin_workspace_bytes(batch, topo, capacity) bytes, 256-byte aligned.
- * If chunk_off[batch*M] exceeds capacity, the ports of the chunks beyond what the workspace covers are
- * not written.
+ * `capacity` is the number of records rail and port hold and sizes the workspace:
+ * railsched_port_round_robin_workspace_bytes(batch, topo, capacity) bytes, 256-byte aligned.
+ * If chunk_off[batch*M] exceeds capacity, rail is not read and port not written.
  * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (ports > 256), WORKSPACE.
  * ------------------------------------------------------------------------------------------- */
 size_t railsched_port_round_robin_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo, int64_t capacity);

@@ -137,6 +137,20 @@ def eval_matrix(chunk_off, w, flow, rail, M, N):
     return Ssum, R, stats
 
 
+def schedule_matrix_by_node(D1mat, M, N, chunk_bytes, include_intra=0):
+    """One whole matrix, one source node at a time (records of a node are dropped once its loads are added):
+    (chunk_off [M+1], S [M][N], R [M][N], stats [8])."""
+    D1mat = _chk(D1mat, np.int64)
+    off = np.empty(M + 1, dtype=np.int64)
+    S = np.empty((M, N), dtype=np.int64)
+    R = np.empty((M, N), dtype=np.int64)
+    stats = np.empty(8, dtype=np.int64)
+    rc = lib().oracle_schedule_matrix_by_node(_p(D1mat), M, N, C.c_int64(chunk_bytes), include_intra, _p(off), _p(S), _p(R), _p(stats))
+    if rc:
+        raise MemoryError("oracle_schedule_matrix_by_node")
+    return off, S, R, stats
+
+
 # ---------------------------------------------------------------- batched
 def chunk_count_batch(D1, M, N, chunk_bytes, include_intra=0) -> np.ndarray:
     D1 = _chk(D1, np.int64)

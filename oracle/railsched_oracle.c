@@ -291,26 +291,14 @@ int64_t oracle_opt_makespan(int n, const uint32_t *w, int N)
  *   stats[4] total bytes, stats[5] w_max, stats[6] chunk count
  *   stats[7] max over nodes of (max_n S[k][n] - min_n S[k][n])
  * ---------------------------------------------------------------------- */
-void oracle_eval(const int64_t *chunk_off, const uint32_t *w, const uint32_t *flow,
-                 const uint8_t *rail, int M, int N, int64_t *Ssum, int64_t *R, int64_t *stats)
+/* stats[0..8) of one matrix from its load matrices, its largest chunk weight and its chunk count */
+static void stats_from_loads(const int64_t *S, const int64_t *R, int64_t wmax, int64_t chunks, int M, int N, int64_t *stats)
 {
-    const int64_t G = (int64_t)M * N;
-    for (int64_t i = 0; i < (int64_t)M * N; ++i) { Ssum[i] = 0; R[i] = 0; }
-    int64_t wmax = 0;
-    for (int k = 0; k < M; ++k) {
-        for (int64_t i = chunk_off[k]; i < chunk_off[k + 1]; ++i) {
-            const int64_t dst = (int64_t)flow[i] % G;
-            const int f = (int)(dst / N);
-            Ssum[(int64_t)k * N + rail[i]] += (int64_t)w[i];
-            R[(int64_t)f * N + rail[i]] += (int64_t)w[i];
-            if ((int64_t)w[i] > wmax) wmax = (int64_t)w[i];
-        }
-    }
     int64_t max_s = 0, max_r = 0, lb = wmax, total = 0, spread = 0;
     for (int k = 0; k < M; ++k) {
         int64_t out = 0, in = 0, smin = INT64_MAX, smax = 0;
         for (int n = 0; n < N; ++n) {
-            const int64_t s = Ssum[(int64_t)k * N + n], r = R[(int64_t)k * N + n];
+            const int64_t s = S[(int64_t)k * N + n], r = R[(int64_t)k * N + n];
             out += s; in += r;
             if (s > max_s) max_s = s;
             if (r > max_r) max_r = r;
@@ -328,8 +316,76 @@ void oracle_eval(const int64_t *chunk_off, const uint32_t *w, const uint32_t *fl
     stats[3] = lb;
     stats[4] = total;
     stats[5] = wmax;
-    stats[6] = chunk_off[M] - chunk_off[0];
+    stats[6] = chunks;
     stats[7] = spread;
+}
+
+void oracle_eval(const int64_t *chunk_off, const uint32_t *w, const uint32_t *flow,
+                 const uint8_t *rail, int M, int N, int64_t *Ssum, int64_t *R, int64_t *stats)
+{
+    const int64_t G = (int64_t)M * N;
+    for (int64_t i = 0; i < (int64_t)M * N; ++i) { Ssum[i] = 0; R[i] = 0; }
+    int64_t wmax = 0;
+    for (int k = 0; k < M; ++k) {
+        for (int64_t i = chunk_off[k]; i < chunk_off[k + 1]; ++i) {
+            const int64_t dst = (int64_t)flow[i] % G;
+            const int f = (int)(dst / N);
+            Ssum[(int64_t)k * N + rail[i]] += (int64_t)w[i];
+            R[(int64_t)f * N + rail[i]] += (int64_t)w[i];
+            if ((int64_t)w[i] > wmax) wmax = (int64_t)w[i];
+        }
+    }
+    stats_from_loads(Ssum, R, wmax, chunk_off[M] - chunk_off[0], M, N, stats);
+}
+
+/* ------------------------------------------------------------------------
+ * One whole traffic matrix taken one source node at a time, for matrices whose chunk records do not fit
+ * in host memory together: node k's flows are split (Section 5.1), sorted and allocated (Algorithm 2
+ * steps 2-3) by the functions above, its final LoadState is S[k][.], and the weight of each of its chunks
+ * is added to R[f][rail] of the chunk's destination node f (Section 4.1; rail n ends on NIC n of the
+ * destination, Theorem 3 proof); the records are then dropped.  Node k's receive contributions are kept
+ * apart until all nodes are done and added in node order.  Same S, R, stats and chunk_off[0..M] as
+ * chunk_sort_batch -> lpt_batch -> eval on the matrix.  Returns 0, or -1 when memory runs out.
+ * ---------------------------------------------------------------------- */
+int oracle_schedule_matrix_by_node(const int64_t *D1mat, int M, int N, int64_t C, int include_intra,
+                                   int64_t *chunk_off, int64_t *S, int64_t *R, int64_t *stats)
+{
+    const int64_t G = (int64_t)M * N;
+    int64_t *Rk = (int64_t *)calloc((size_t)M * (size_t)G, sizeof(int64_t));     /* [k][f][n] */
+    int64_t *cnt = (int64_t *)calloc((size_t)M, sizeof(int64_t));
+    int64_t *wmax_k = (int64_t *)calloc((size_t)M, sizeof(int64_t));
+    if (!Rk || !cnt || !wmax_k) { free(Rk); free(cnt); free(wmax_k); return -1; }
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(min : err)
+    for (int k = 0; k < M; ++k) {
+        const int64_t n = oracle_chunk_split(D1mat, M, N, C, include_intra, k, NULL, NULL);
+        cnt[k] = n;
+        uint32_t *w = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(n > 0 ? n : 1));
+        uint32_t *flow = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(n > 0 ? n : 1));
+        uint8_t *rail = (uint8_t *)malloc((size_t)(n > 0 ? n : 1));
+        if (!w || !flow || !rail || oracle_sort_desc(oracle_chunk_split(D1mat, M, N, C, include_intra, k, w, flow), w, flow, NULL)) {
+            err = -1;
+        } else {
+            oracle_lpt(n, w, N, rail, S + (int64_t)k * N);
+            for (int64_t i = 0; i < n; ++i) {
+                const int f = (int)(((int64_t)flow[i] % G) / N);
+                Rk[(int64_t)k * G + (int64_t)f * N + rail[i]] += (int64_t)w[i];
+                if ((int64_t)w[i] > wmax_k[k]) wmax_k[k] = (int64_t)w[i];
+            }
+        }
+        free(w); free(flow); free(rail);
+    }
+    int64_t wmax = 0;
+    chunk_off[0] = 0;
+    for (int64_t i = 0; i < G; ++i) R[i] = 0;
+    for (int k = 0; k < M; ++k) {
+        chunk_off[k + 1] = chunk_off[k] + cnt[k];
+        if (wmax_k[k] > wmax) wmax = wmax_k[k];
+        for (int64_t i = 0; i < G; ++i) R[i] += Rk[(int64_t)k * G + i];
+    }
+    if (!err) stats_from_loads(S, R, wmax, chunk_off[M], M, N, stats);
+    free(Rk); free(cnt); free(wmax_k);
+    return err;
 }
 
 /* ------------------------------------------------------------------------

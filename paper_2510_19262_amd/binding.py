@@ -19,7 +19,8 @@ _LIB_PATH = os.path.join(_HERE, "librailsched.so")
 _lib = None
 
 EXPORTS = (
-    "railsched_version", "railsched_strerror", "railsched_route_topk", "railsched_traffic_matrix",
+    "railsched_version", "railsched_strerror", "railsched_check_capacity", "railsched_route_topk",
+    "railsched_traffic_matrix_workspace_bytes", "railsched_traffic_matrix",
     "railsched_route_traffic_workspace_bytes", "railsched_route_traffic",
     "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray", "railsched_lpt_spray_chunkwise",
     "railsched_eval_workspace_bytes", "railsched_eval", "railsched_schedule_workspace_bytes", "railsched_schedule", "railsched_transpose_matrix", "railsched_assign_policy",
@@ -74,32 +75,35 @@ def load():
     P, I32, I64, SZ = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     TP = C.POINTER(_TopoStruct)
     lib.railsched_route_topk.argtypes = [P, I64, I32, I32, P, P]
-    lib.railsched_traffic_matrix.argtypes = [P, I32, I64, I32, P, I32, I32, I64, TP, P, P]
-    lib.railsched_route_traffic_workspace_bytes.argtypes = [I32, I64, I32, TP]
+    lib.railsched_check_capacity.argtypes = [P, I32, TP, I64, C.POINTER(C.c_int64), P]
+    lib.railsched_traffic_matrix_workspace_bytes.argtypes = [I32, I64, I32, TP]
+    lib.railsched_traffic_matrix_workspace_bytes.restype = SZ
+    lib.railsched_traffic_matrix.argtypes = [P, I32, I64, I32, P, I32, I32, I64, TP, P, P, SZ, P]
+    lib.railsched_route_traffic_workspace_bytes.argtypes = [I32, I64, I32, I32, TP]
     lib.railsched_route_traffic_workspace_bytes.restype = SZ
     lib.railsched_route_traffic.argtypes = [P, I32, I64, I32, I32, P, I32, I64, TP, P, P, P, SZ, P]
     lib.railsched_chunk_sort_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_chunk_sort_workspace_bytes.restype = SZ
     lib.railsched_chunk_sort.argtypes = [P, I32, TP, P, P, P, P, I64, P, SZ, P]
-    lib.railsched_lpt_spray.argtypes = [P, P, I32, TP, P, P, P]
-    lib.railsched_lpt_spray_chunkwise.argtypes = [P, P, I32, TP, P, P, P]
+    lib.railsched_lpt_spray.argtypes = [P, P, I32, TP, I64, P, P, P]
+    lib.railsched_lpt_spray_chunkwise.argtypes = [P, P, I32, TP, I64, P, P, P]
     lib.railsched_eval_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_eval_workspace_bytes.restype = SZ
-    lib.railsched_eval.argtypes = [P, P, P, P, P, I32, TP, P, P, P, SZ, P]
+    lib.railsched_eval.argtypes = [P, P, P, P, P, I32, TP, I64, P, P, P, SZ, P]
     lib.railsched_schedule_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_schedule_workspace_bytes.restype = SZ
     lib.railsched_schedule.argtypes = [P, I32, TP, P, P, P, P, I64, P, P, P, P, P, SZ, P]
     lib.railsched_transpose_matrix.argtypes = [P, I32, TP, P, P]
-    lib.railsched_assign_policy.argtypes = [I32, C.c_uint64, P, P, P, I32, TP, P, P, P]
+    lib.railsched_assign_policy.argtypes = [I32, C.c_uint64, P, P, P, I32, TP, I64, P, P, P]
     lib.railsched_port_round_robin_workspace_bytes.argtypes = [I32, TP, I64]
     lib.railsched_port_round_robin_workspace_bytes.restype = SZ
     lib.railsched_port_round_robin.argtypes = [P, P, I32, TP, I32, I64, P, P, SZ, P]
     lib.railsched_port_round_robin.restype = C.c_int
     lib.railsched_transpose_matrix.restype = C.c_int
     lib.railsched_assign_policy.restype = C.c_int
-    for fn in ("railsched_route_topk", "railsched_traffic_matrix",
-    "railsched_route_traffic_workspace_bytes", "railsched_route_traffic", "railsched_chunk_sort", "railsched_lpt_spray",
-               "railsched_lpt_spray_chunkwise", "railsched_eval"):
+    for fn in ("railsched_check_capacity", "railsched_route_topk", "railsched_traffic_matrix", "railsched_route_traffic",
+               "railsched_chunk_sort", "railsched_lpt_spray", "railsched_lpt_spray_chunkwise", "railsched_eval",
+               "railsched_schedule"):
         getattr(lib, fn).restype = C.c_int
     _lib = lib
     return lib
@@ -140,6 +144,20 @@ def _ws(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+def check_capacity(chunk_off: torch.Tensor, batch: int, topo: Topo, capacity: int) -> int:
+    """Waits for the current stream, returns the chunk count; raises RailschedError(RAILSCHED_ERR_CAPACITY) if it
+    exceeds `capacity` (the one synchronising call of the library)."""
+    _dev(chunk_off, torch.int64, "chunk_off")
+    total = C.c_int64(0)
+    t = topo.c()
+    rc = load().railsched_check_capacity(_ptr(chunk_off), batch, C.byref(t), capacity, C.byref(total), _stream())
+    if rc != 0:
+        err = RailschedError(rc, "railsched_check_capacity")
+        err.total = int(total.value)
+        raise err
+    return int(total.value)
+
+
 # ---------------------------------------------------------------------------------- stage 1
 def route_topk(logits: torch.Tensor, k: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """[rows][E] fp32 -> [rows][k] int32 indices of the k largest logits, lowest index on ties."""
@@ -153,8 +171,14 @@ def route_topk(logits: torch.Tensor, k: int, out: Optional[torch.Tensor] = None)
 
 
 # ---------------------------------------------------------------------------------- stage 2
+def traffic_matrix_workspace_bytes(batch: int, tokens_per_gpu: int, k: int, topo: Topo) -> int:
+    t = topo.c()
+    return int(load().railsched_traffic_matrix_workspace_bytes(batch, tokens_per_gpu, k, C.byref(t)))
+
+
 def traffic_matrix(topk_idx: torch.Tensor, batch: int, tokens_per_gpu: int, expert_gpu: torch.Tensor,
-                   payload_bytes: int, topo: Topo, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                   payload_bytes: int, topo: Topo, out: Optional[torch.Tensor] = None,
+                   ws: Optional[torch.Tensor] = None) -> torch.Tensor:
     """top-k indices + expert placement -> D1 [batch][G][G] int64 bytes."""
     _dev(topk_idx, torch.int32, "topk_idx")
     _dev(expert_gpu, torch.int32, "expert_gpu")
@@ -166,15 +190,18 @@ def traffic_matrix(topk_idx: torch.Tensor, batch: int, tokens_per_gpu: int, expe
     if out is None:
         out = torch.empty((batch, G, G), dtype=torch.int64, device=topk_idx.device)
     _dev(out, torch.int64, "out")
+    if ws is None:
+        ws = _ws(traffic_matrix_workspace_bytes(batch, tokens_per_gpu, k, topo), topk_idx.device)
     t = topo.c()
     _check(load().railsched_traffic_matrix(_ptr(topk_idx), batch, tokens_per_gpu, k, _ptr(expert_gpu), E, R,
-                                           payload_bytes, C.byref(t), _ptr(out), _stream()), "railsched_traffic_matrix")
+                                           payload_bytes, C.byref(t), _ptr(out), _ptr(ws), ws.numel(), _stream()),
+           "railsched_traffic_matrix")
     return out
 
 
-def route_traffic_workspace_bytes(batch: int, tokens_per_gpu: int, E: int, topo: Topo) -> int:
+def route_traffic_workspace_bytes(batch: int, tokens_per_gpu: int, E: int, k: int, topo: Topo) -> int:
     t = topo.c()
-    return int(load().railsched_route_traffic_workspace_bytes(batch, tokens_per_gpu, E, C.byref(t)))
+    return int(load().railsched_route_traffic_workspace_bytes(batch, tokens_per_gpu, E, k, C.byref(t)))
 
 
 def route_traffic(logits: torch.Tensor, k: int, batch: int, tokens_per_gpu: int, expert_gpu: torch.Tensor,
@@ -199,7 +226,7 @@ def route_traffic(logits: torch.Tensor, k: int, batch: int, tokens_per_gpu: int,
         _dev(idx, torch.int32, "topk_idx")
     _dev(D1, torch.int64, "D1")
     if ws is None:
-        ws = _ws(route_traffic_workspace_bytes(batch, tokens_per_gpu, E, topo), logits.device)
+        ws = _ws(route_traffic_workspace_bytes(batch, tokens_per_gpu, E, k, topo), logits.device)
     t = topo.c()
     _check(load().railsched_route_traffic(_ptr(logits), batch, tokens_per_gpu, E, k, _ptr(expert_gpu), R, payload_bytes,
                                           C.byref(t), None if idx is None else _ptr(idx), _ptr(D1), _ptr(ws), ws.numel(),
@@ -232,6 +259,12 @@ def chunk_count(D1: torch.Tensor, topo: Topo, ws: Optional[torch.Tensor] = None)
     return off
 
 
+def chunk_total(D1: torch.Tensor, topo: Topo, ws: Optional[torch.Tensor] = None) -> int:
+    """Count query followed by the one synchronising call: the number of chunks stage 3 will produce for D1."""
+    off = chunk_count(D1, topo, ws)
+    return check_capacity(off, D1.shape[0], topo, (1 << 62))
+
+
 def chunk_sort(D1: torch.Tensor, topo: Topo, want_perm: bool = True, capacity: Optional[int] = None,
                out=None, ws: Optional[torch.Tensor] = None):
     """D1 -> (chunk_off, chunk_w, chunk_flow, perm|None), every instance sorted by descending weight.
@@ -247,7 +280,7 @@ def chunk_sort(D1: torch.Tensor, topo: Topo, want_perm: bool = True, capacity: O
     if ws is None:
         ws = _ws(chunk_sort_workspace_bytes(batch, topo), dev)
     if capacity is None:
-        capacity = int(chunk_count(D1, topo, ws)[-1].item())
+        capacity = chunk_total(D1, topo, ws)
     if out is None:
         off = torch.empty(batch * topo.nodes + 1, dtype=torch.int64, device=dev)
         w = torch.empty(max(capacity, 1), dtype=torch.int32, device=dev)
@@ -262,28 +295,37 @@ def chunk_sort(D1: torch.Tensor, topo: Topo, want_perm: bool = True, capacity: O
 
 
 # ---------------------------------------------------------------------------------- stage 4
-def lpt_spray(chunk_off: torch.Tensor, chunk_w: torch.Tensor, batch: int, topo: Topo, out=None, chunkwise: bool = False):
-    """Greedy least-loaded-rail assignment per instance -> (rail uint8 [chunks], S int64 [batch][M][N]).
-    chunkwise=True calls railsched_lpt_spray_chunkwise (same result, no closed-form periods)."""
+def lpt_spray(chunk_off: torch.Tensor, chunk_w: torch.Tensor, batch: int, topo: Topo, out=None, chunkwise: bool = False,
+              capacity: Optional[int] = None):
+    """Greedy least-loaded-rail assignment per instance -> (rail uint8 [capacity], S int64 [batch][M][N]).
+    chunkwise=True calls railsched_lpt_spray_chunkwise (same result, no closed-form periods).
+    capacity = records chunk_w and rail hold (default: the length of chunk_w)."""
     _dev(chunk_off, torch.int64, "chunk_off")
     if chunk_w.dtype not in (torch.int32, torch.uint32):
         raise ValueError("chunk_w must be a 32-bit integer tensor")
+    if capacity is None:
+        capacity = chunk_w.numel()
     if out is None:
-        rail = torch.empty(max(chunk_w.numel(), 1), dtype=torch.uint8, device=chunk_off.device)
+        rail = torch.empty(max(capacity, 1), dtype=torch.uint8, device=chunk_off.device)
         S = torch.empty((batch, topo.nodes, topo.rails), dtype=torch.int64, device=chunk_off.device)
     else:
         rail, S = out
+    if min(chunk_w.numel(), rail.numel()) < capacity:
+        raise ValueError("chunk_w and rail must hold `capacity` records")
     t = topo.c()
     fn = load().railsched_lpt_spray_chunkwise if chunkwise else load().railsched_lpt_spray
-    _check(fn(_ptr(chunk_off), _ptr(chunk_w), batch, C.byref(t), _ptr(rail), _ptr(S), _stream()), "railsched_lpt_spray")
+    _check(fn(_ptr(chunk_off), _ptr(chunk_w), batch, C.byref(t), capacity, _ptr(rail), _ptr(S), _stream()), "railsched_lpt_spray")
     return rail, S
 
 
 # ---------------------------------------------------------------------------------- stage 5
 def eval(chunk_off, chunk_w, chunk_flow, rail, S, batch: int, topo: Topo, out=None,  # noqa: A001
-         ws: Optional[torch.Tensor] = None):
-    """Receive loads R [batch][M][N] and stats [batch][8] (see include/railsched.h)."""
+         ws: Optional[torch.Tensor] = None, capacity: Optional[int] = None):
+    """Receive loads R [batch][M][N] and stats [batch][8] (see include/railsched.h).
+    capacity = records the per-chunk arrays hold (default: the shortest of them)."""
     dev = chunk_off.device
+    if capacity is None:
+        capacity = min(chunk_w.numel(), chunk_flow.numel(), rail.numel())
     if out is None:
         R = torch.empty((batch, topo.nodes, topo.rails), dtype=torch.int64, device=dev)
         stats = torch.empty((batch, 8), dtype=torch.int64, device=dev)
@@ -293,7 +335,7 @@ def eval(chunk_off, chunk_w, chunk_flow, rail, S, batch: int, topo: Topo, out=No
         ws = _ws(eval_workspace_bytes(batch, topo), dev)
     t = topo.c()
     _check(load().railsched_eval(_ptr(chunk_off), _ptr(chunk_w), _ptr(chunk_flow), _ptr(rail), _ptr(S), batch,
-                                 C.byref(t), _ptr(R), _ptr(stats), _ptr(ws), ws.numel(), _stream()), "railsched_eval")
+                                 C.byref(t), capacity, _ptr(R), _ptr(stats), _ptr(ws), ws.numel(), _stream()), "railsched_eval")
     return R, stats
 
 
@@ -313,17 +355,22 @@ def transpose_matrix(D1: torch.Tensor, topo: Topo, out: Optional[torch.Tensor] =
     return out
 
 
-def assign_policy(policy, seed: int, chunk_off, chunk_w, chunk_flow, batch: int, topo: Topo, out=None):
+def assign_policy(policy, seed: int, chunk_off, chunk_w, chunk_flow, batch: int, topo: Topo, out=None,
+                  capacity: Optional[int] = None):
     """Rails under a comparison scheme ("nic_direct", "flow_hash", "random_spray", "round_robin") -> (rail, S)."""
+    if capacity is None:
+        capacity = min(chunk_w.numel(), chunk_flow.numel())
     if out is None:
-        rail = torch.empty(max(chunk_w.numel(), 1), dtype=torch.uint8, device=chunk_off.device)
+        rail = torch.empty(max(capacity, 1), dtype=torch.uint8, device=chunk_off.device)
         S = torch.empty((batch, topo.nodes, topo.rails), dtype=torch.int64, device=chunk_off.device)
     else:
         rail, S = out
     t = topo.c()
     pol = POLICIES[policy] if isinstance(policy, str) else int(policy)
+    if rail.numel() < capacity:
+        raise ValueError("rail must hold `capacity` records")
     _check(load().railsched_assign_policy(pol, seed, _ptr(chunk_off), _ptr(chunk_w), _ptr(chunk_flow), batch, C.byref(t),
-                                          _ptr(rail), _ptr(S), _stream()), "railsched_assign_policy")
+                                          capacity, _ptr(rail), _ptr(S), _stream()), "railsched_assign_policy")
     return rail, S
 
 
@@ -375,10 +422,14 @@ class Plan:
         self.ws_sort = _ws(chunk_sort_workspace_bytes(batch, topo), device)
         self.ws_eval = _ws(eval_workspace_bytes(batch, topo), device)
         self.ws_sched = _ws(schedule_workspace_bytes(batch, topo), device)
+        self.ws_tm = None
 
     def route(self, logits, tokens_per_gpu, expert_gpu, payload_bytes):
-        route_topk(logits, self.topk_idx.shape[1], out=self.topk_idx)
-        traffic_matrix(self.topk_idx, self.batch, tokens_per_gpu, expert_gpu, payload_bytes, self.topo, out=self.D1)
+        k = self.topk_idx.shape[1]
+        if self.ws_tm is None:
+            self.ws_tm = _ws(traffic_matrix_workspace_bytes(self.batch, tokens_per_gpu, k, self.topo), logits.device)
+        route_topk(logits, k, out=self.topk_idx)
+        traffic_matrix(self.topk_idx, self.batch, tokens_per_gpu, expert_gpu, payload_bytes, self.topo, out=self.D1, ws=self.ws_tm)
         return self.D1
 
     def schedule_one_call(self, D1=None):
@@ -389,12 +440,14 @@ class Plan:
         return self.stats
 
     def schedule(self, D1=None):
+        """Stages 3-5 through the three calls; like schedule_one_call, fills S, R and stats with -1 (and touches no
+        per-chunk array) if the batch yields more chunks than the plan's capacity."""
         D1 = self.D1 if D1 is None else D1
         chunk_sort(D1, self.topo, capacity=self.capacity,
                    out=(self.chunk_off, self.chunk_w, self.chunk_flow, self.perm), ws=self.ws_sort)
-        lpt_spray(self.chunk_off, self.chunk_w, self.batch, self.topo, out=(self.rail, self.S))
+        lpt_spray(self.chunk_off, self.chunk_w, self.batch, self.topo, out=(self.rail, self.S), capacity=self.capacity)
         eval(self.chunk_off, self.chunk_w, self.chunk_flow, self.rail, self.S, self.batch, self.topo,
-             out=(self.R, self.stats), ws=self.ws_eval)
+             out=(self.R, self.stats), ws=self.ws_eval, capacity=self.capacity)
         return self.stats
 
 

@@ -21,6 +21,7 @@ __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
     // the odd stride puts a bin's copies in different banks.
     extern __shared__ unsigned long long ev_all[];
     __shared__ unsigned ev_wmax;
+    if (a.chunk_off[a.n_inst] > a.capacity) return;                     // the record arrays hold nothing
     const int b = blockIdx.y, t = blockIdx.x;
     const int stride = a.G + 1;
     for (int i = threadIdx.x; i < stride * a.copies; i += kEvThreads) ev_all[i] = 0;
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(kEvThreads) void eval_partial_kernel(EvArgs a)
 __global__ __launch_bounds__(256) void eval_sum_kernel(EvArgs a)
 {
     __shared__ int64_t part[4][64];
+    if (a.chunk_off[a.n_inst] > a.capacity) return;
     const int b = blockIdx.y, base = blockIdx.x * 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t *slots = a.partial + (int64_t)b * a.slices * (a.G + 1);
@@ -109,6 +111,11 @@ __global__ __launch_bounds__(THREADS) void eval_reduce_kernel(EvArgs a)
     const int64_t *slots = a.partial + (int64_t)b * a.slices * (a.G + 1);
     int64_t *Rb = a.R + (int64_t)b * a.G;
     const int64_t *Sb = a.S + (int64_t)b * a.G;
+    if (a.chunk_off[a.n_inst] > a.capacity) {         // more chunks than the record arrays hold: nothing was read, say so
+        for (int i = threadIdx.x; i < a.G; i += THREADS) Rb[i] = -1;
+        if (threadIdx.x < 8) a.stats[(int64_t)b * 8 + threadIdx.x] = -1;
+        return;
+    }
 
     int width = 64;                                   // lanes per slice row: 64, or the power of two >= G
     while (width / 2 >= a.G) width /= 2;
@@ -222,14 +229,14 @@ extern "C" size_t railsched_eval_workspace_bytes(int32_t batch, const railsched_
 
 extern "C" int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w, const uint32_t *chunk_flow,
                               const uint8_t *rail, const int64_t *S, int32_t batch, const railsched_topo_t *h_topo,
-                              int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream)
+                              int64_t capacity, int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream)
 {
     using namespace rs;
     if (int rc = check_topo(h_topo)) return rc;
-    if (batch < 0) return RAILSCHED_ERR_INVALID_ARG;
+    if (batch < 0 || capacity < 0) return RAILSCHED_ERR_INVALID_ARG;
     if (batch > 65535) return RAILSCHED_ERR_UNSUPPORTED;
     if (batch == 0) return RAILSCHED_OK;
-    if (!chunk_off || !S || !R || !stats) return RAILSCHED_ERR_NULL_PTR;
+    if (!chunk_off || !S || !R || !stats || (capacity > 0 && (!chunk_w || !chunk_flow || !rail))) return RAILSCHED_ERR_NULL_PTR;
     if (!ws || ws_bytes < railsched_eval_workspace_bytes(batch, h_topo) || reinterpret_cast<uintptr_t>(ws) % 256)
         return RAILSCHED_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -238,6 +245,7 @@ extern "C" int railsched_eval(const int64_t *chunk_off, const uint32_t *chunk_w,
     a.chunk_off = chunk_off; a.chunk_w = chunk_w; a.chunk_flow = chunk_flow; a.rail = rail; a.S = S;
     a.R = R; a.stats = stats; a.partial = static_cast<int64_t *>(ws);
     a.M = h_topo->nodes; a.N = h_topo->rails; a.G = a.M * a.N; a.slices = eval_slices(batch);
+    a.capacity = capacity; a.n_inst = batch * a.M;
     a.nshift = is_pow2(a.N) ? ilog2(a.N) : -1;
     a.gmask = is_pow2(a.G) ? a.G - 1 : -1;
     a.wide_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(chunk_flow) % 16 == 0 &&

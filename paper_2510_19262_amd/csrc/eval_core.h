@@ -19,6 +19,8 @@ struct EvArgs {
     int32_t nshift, gmask;   // >= 0 when N / G are powers of two
     int32_t wide_ok;         // record arrays aligned for 16-byte (weights, flows) and 4-byte (rails) loads
     int32_t copies;          // LDS copies of the receive bins (power of two); lanes that would add to one bin use different ones
+    int64_t capacity;        // records the per-chunk arrays hold; more chunks than that: R and stats become -1
+    int32_t n_inst;          // batch * M
 };
 
 __device__ __forceinline__ int dst_node(const EvArgs &a, uint32_t flow)

@@ -45,6 +45,7 @@ struct PolArgs {
     int32_t n_inst, N, G, NF, policy;
     int32_t nmask, gshift;          // >= 0 when N / G are powers of two
     int32_t wide_ok;
+    int64_t capacity;               // records the per-chunk arrays hold
 };
 
 __device__ __forceinline__ uint64_t mix64(uint64_t z)                   // splitmix64 finaliser
@@ -70,9 +71,12 @@ __device__ __forceinline__ uint32_t policy_rail(const PolArgs &a, int64_t inst, 
     }
 }
 
-__global__ void fill_zero_kernel(int64_t *p, int64_t n)
+// S = 0 before the sums; -1 throughout when there are more chunks than the record arrays hold (the policy kernel
+// then touches nothing)
+__global__ void policy_init_kernel(PolArgs a, int64_t n)
 {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+    const int64_t v = a.chunk_off[a.n_inst] > a.capacity ? -1 : 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) a.S[i] = v;
 }
 
 // Streaming over all chunk positions, four per thread at multiples of four.  Send loads go to LDS bins
@@ -83,6 +87,7 @@ __global__ __launch_bounds__(kPolThreads) void policy_kernel(PolArgs a)
     __shared__ int64_t s_off[kPolStage + 1];
     __shared__ unsigned long long bins[kPolSlots][kMaxRails];
     const int64_t total = a.chunk_off[a.n_inst];
+    if (total > a.capacity) return;
     for (int64_t t0 = (int64_t)blockIdx.x * kPolTile; t0 < total; t0 += (int64_t)gridDim.x * kPolTile) {
         const int64_t t1 = t0 + kPolTile < total ? t0 + kPolTile : total;
         const int inst_lo = wave_last_le<int64_t>(a.chunk_off, a.n_inst, t0);
@@ -164,6 +169,7 @@ struct PortArgs {
     int64_t *tile_off;          // [n_inst + 1]
     uint32_t *cnt;              // [tiles][N]: counts, then exclusive prefixes inside the instance
     int64_t max_tiles;
+    int64_t capacity;           // records rail and port hold
     int32_t n_inst, N, P, pmask, rail_bits;
 };
 
@@ -199,6 +205,7 @@ __global__ __launch_bounds__(64 * kPortWaves) void port_tile_kernel(PortArgs a)
     __shared__ unsigned run[kPortWaves][kMaxRails];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const unsigned long long lt = (1ull << lane) - 1ull;
+    if (a.chunk_off[a.n_inst] > a.capacity) return;                 // more chunks than rail and port hold: touch neither
     int64_t n_tiles = a.tile_off[a.n_inst];
     if (n_tiles > a.max_tiles) n_tiles = a.max_tiles;               // workspace sized for fewer chunks: never write past it
     unsigned *mine = run[wv];
@@ -283,17 +290,18 @@ extern "C" int railsched_transpose_matrix(const int64_t *D1, int32_t batch, cons
 
 extern "C" int railsched_assign_policy(int32_t policy, uint64_t seed, const int64_t *chunk_off, const uint32_t *chunk_w,
                                        const uint32_t *chunk_flow, int32_t batch, const railsched_topo_t *h_topo,
-                                       uint8_t *rail, int64_t *S, void *stream)
+                                       int64_t capacity, uint8_t *rail, int64_t *S, void *stream)
 {
     using namespace rs;
     if (int rc = check_topo(h_topo)) return rc;
-    if (batch < 0 || policy < 0 || policy > 3) return RAILSCHED_ERR_INVALID_ARG;
+    if (batch < 0 || policy < 0 || policy > 3 || capacity < 0) return RAILSCHED_ERR_INVALID_ARG;
     const int64_t n_inst = (int64_t)batch * h_topo->nodes;
     if (n_inst > 0x7FFFFFFFll / 64) return RAILSCHED_ERR_UNSUPPORTED;
     if (n_inst == 0) return RAILSCHED_OK;
-    if (!chunk_off || !S) return RAILSCHED_ERR_NULL_PTR;
+    if (!chunk_off || !S || (capacity > 0 && (!chunk_w || !chunk_flow || !rail))) return RAILSCHED_ERR_NULL_PTR;
     hipStream_t st = static_cast<hipStream_t>(stream);
     PolArgs a;
+    a.capacity = capacity;
     a.chunk_off = chunk_off; a.chunk_w = chunk_w; a.chunk_flow = chunk_flow; a.rail = rail; a.S = S; a.seed = seed;
     a.n_inst = (int32_t)n_inst; a.N = h_topo->rails; a.G = h_topo->nodes * h_topo->rails; a.NF = a.N * a.G; a.policy = policy;
     a.nmask = is_pow2(a.N) ? a.N - 1 : -1;
@@ -301,7 +309,7 @@ extern "C" int railsched_assign_policy(int32_t policy, uint64_t seed, const int6
     a.wide_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(chunk_flow) % 16 == 0 &&
                  reinterpret_cast<uintptr_t>(rail) % 4 == 0) ? 1 : 0;
     const int64_t n = n_inst * a.N;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256 > 1024 ? 1024 : (n + 255) / 256)), dim3(256), 0, st, S, n);
+    hipLaunchKernelGGL(policy_init_kernel, dim3((unsigned)((n + 255) / 256 > 1024 ? 1024 : (n + 255) / 256)), dim3(256), 0, st, a, n);
     if (int rc = launch_status()) return rc;
     hipLaunchKernelGGL(policy_kernel, dim3(kPolBlocks), dim3(kPolThreads), 0, st, a);
     return launch_status();
@@ -338,7 +346,7 @@ extern "C" int railsched_port_round_robin(const int64_t *chunk_off, const uint8_
     a.chunk_off = chunk_off; a.rail = rail; a.port = port;
     a.tile_off = reinterpret_cast<int64_t *>(static_cast<char *>(ws) + off[0]);
     a.cnt = reinterpret_cast<uint32_t *>(static_cast<char *>(ws) + off[1]);
-    a.max_tiles = max_tiles;
+    a.max_tiles = max_tiles; a.capacity = capacity;
     a.n_inst = (int32_t)n_inst; a.N = h_topo->rails; a.P = ports; a.pmask = is_pow2(ports) ? ports - 1 : -1;
     a.rail_bits = a.N > 1 ? ilog2(a.N - 1) + 1 : 0;
     hipLaunchKernelGGL(port_tiles_kernel, dim3(1), dim3(1024), 0, st, a);

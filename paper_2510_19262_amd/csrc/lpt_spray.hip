@@ -56,11 +56,12 @@ __global__ void lpt_prefix_init_kernel(int64_t *run_end, int n_inst, int N)
 __global__ __launch_bounds__(kPfThreads) void lpt_prefix_kernel(const int64_t *__restrict__ chunk_off,
                                                                 const uint32_t *__restrict__ chunk_w, int n_inst, int N,
                                                                 int nmask, uint8_t *__restrict__ rail, int64_t *run_end,
-                                                                int wide_ok)
+                                                                int wide_ok, int64_t capacity)
 {
     __shared__ int64_t s_off[kPfStage + 1];
     __shared__ uint32_t s_w0[kPfStage];
     const int64_t total = chunk_off[n_inst];
+    if (total > capacity) return;                   // more chunks than the arrays hold: the serial kernel marks S
     // tile: the share of one workgroup when the whole grid takes one tile each, in whole passes, at most kPfTile
     int64_t tile = ((total + gridDim.x - 1) / gridDim.x + kPfPass - 1) / kPfPass * kPfPass;
     tile = tile < kPfPass ? kPfPass : tile > kPfTile ? kPfTile : tile;
@@ -267,7 +268,6 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
                                                                     uint8_t *__restrict__ rail, int64_t *__restrict__ S_out,
                                                                     int64_t capacity)
 {
-    if (chunk_off[n_inst] > capacity) return;       // the record arrays were too small and hold nothing
     constexpr int S = GroupBits<GW>::S;
     constexpr int IPW = 64 / GW;                    // instances per wavefront
     constexpr int STEP = GW <= 4 ? kBatch / 2 : kBatch;   // chunks per instance and period (GW = 4 holds 8 weights per lane and period already)
@@ -282,6 +282,10 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
     const int inst = wave * IPW + lane / GW;
     const bool has_inst = inst < n_inst;
     const bool has_rail = has_inst && (int)q < N;
+    if (chunk_off[n_inst] > capacity) {             // more chunks than the record arrays hold: touch none, mark the loads
+        if (has_rail) S_out[(int64_t)inst * N + q] = -1;
+        return;
+    }
     int64_t beg = has_inst ? chunk_off[inst] : 0;
     int64_t len = has_inst ? chunk_off[inst + 1] - beg : 0;
     unsigned long long base = 0;
@@ -411,9 +415,12 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t 
                                                                   uint8_t *__restrict__ rail, int64_t *__restrict__ S_out,
                                                                   int64_t capacity)
 {
-    if (chunk_off[n_inst] > capacity) return;       // the record arrays were too small and hold nothing
     const int inst = (int)((blockIdx.x * (unsigned)kLptWaves) + (threadIdx.x >> 6));
     if (inst >= n_inst) return;                     // whole wavefront leaves; nothing below synchronises across waves
+    if (chunk_off[n_inst] > capacity) {             // more chunks than the record arrays hold: touch none, mark the loads
+        if ((int)(threadIdx.x & 63) < N) S_out[(int64_t)inst * N + (threadIdx.x & 63)] = -1;
+        return;
+    }
     int64_t beg = chunk_off[inst];
     int64_t len = chunk_off[inst + 1] - beg;
     unsigned long long base = 0;
@@ -457,17 +464,17 @@ static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, 
 
 template <int GW, bool RUNS>
 static int launch_lpt(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
-                      int64_t *S, hipStream_t st)
+                      int64_t *S, int64_t capacity, hipStream_t st)
 {
     if (RUNS) {
         hipLaunchKernelGGL(lpt_prefix_init_kernel, dim3((unsigned)((n_inst + 255) / 256 > 1024 ? 1024 : (n_inst + 255) / 256)), dim3(256),
                            0, st, S, (int)n_inst, N);
         const int wide_ok = (reinterpret_cast<uintptr_t>(chunk_w) % 16 == 0 && reinterpret_cast<uintptr_t>(rail) % 4 == 0) ? 1 : 0;
         hipLaunchKernelGGL(lpt_prefix_kernel, dim3(kPfBlocks), dim3(kPfThreads), 0, st, chunk_off, chunk_w, (int)n_inst, N,
-                           is_pow2(N) ? N - 1 : -1, rail, S, wide_ok);
+                           is_pow2(N) ? N - 1 : -1, rail, S, wide_ok, capacity);
         if (int rc = launch_status()) return rc;
     }
-    return launch_lpt_serial<GW, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, INT64_MAX, st);
+    return launch_lpt_serial<GW, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
 }
 
 // for the one-call scheduler, which knows every leading run from stage 3 and has written its rails
@@ -483,33 +490,34 @@ int lpt_serial_after_leading_runs(const int64_t *chunk_off, const uint32_t *chun
 
 template <bool RUNS>
 static int lpt_entry(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch, const railsched_topo_t *h_topo,
-                     uint8_t *rail, int64_t *S, void *stream)
+                     int64_t capacity, uint8_t *rail, int64_t *S, void *stream)
 {
     if (int rc = check_topo(h_topo)) return rc;
-    if (batch < 0) return RAILSCHED_ERR_INVALID_ARG;
+    if (batch < 0 || capacity < 0) return RAILSCHED_ERR_INVALID_ARG;
     const int64_t n_inst = (int64_t)batch * h_topo->nodes;
     if (n_inst > 0x7FFFFFFFll / 64) return RAILSCHED_ERR_UNSUPPORTED;
     if (n_inst == 0) return RAILSCHED_OK;
-    if (!chunk_off || !S) return RAILSCHED_ERR_NULL_PTR;   // chunk_w / rail may be NULL only when there are no chunks
+    if (!chunk_off || !S || (capacity > 0 && (!chunk_w || !rail))) return RAILSCHED_ERR_NULL_PTR;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int N = h_topo->rails;
-    if (N <= 4) return launch_lpt<4, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
-    if (N <= 8) return launch_lpt<8, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
-    if (N <= 16) return launch_lpt<16, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
-    if (N <= 32) return launch_lpt<32, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
-    return launch_lpt<64, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, st);
+    if (N <= 4) return launch_lpt<4, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    if (N <= 8) return launch_lpt<8, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    if (N <= 16) return launch_lpt<16, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    if (N <= 32) return launch_lpt<32, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    return launch_lpt<64, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
 }
 
 }  // namespace rs
 
 extern "C" int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
-                                   const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream)
+                                   const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S, void *stream)
 {
-    return rs::lpt_entry<true>(chunk_off, chunk_w, batch, h_topo, rail, S, stream);
+    return rs::lpt_entry<true>(chunk_off, chunk_w, batch, h_topo, capacity, rail, S, stream);
 }
 
 extern "C" int railsched_lpt_spray_chunkwise(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
-                                             const railsched_topo_t *h_topo, uint8_t *rail, int64_t *S, void *stream)
+                                             const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S,
+                                             void *stream)
 {
-    return rs::lpt_entry<false>(chunk_off, chunk_w, batch, h_topo, rail, S, stream);
+    return rs::lpt_entry<false>(chunk_off, chunk_w, batch, h_topo, capacity, rail, S, stream);
 }

@@ -13,6 +13,7 @@
 // into many slices; each slice leaves its G counts in the workspace with plain stores and a second,
 // small kernel sums a pair's slices and scales by the payload.
 #include "common.h"
+#include "count_reduce.h"
 
 #include <cfloat>
 #include <climits>
@@ -62,6 +63,13 @@ __global__ __launch_bounds__(256) void rt_reduce_kernel(const uint32_t *__restri
         for (; p < splits; ++p) cnt += src[(int64_t)p * G];
         D1[i] = (int64_t)cnt * payload;
     }
+}
+
+int launch_count_reduce(const uint32_t *partial, int64_t *D1, int64_t n, int G, int splits, int64_t payload, hipStream_t st)
+{
+    const int64_t blocks = (n + 255) / 256 > 65536 ? 65536 : (n + 255) / 256;
+    hipLaunchKernelGGL(rt_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, partial, D1, n, G, splits, payload);
+    return launch_status();
 }
 
 template <int VPL, bool VEC4>
@@ -212,14 +220,15 @@ static int64_t rt_splits(int64_t tokens_per_gpu, int64_t G, int64_t pairs)
 }
 }  // namespace rs
 
-extern "C" size_t railsched_route_traffic_workspace_bytes(int32_t batch, int64_t tokens_per_gpu, int32_t E,
+extern "C" size_t railsched_route_traffic_workspace_bytes(int32_t batch, int64_t tokens_per_gpu, int32_t E, int32_t k,
                                                           const railsched_topo_t *h_topo)
 {
     using namespace rs;
-    if (check_topo(h_topo) != RAILSCHED_OK || batch < 0 || tokens_per_gpu < 0 || E < 1) return 0;
+    if (check_topo(h_topo) != RAILSCHED_OK || batch < 0 || tokens_per_gpu < 0 || E < 1 || k < 1) return 0;
     const int64_t G = (int64_t)h_topo->nodes * h_topo->rails;
     const int64_t pairs = (int64_t)batch * G;
-    if (E > 8 || pairs == 0) return 256;
+    if (E > 8) return railsched_traffic_matrix_workspace_bytes(batch, tokens_per_gpu, k, h_topo);
+    if (pairs == 0) return 256;
     const int64_t splits = rt_splits(tokens_per_gpu, G, pairs);
     return splits > 1 ? align_up(sizeof(uint32_t) * (size_t)(pairs * splits * G), 256) : 256;
 }
@@ -244,7 +253,7 @@ extern "C" int railsched_route_traffic(const float *logits, int32_t batch, int64
         // a row spans several lanes: the two stages run one after the other through the index array
         if (!topk_idx && rows > 0) return RAILSCHED_ERR_NULL_PTR;
         if (int rc = railsched_route_topk(logits, rows, E, k, topk_idx, stream)) return rc;
-        return railsched_traffic_matrix(topk_idx, batch, tokens_per_gpu, k, expert_gpu, E, R, payload_bytes, h_topo, D1, stream);
+        return railsched_traffic_matrix(topk_idx, batch, tokens_per_gpu, k, expert_gpu, E, R, payload_bytes, h_topo, D1, ws, ws_bytes, stream);
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
 
@@ -269,11 +278,6 @@ extern "C" int railsched_route_traffic(const float *logits, int32_t batch, int64
     }
     const size_t lds = sizeof(unsigned) * (size_t)a.bin_stride * a.copies + (a.table_in_lds ? sizeof(int32_t) * (size_t)E * R : 0);
     if (int rc = E <= 4 ? launch_route_traffic<4>(a, pairs, lds, st) : launch_route_traffic<8>(a, pairs, lds, st)) return rc;
-    if (splits > 1) {
-        const int64_t n = pairs * G;
-        const int64_t blocks = (n + 255) / 256 > 65536 ? 65536 : (n + 255) / 256;
-        hipLaunchKernelGGL(rt_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a.partial, D1, n, (int)G, (int)splits, payload_bytes);
-        return launch_status();
-    }
+    if (splits > 1) return launch_count_reduce(a.partial, D1, pairs * G, (int)G, (int)splits, payload_bytes, st);
     return RAILSCHED_OK;
 }

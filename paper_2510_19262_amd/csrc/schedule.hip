@@ -106,7 +106,10 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
         a.chunk_off[inst] = out0;
         if (inst == a.n_inst - 1) a.chunk_off[a.n_inst] = total;
     }
-    if (total > a.capacity) return;                                      // record arrays too small: leave them alone
+    if (total > a.capacity) {                                            // record arrays too small: leave them alone, mark the loads
+        if (tid < N) x.S[(int64_t)inst * N + tid] = -1;
+        return;
+    }
 
     // leading run: the full chunks (weight C) up to a multiple of N go round robin from empty rails
     const uint32_t cw = (uint32_t)a.C;
@@ -328,6 +331,7 @@ extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsc
     e.R = R; e.stats = stats; e.partial = x.partial;
     e.M = (int32_t)M; e.N = (int32_t)N; e.G = (int32_t)G; e.slices = (int32_t)M;   // one slot per instance
     e.nshift = x.nshift; e.gmask = x.gmask; e.wide_ok = 0; e.copies = 1;
+    e.capacity = capacity; e.n_inst = (int32_t)n_inst;
 
     if (!small) {
         CsArgs a;

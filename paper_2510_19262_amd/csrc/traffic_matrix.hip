@@ -5,22 +5,23 @@
 // the expert placement table (staged in LDS) and counts hits in an LDS histogram private to the
 // workgroup: G 32-bit bins.  Counts become bytes (count * payload) only when the histogram is
 // flushed.  HBM traffic is the index stream once plus 8*G bytes per (b, s) pair.
+//
+// Short-lived workgroups stream best on this chip, so a pair's slots are cut into slices of a few thousand;
+// a slice leaves its G counts in the workspace with plain stores and the small reduction kernel shared with
+// the one-pass call sums a pair's slices and scales by the payload: no atomics outside LDS, nothing to zero.
 #include "common.h"
+#include "count_reduce.h"
 
 namespace rs {
 
 constexpr int kTmThreads = 256;
 constexpr int kTmTableMax = 8192;   // placement entries staged in LDS (32 KiB)
 
-__global__ void fill_zero_i64(int64_t *p, int64_t n)
-{
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
-}
-
 struct TmArgs {
     const int32_t *topk_idx;
     const int32_t *expert_gpu;
     int64_t *D1;
+    uint32_t *partial;       // [pairs][splits][G] counts when a pair has several slices
     int64_t slots_per_gpu;   // tokens_per_gpu * k
     int64_t payload;
     int32_t k, kshift;       // kshift >= 0 when k is a power of two
@@ -97,17 +98,43 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
     for (int i = threadIdx.x; i < a.G; i += kTmThreads) {
         unsigned cnt = 0;
         for (int c = 0; c < a.copies; ++c) cnt += all_bins[(size_t)c * a.bin_stride + i];
-        const int64_t bytes = (int64_t)cnt * a.payload;
-        if (a.splits == 1) dst[i] = bytes;                               // sole owner: plain store, zeros included
-        else if (bytes) atomicAdd(reinterpret_cast<unsigned long long *>(dst + i), (unsigned long long)bytes);
+        if (a.splits == 1) dst[i] = (int64_t)cnt * a.payload;           // sole owner of the pair
+        else a.partial[((int64_t)pair * a.splits + part) * a.G + i] = cnt;
     }
 }
 
 }  // namespace rs
 
+namespace rs {
+// slices per pair: a few thousand slots each, more for large G so that a slice's G counts stay a small share of
+// its index bytes
+static int64_t tm_splits(int64_t slots_per_gpu, int64_t G, int64_t pairs)
+{
+    const int64_t unit = (int64_t)kTmThreads * kTmUnroll * 4;            // slots one workgroup covers per step
+    int64_t slice = unit;
+    while (slice < 32 * G) slice += unit;
+    int64_t splits = (slots_per_gpu + slice - 1) / slice;
+    if (splits < 1) splits = 1;
+    while (splits > 1 && pairs * splits > 0x7FFFFFFFll) splits = (splits + 1) / 2;
+    return splits;
+}
+}  // namespace rs
+
+extern "C" size_t railsched_traffic_matrix_workspace_bytes(int32_t batch, int64_t tokens_per_gpu, int32_t k,
+                                                           const railsched_topo_t *h_topo)
+{
+    using namespace rs;
+    if (check_topo(h_topo) != RAILSCHED_OK || batch < 0 || tokens_per_gpu < 0 || k < 1) return 0;
+    const int64_t G = (int64_t)h_topo->nodes * h_topo->rails;
+    const int64_t pairs = (int64_t)batch * G;
+    if (pairs == 0 || tokens_per_gpu > (int64_t(1) << 31) / k) return 256;
+    const int64_t splits = tm_splits(tokens_per_gpu * k, G, pairs);
+    return splits > 1 ? align_up(sizeof(uint32_t) * (size_t)(pairs * splits * G), 256) : 256;
+}
+
 extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, int64_t tokens_per_gpu, int32_t k,
                                         const int32_t *expert_gpu, int32_t E, int32_t R, int64_t payload_bytes,
-                                        const railsched_topo_t *h_topo, int64_t *D1, void *stream)
+                                        const railsched_topo_t *h_topo, int64_t *D1, void *ws, size_t ws_bytes, void *stream)
 {
     using namespace rs;
     if (int rc = check_topo(h_topo)) return rc;
@@ -132,19 +159,14 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
     a.bin_stride = (int32_t)(a.copies > 1 ? (G | 1) : G);
     a.table_in_lds = ((int64_t)E * R <= kTmTableMax && 4 * (a.copies * (int64_t)a.bin_stride + (int64_t)E * R) <= 64 * 1024) ? 1 : 0;
 
-    // enough workgroups to cover the chip, but no slice shorter than 16 Ki slots
     const int64_t pairs = (int64_t)batch * G;
-    int64_t splits = (2048 + pairs - 1) / pairs;
-    const int64_t max_splits = (a.slots_per_gpu + 16383) / 16384;
-    if (splits > max_splits) splits = max_splits;
-    if (splits < 1) splits = 1;
-    a.splits = (int32_t)splits;
+    const int64_t splits = tm_splits(a.slots_per_gpu, G, pairs);
     if (pairs * splits > 0x7FFFFFFFll) return RAILSCHED_ERR_UNSUPPORTED;
-
+    a.splits = (int32_t)splits;
+    a.partial = static_cast<uint32_t *>(ws);
     if (splits > 1) {
-        const int64_t n = pairs * G;
-        hipLaunchKernelGGL(fill_zero_i64, dim3((unsigned)((n + 1023) / 1024 > 4096 ? 4096 : (n + 1023) / 1024)), dim3(256), 0, st, D1, n);
-        if (int rc = launch_status()) return rc;
+        const size_t need = sizeof(uint32_t) * (size_t)(pairs * splits * G);
+        if (!ws || ws_bytes < need || reinterpret_cast<uintptr_t>(ws) % 4 != 0) return RAILSCHED_ERR_WORKSPACE;
     }
     const size_t lds = sizeof(unsigned) * (size_t)a.bin_stride * a.copies + (a.table_in_lds ? sizeof(int32_t) * (size_t)E * R : 0);
     const dim3 grid((unsigned)(pairs * splits));
@@ -153,5 +175,7 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
     else if (fast) hipLaunchKernelGGL((traffic_matrix_kernel<true, false>), grid, dim3(kTmThreads), lds, st, a);
     else if (a.table_in_lds) hipLaunchKernelGGL((traffic_matrix_kernel<false, true>), grid, dim3(kTmThreads), lds, st, a);
     else hipLaunchKernelGGL((traffic_matrix_kernel<false, false>), grid, dim3(kTmThreads), lds, st, a);
-    return launch_status();
+    if (int rc = launch_status()) return rc;
+    if (splits > 1) return launch_count_reduce(a.partial, D1, pairs * G, (int)G, (int)splits, payload_bytes, st);
+    return RAILSCHED_OK;
 }

@@ -53,34 +53,56 @@ def test_topology_validation():
     lib = rs.load()
     for t, want in ((_topo(M=0), -1), (_topo(N=0), -1), (_topo(Cb=0), -1), (_topo(reserved=1), -1), (_topo(intra=2), -1),
                     (_topo(N=65), -3), (_topo(M=4096, N=8), -3), (_topo(Cb=1 << 32), -3)):
-        assert lib.railsched_lpt_spray(FAKE, FAKE, 1, C.byref(t), FAKE, FAKE, None) == want
+        assert lib.railsched_lpt_spray(FAKE, FAKE, 1, C.byref(t), 10, FAKE, FAKE, None) == want
         assert lib.railsched_chunk_sort_workspace_bytes(1, C.byref(t)) == 0
         assert lib.railsched_eval_workspace_bytes(1, C.byref(t)) == 0
-    assert lib.railsched_lpt_spray(FAKE, FAKE, 1, None, FAKE, FAKE, None) == -2
+    assert lib.railsched_lpt_spray(FAKE, FAKE, 1, None, 10, FAKE, FAKE, None) == -2
 
 
 def test_traffic_matrix_validation():
     lib = rs.load()
     t = _topo()
-    f = lib.railsched_traffic_matrix
-    assert f(FAKE, -1, 10, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, None) == -1
-    assert f(FAKE, 1, 10, 0, FAKE, 8, 2, 1024, C.byref(t), FAKE, None) == -1
-    assert f(FAKE, 1, 10, 2, FAKE, 8, 0, 1024, C.byref(t), FAKE, None) == -1
-    assert f(FAKE, 1, 10, 2, FAKE, 8, 2, -5, C.byref(t), FAKE, None) == -1
-    assert f(FAKE, 1, 1 << 31, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, None) == -3
-    assert f(FAKE, 1, 10, 2, None, 8, 2, 1024, C.byref(t), FAKE, None) == -2
-    assert f(FAKE, 1, 10, 2, FAKE, 8, 2, 1024, C.byref(t), None, None) == -2
-    assert f(FAKE, 0, 10, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, None) == 0
+    need = lib.railsched_traffic_matrix_workspace_bytes(1, 100_000, 2, C.byref(t))
+    assert need >= 4 * 16 * 16 * (200_000 // 8192) and need % 256 == 0                 # several slices per pair
+    assert lib.railsched_traffic_matrix_workspace_bytes(1, 10, 2, C.byref(t)) == 256     # one slice per pair: nothing needed
+    assert lib.railsched_traffic_matrix_workspace_bytes(-1, 10, 2, C.byref(t)) == 0
+    assert lib.railsched_traffic_matrix_workspace_bytes(1, 10, 0, C.byref(t)) == 0
+    f = lib.railsched_traffic_matrix   # (idx, batch, tokens_per_gpu, k, expert_gpu, E, R, payload, topo, D1, ws, ws_bytes, stream)
+    assert f(FAKE, -1, 10, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, FAKE, 256, None) == -1
+    assert f(FAKE, 1, 10, 0, FAKE, 8, 2, 1024, C.byref(t), FAKE, FAKE, 256, None) == -1
+    assert f(FAKE, 1, 10, 2, FAKE, 8, 0, 1024, C.byref(t), FAKE, FAKE, 256, None) == -1
+    assert f(FAKE, 1, 10, 2, FAKE, 8, 2, -5, C.byref(t), FAKE, FAKE, 256, None) == -1
+    assert f(FAKE, 1, 1 << 31, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, FAKE, 256, None) == -3
+    assert f(FAKE, 1, 10, 2, None, 8, 2, 1024, C.byref(t), FAKE, FAKE, 256, None) == -2
+    assert f(FAKE, 1, 10, 2, FAKE, 8, 2, 1024, C.byref(t), None, FAKE, 256, None) == -2
+    assert f(FAKE, 1, 100_000, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, None, need, None) == -5
+    assert f(FAKE, 1, 100_000, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, FAKE, need - 256, None) == -5
+    assert f(FAKE, 1, 100_000, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, P(0x1001), need, None) == -5
+    assert f(FAKE, 0, 10, 2, FAKE, 8, 2, 1024, C.byref(t), FAKE, FAKE, 256, None) == 0
+
+
+def test_check_capacity_validation():
+    lib = rs.load()
+    t = _topo()
+    total = C.c_int64(-7)
+    f = lib.railsched_check_capacity   # (chunk_off, batch, topo, capacity, h_total, stream)
+    assert f(None, 1, C.byref(t), 10, C.byref(total), None) == -2
+    assert f(FAKE, -1, C.byref(t), 10, C.byref(total), None) == -1
+    assert f(FAKE, 1, C.byref(t), -1, C.byref(total), None) == -1
+    assert f(FAKE, 1, None, 10, C.byref(total), None) == -2
+    assert total.value == -7                                              # untouched on an argument error
+    assert "chunks" in rs.strerror(-4)
 
 
 def test_route_traffic_validation():
     lib = rs.load()
     t = _topo()
-    need = lib.railsched_route_traffic_workspace_bytes(1, 10_000, 8, C.byref(t))
+    need = lib.railsched_route_traffic_workspace_bytes(1, 10_000, 8, 2, C.byref(t))
     assert need >= 4 * 16 * 16 * (10_000 // 4096) and need % 256 == 0
-    assert lib.railsched_route_traffic_workspace_bytes(1, 10, 8, C.byref(t)) == 256     # one slice per pair: nothing needed
-    assert lib.railsched_route_traffic_workspace_bytes(1, 10_000, 16, C.byref(t)) == 256
-    assert lib.railsched_route_traffic_workspace_bytes(-1, 10, 8, C.byref(t)) == 0
+    assert lib.railsched_route_traffic_workspace_bytes(1, 10, 8, 2, C.byref(t)) == 256     # one slice per pair: nothing needed
+    assert lib.railsched_route_traffic_workspace_bytes(1, 1_000, 16, 2, C.byref(t)) == 256
+    assert lib.railsched_route_traffic_workspace_bytes(-1, 10, 8, 2, C.byref(t)) == 0
+    assert lib.railsched_route_traffic_workspace_bytes(1, 10, 8, 0, C.byref(t)) == 0
     f = lib.railsched_route_traffic   # (logits, batch, tokens_per_gpu, E, k, expert_gpu, R, payload, topo, idx, D1, ws, ws_bytes, stream)
     assert f(FAKE, -1, 10, 8, 2, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == -1
     assert f(FAKE, 1, 10, 8, 9, FAKE, 2, 1024, C.byref(t), FAKE, FAKE, FAKE, need, None) == -1
@@ -118,13 +140,18 @@ def test_chunk_sort_and_eval_validation():
     ev = lib.railsched_eval
     need = lib.railsched_eval_workspace_bytes(2, C.byref(t))
     assert need > 0
-    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, -1, C.byref(t), FAKE, FAKE, FAKE, need, None) == -1
-    assert ev(FAKE, FAKE, FAKE, FAKE, None, 2, C.byref(t), FAKE, FAKE, FAKE, need, None) == -2
-    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 2, C.byref(t), None, FAKE, FAKE, need, None) == -2
-    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 2, C.byref(t), FAKE, FAKE, FAKE, need - 1, None) == -5
-    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 0, C.byref(t), FAKE, FAKE, FAKE, need, None) == 0
-    assert lib.railsched_lpt_spray(FAKE, FAKE, 0, C.byref(t), FAKE, FAKE, None) == 0
-    assert lib.railsched_lpt_spray(None, FAKE, 1, C.byref(t), FAKE, FAKE, None) == -2
+    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, -1, C.byref(t), 10, FAKE, FAKE, FAKE, need, None) == -1
+    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 2, C.byref(t), -1, FAKE, FAKE, FAKE, need, None) == -1
+    assert ev(FAKE, FAKE, FAKE, FAKE, None, 2, C.byref(t), 10, FAKE, FAKE, FAKE, need, None) == -2
+    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 2, C.byref(t), 10, None, FAKE, FAKE, need, None) == -2
+    assert ev(FAKE, FAKE, None, FAKE, FAKE, 2, C.byref(t), 10, FAKE, FAKE, FAKE, need, None) == -2
+    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 2, C.byref(t), 10, FAKE, FAKE, FAKE, need - 1, None) == -5
+    assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 0, C.byref(t), 10, FAKE, FAKE, FAKE, need, None) == 0
+    assert lib.railsched_lpt_spray(FAKE, FAKE, 0, C.byref(t), 10, FAKE, FAKE, None) == 0
+    assert lib.railsched_lpt_spray(None, FAKE, 1, C.byref(t), 10, FAKE, FAKE, None) == -2
+    assert lib.railsched_lpt_spray(FAKE, FAKE, 1, C.byref(t), -1, FAKE, FAKE, None) == -1
+    assert lib.railsched_lpt_spray(FAKE, None, 1, C.byref(t), 10, FAKE, FAKE, None) == -2     # records without arrays
+    assert lib.railsched_lpt_spray_chunkwise(FAKE, FAKE, 1, C.byref(t), 10, None, FAKE, None) == -2
 
 
 def test_extras_validation():
@@ -136,11 +163,12 @@ def test_extras_validation():
     assert tr(FAKE, 1, C.byref(t), FAKE, None) == -1           # in place is refused
     assert tr(FAKE, 0, C.byref(t), FAKE, None) == 0
     ap = lib.railsched_assign_policy
-    assert ap(4, 0, FAKE, FAKE, FAKE, 1, C.byref(t), FAKE, FAKE, None) == -1
-    assert ap(-1, 0, FAKE, FAKE, FAKE, 1, C.byref(t), FAKE, FAKE, None) == -1
-    assert ap(0, 0, None, FAKE, FAKE, 1, C.byref(t), FAKE, FAKE, None) == -2
-    assert ap(0, 0, FAKE, FAKE, FAKE, 1, C.byref(t), FAKE, None, None) == -2
-    assert ap(0, 0, FAKE, FAKE, FAKE, 0, C.byref(t), FAKE, FAKE, None) == 0
+    assert ap(4, 0, FAKE, FAKE, FAKE, 1, C.byref(t), 10, FAKE, FAKE, None) == -1
+    assert ap(-1, 0, FAKE, FAKE, FAKE, 1, C.byref(t), 10, FAKE, FAKE, None) == -1
+    assert ap(0, 0, FAKE, FAKE, FAKE, 1, C.byref(t), -1, FAKE, FAKE, None) == -1
+    assert ap(0, 0, None, FAKE, FAKE, 1, C.byref(t), 10, FAKE, FAKE, None) == -2
+    assert ap(0, 0, FAKE, FAKE, FAKE, 1, C.byref(t), 10, FAKE, None, None) == -2
+    assert ap(0, 0, FAKE, FAKE, FAKE, 0, C.byref(t), 10, FAKE, FAKE, None) == 0
 
 
 def test_port_round_robin_validation():

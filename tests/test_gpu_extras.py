@@ -205,7 +205,7 @@ def test_whole_path_replays_from_a_hip_graph(fused):
         cap = max(cap, int(rs.chunk_count(D, topo)[-1].item()))
     plan = rs.Plan(topo, B, cap, DEV, rows=rows, k=cfg.k)
 
-    ws_rt = torch.empty(rs.route_traffic_workspace_bytes(B, cfg.tokens_per_gpu, cfg.E, topo), dtype=torch.uint8, device=DEV)
+    ws_rt = torch.empty(rs.route_traffic_workspace_bytes(B, cfg.tokens_per_gpu, cfg.E, cfg.k, topo), dtype=torch.uint8, device=DEV)
 
     def step(eager=False):
         if fused and not eager:                                     # the two fused calls, checked against the five stages

@@ -55,6 +55,7 @@ def _check_instances(g, D1_host_of, M, N, C, insts):
     """Whole instances against the oracle: records, permutation, rails, send loads."""
     off = g["off"].cpu().numpy()
     for inst in insts:
+        print(f"  instance {inst}: {int(off[inst + 1] - off[inst])} chunks against the oracle", flush=True)
         b, k = divmod(int(inst), M)
         cw, cf = oracle.chunk_split(D1_host_of(b), M, N, C, k)
         sw, sf, sp = oracle.sort_desc(cw, cf)
@@ -219,21 +220,35 @@ def test_c4_all_layers_sampled():
 
 
 # ---------------------------------------------------------------------------------------- c5
+C5_MATRICES = (0, 3, 128, 255)          # of the 256 the workload has; each is ~3.9e9 chunks and runs on its own
+C5_WHOLE_MATRICES = (3, 255)           # these also meet the oracle in full: S, R and stats of all 128 instances
+
+
 @pytest.mark.timeout(900)
-def test_c5_one_matrix_sampled():
+@pytest.mark.parametrize("b", C5_MATRICES)
+def test_c5_matrix(b):
     cfg = W.get_config("c5")
     M, N, C = cfg.M, cfg.N, cfg.chunk_bytes
     topo = rs.Topo(M, N, C)
-    D1 = W.gen_flow_matrices_device(cfg, DEV, first=3, count=1)             # one 1024x1024 matrix: ~4e9 chunks
+    D1 = W.gen_flow_matrices_device(cfg, DEV, first=b, count=1)             # one 1024x1024 matrix: ~4e9 chunks
     g = _schedule_dev(D1, topo, want_perm=False)
     _check_one_call(g, D1, topo)
     D1_h = D1.cpu().numpy()
-    assert np.array_equal(g["off"].cpu().numpy(), oracle.chunk_count_batch(D1_h, M, N, C))
-    sizes = np.diff(g["off"].cpu().numpy())
+    off_g = g["off"].cpu().numpy()
+    assert np.array_equal(off_g, oracle.chunk_count_batch(D1_h, M, N, C))
+    sizes = np.diff(off_g)
     assert sizes.max() > 10_000_000
     order = np.argsort(sizes)
-    _check_instances(g, lambda b: D1_h[b], M, N, C, [int(order[0]), int(order[len(order) // 2])])
+    # the largest instance (the heavy tail this workload exists for), the smallest and the median, element by element
+    _check_instances(g, lambda _: D1_h[0], M, N, C, [int(order[-1]), int(order[0]), int(order[len(order) // 2])])
     _check_properties(g, D1, M, N)
+    if b in C5_WHOLE_MATRICES:
+        # every instance of the matrix through the oracle, one node at a time (its records would not fit otherwise)
+        off_c, S_c, R_c, stats_c = oracle.schedule_matrix_by_node(D1_h[0], M, N, C)
+        assert np.array_equal(off_g, off_c)
+        assert np.array_equal(g["S"][0].cpu().numpy(), S_c), "S"
+        assert np.array_equal(g["R"][0].cpu().numpy(), R_c), "R"
+        assert np.array_equal(g["stats"][0].cpu().numpy(), stats_c), "stats"
     del D1, g
     _free()
 

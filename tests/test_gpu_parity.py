@@ -312,6 +312,11 @@ def test_schedule_one_call_capacity_overflow_leaves_records_alone():
     torch.cuda.synchronize()
     assert int(out[0][-1].item()) == total
     assert bool((out[1] == -1).all()) and bool((out[2] == -1).all()) and bool((out[4] == 255).all())
+    assert all(bool((t == -1).all()) for t in out[5:])                  # S, R, stats say so without a read-back of chunk_off
+    with pytest.raises(rs.RailschedError) as err:                       # and the synchronising call reports it to the host
+        rs.check_capacity(out[0], B, topo, cap)
+    assert err.value.status == -4 and err.value.total == total
+    assert rs.check_capacity(out[0], B, topo, total) == total
     # the same through the three-stage shape (more instances than one workgroup each serves)
     B2 = 300
     D2n = _rand_stack(rng, B2, M * N, C)
@@ -325,6 +330,55 @@ def test_schedule_one_call_capacity_overflow_leaves_records_alone():
     torch.cuda.synchronize()
     assert int(out2[0][-1].item()) == total2
     assert bool((out2[1] == -1).all()) and bool((out2[2] == -1).all()) and bool((out2[4] == 255).all())
+    assert all(bool((t == -1).all()) for t in out2[5:])
+
+
+@pytest.mark.parametrize("B", [2, 300, 8200])      # wide shape of stage 4, and packed shape (N = 4: from 32768 instances on)
+@pytest.mark.parametrize("chunkwise", [False, True])
+def test_three_calls_capacity_overflow_touches_no_record(B, chunkwise):
+    # stage 3 finds more chunks than the arrays hold: stages 4 and 5, given the same capacity, must neither read nor
+    # write a record and must mark their outputs (sentinel-filled arrays sized exactly `capacity` stay as they were)
+    rng = np.random.default_rng(79 + B)
+    M, N, C = 4, 4, 4096
+    D1n = _rand_stack(rng, B, M * N, C)
+    topo = rs.Topo(M, N, C)
+    total = int(oracle.chunk_count_batch(D1n, M, N, C)[-1])
+    cap = total - 1
+    off = torch.empty(B * M + 1, dtype=torch.int64, device=DEV)
+    w = torch.full((cap,), -1, dtype=torch.int32, device=DEV)
+    flow = torch.full((cap,), -1, dtype=torch.int32, device=DEV)
+    perm = torch.full((cap,), -1, dtype=torch.int32, device=DEV)
+    rail = torch.full((cap,), 255, dtype=torch.uint8, device=DEV)
+    port = torch.full((cap,), 254, dtype=torch.uint8, device=DEV)
+    S = torch.zeros((B, M, N), dtype=torch.int64, device=DEV)
+    R = torch.zeros((B, M, N), dtype=torch.int64, device=DEV)
+    stats = torch.zeros((B, 8), dtype=torch.int64, device=DEV)
+    rs.chunk_sort(torch.from_numpy(D1n).to(DEV), topo, capacity=cap, out=(off, w, flow, perm))
+    rs.lpt_spray(off, w, B, topo, out=(rail, S), chunkwise=chunkwise, capacity=cap)
+    rs.eval(off, w, flow, rail, S, B, topo, out=(R, stats), capacity=cap)
+    rs.port_round_robin(off, rail, B, topo, 4, capacity=cap, out=port)
+    torch.cuda.synchronize()
+    assert int(off[-1].item()) == total
+    assert bool((w == -1).all()) and bool((flow == -1).all()) and bool((perm == -1).all())
+    assert bool((rail == 255).all()) and bool((port == 254).all())
+    assert bool((S == -1).all()) and bool((R == -1).all()) and bool((stats == -1).all())
+    for policy in ("nic_direct", "random_spray"):
+        S.zero_()
+        rs.assign_policy(policy, 5, off, w, flow, B, topo, out=(rail, S), capacity=cap)
+        torch.cuda.synchronize()
+        assert bool((rail == 255).all()) and bool((S == -1).all())
+    # with room for every chunk the same buffers come out as the oracle says (one spare record stays untouched)
+    cap = total + 1
+    w, flow, perm = (torch.full((cap,), -1, dtype=torch.int32, device=DEV) for _ in range(3))
+    rail = torch.full((cap,), 255, dtype=torch.uint8, device=DEV)
+    rs.chunk_sort(torch.from_numpy(D1n).to(DEV), topo, capacity=cap, out=(off, w, flow, perm))
+    rs.lpt_spray(off, w, B, topo, out=(rail, S), chunkwise=chunkwise, capacity=cap)
+    rs.eval(off, w, flow, rail, S, B, topo, out=(R, stats), capacity=cap)
+    torch.cuda.synchronize()
+    c = cpu_schedule(D1n, M, N, C)
+    assert np.array_equal(_u32(w)[:total], c["w"]) and np.array_equal(rail.cpu().numpy()[:total], c["rail"])
+    assert np.array_equal(S.cpu().numpy(), c["S"]) and np.array_equal(R.cpu().numpy(), c["R"]) and np.array_equal(stats.cpu().numpy(), c["stats"])
+    assert int(w[-1].item()) == -1 and int(rail[-1].item()) == 255
 
 
 @pytest.mark.parametrize("M,N,C,B,intra", [(4, 4, 65536, 1, 0), (3, 2, 100, 4, 0), (3, 2, 100, 4, 1), (5, 3, 1000, 3, 0),

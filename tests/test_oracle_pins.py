@@ -335,6 +335,34 @@ def test_eval_single_flow_fixture(golden_dir):
     assert stats[0].tolist() == [25, 25, 20, 24, 47, 10, 6, 3]
 
 
+def test_schedule_matrix_by_node_pins(golden_dir):
+    # the node-at-a-time form used for matrices too large to hold: the hand-worked fixture, the closed form of the
+    # all-equal matrix (Theorem 3) and, on random matrices with and without intra-node traffic, the batched steps
+    g = _read_golden(os.path.join(golden_dir, "single_flow_receive.txt"))
+    M, N, C = g["M"][0], g["N"][0], g["C"][0]
+    D1 = np.zeros((M * N, M * N), dtype=np.int64)
+    for d, n, f, m, nbytes in g["flow"]:
+        D1[d * N + n, f * N + m] = nbytes
+    off, S, R, stats = oracle.schedule_matrix_by_node(D1, M, N, C)
+    assert off.tolist() == [0, 6, 6, 6] and S[0].tolist() == g["S0"] and R.tolist() == [[0, 0], g["R1"], g["R2"]]
+    assert stats.tolist() == [25, 25, 20, 24, 47, 10, 6, 3]
+    for (M, N, q) in [(4, 4, 3), (5, 3, 2)]:
+        C = 4096
+        off, S, R, stats = oracle.schedule_matrix_by_node(W.symmetric_matrix(M, N, q, C), M, N, C)
+        expect = (M - 1) * N * q * C
+        assert np.all(S == expect) and np.all(R == expect) and stats[0] == stats[3] == expect and stats[7] == 0
+        assert off.tolist() == [k * (M - 1) * N * N * q for k in range(M + 1)]
+    rng = np.random.default_rng(21)
+    for (M, N, C, intra) in [(6, 4, 1000, 0), (3, 5, 64, 1), (9, 2, 4096, 0)]:
+        D1 = rng.integers(0, 7 * C, size=(M * N, M * N)).astype(np.int64)
+        D1[rng.random(D1.shape) < 0.3] = 0
+        off, S, R, stats = oracle.schedule_matrix_by_node(D1, M, N, C, intra)
+        b_off, b_w, b_flow, _ = oracle.chunk_sort_batch(D1[None], M, N, C, intra)
+        b_rail, b_S = oracle.lpt_batch(b_off, b_w, 1, M, N)
+        _, b_R, b_stats = oracle.eval_batch(b_off, b_w, b_flow, b_rail, 1, M, N)
+        assert np.array_equal(off, b_off) and np.array_equal(S, b_S[0]) and np.array_equal(R, b_R[0]) and np.array_equal(stats, b_stats[0])
+
+
 def test_eval_conservation_on_workload():
     cfg = W.get_config("c1")
     _, _, _, D1 = _routing(cfg)
