@@ -296,25 +296,16 @@ extern "C" size_t railsched_schedule_workspace_bytes(int32_t batch, const railsc
     return (s && e) ? s + rs::sched_eval_bytes(batch, h_topo) : 0;     // both are multiples of 256
 }
 
-extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off,
-                                  uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm, int64_t capacity, uint8_t *rail,
-                                  int64_t *S, int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream)
+namespace rs {
+// Stages 3-5 with the workspace already checked: ws holds railsched_schedule_workspace_bytes(batch, topo) bytes, 256-byte aligned.
+static int schedule_run(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off, uint32_t *chunk_w,
+                        uint32_t *chunk_flow, uint32_t *perm, int64_t capacity, uint8_t *rail, int64_t *S, int64_t *R, int64_t *stats,
+                        void *ws, hipStream_t st)
 {
-    using namespace rs;
-    if (int rc = check_topo(h_topo)) return rc;
-    if (batch < 0 || capacity < 0) return RAILSCHED_ERR_INVALID_ARG;
-    if (batch > 65535) return RAILSCHED_ERR_UNSUPPORTED;
     const int64_t M = h_topo->nodes, N = h_topo->rails, G = M * N, NF = N * G;
-    if (NF > kMaxFlows) return RAILSCHED_ERR_UNSUPPORTED;
     const int64_t n_inst = (int64_t)batch * M;
-    if (n_inst > 0x7FFFFFFFll / 64) return RAILSCHED_ERR_UNSUPPORTED;
-    if (batch == 0) return RAILSCHED_OK;
-    if (!D1 || !chunk_off || !chunk_w || !chunk_flow || !rail || !S || !R || !stats) return RAILSCHED_ERR_NULL_PTR;
     const size_t ws_sort = railsched_chunk_sort_workspace_bytes(batch, h_topo);
-    const size_t ws_eval = sched_eval_bytes(batch, h_topo);
-    if (!ws || ws_bytes < ws_sort + ws_eval || reinterpret_cast<uintptr_t>(ws) % 256) return RAILSCHED_ERR_WORKSPACE;
     char *w8 = static_cast<char *>(ws);
-    hipStream_t st = static_cast<hipStream_t>(stream);
 
     const int GW = N <= 4 ? 4 : N <= 8 ? 8 : N <= 16 ? 16 : N <= 32 ? 32 : 64;
     const unsigned w_limit = GW == 4 ? WideLimit<4>::value : GW == 8 ? WideLimit<8>::value : GW == 16 ? WideLimit<16>::value
@@ -377,4 +368,36 @@ extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsc
            : GW == 32 ? launch_ss<32>(a, x, st) : launch_ss<64>(a, x, st);
     if (rc) return rc;
     return launch_eval_reduce(e, batch, st);
+}
+
+// arguments of railsched_schedule apart from the workspace: 0 and *nothing_to_do = false when the kernels should run
+static int schedule_check(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off, uint32_t *chunk_w,
+                          uint32_t *chunk_flow, int64_t capacity, uint8_t *rail, int64_t *S, int64_t *R, int64_t *stats,
+                          bool *nothing_to_do)
+{
+    *nothing_to_do = false;
+    if (int rc = check_topo(h_topo)) return rc;
+    if (batch < 0 || capacity < 0) return RAILSCHED_ERR_INVALID_ARG;
+    if (batch > 65535) return RAILSCHED_ERR_UNSUPPORTED;
+    const int64_t M = h_topo->nodes, N = h_topo->rails, G = M * N, NF = N * G;
+    if (NF > kMaxFlows) return RAILSCHED_ERR_UNSUPPORTED;
+    if ((int64_t)batch * M > 0x7FFFFFFFll / 64) return RAILSCHED_ERR_UNSUPPORTED;
+    if (batch == 0) { *nothing_to_do = true; return RAILSCHED_OK; }
+    if (!D1 || !chunk_off || !chunk_w || !chunk_flow || !rail || !S || !R || !stats) return RAILSCHED_ERR_NULL_PTR;
+    return RAILSCHED_OK;
+}
+}  // namespace rs
+
+extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off,
+                                  uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm, int64_t capacity, uint8_t *rail,
+                                  int64_t *S, int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream)
+{
+    using namespace rs;
+    bool nothing = false;
+    if (int rc = schedule_check(D1, batch, h_topo, chunk_off, chunk_w, chunk_flow, capacity, rail, S, R, stats, &nothing)) return rc;
+    if (nothing) return RAILSCHED_OK;
+    if (!ws || ws_bytes < railsched_schedule_workspace_bytes(batch, h_topo) || reinterpret_cast<uintptr_t>(ws) % 256)
+        return RAILSCHED_ERR_WORKSPACE;
+    return schedule_run(D1, batch, h_topo, chunk_off, chunk_w, chunk_flow, perm, capacity, rail, S, R, stats, ws,
+                        static_cast<hipStream_t>(stream));
 }
