@@ -47,7 +47,8 @@ typedef enum railsched_status {
     RAILSCHED_ERR_UNSUPPORTED = -3, /* valid in the paper's model but beyond this build's limits */
     RAILSCHED_ERR_CAPACITY    = -4, /* railsched_check_capacity: more chunks than the arrays hold */
     RAILSCHED_ERR_WORKSPACE   = -5, /* workspace missing or smaller than *_workspace_bytes()     */
-    RAILSCHED_ERR_HIP         = -6  /* the HIP runtime refused a launch                          */
+    RAILSCHED_ERR_HIP         = -6, /* the HIP runtime refused a launch                          */
+    RAILSCHED_ERR_SCRATCH     = -7  /* railsched_schedule_static: needs more than the static buffer */
 } railsched_status;
 
 /* Topology and chunking of the Rail fabric (Section 4.1; chunk size: Section 5.1, "Flow Splitting
@@ -218,6 +219,24 @@ size_t railsched_schedule_workspace_bytes(int32_t batch, const railsched_topo_t 
 int railsched_schedule(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off,
                        uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm, int64_t capacity, uint8_t *rail,
                        int64_t *S, int64_t *R, int64_t *stats, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * railsched_schedule for callers that cannot allocate device memory or carry a workspace around: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments without the
+ * workspace, same outputs bit for bit; the workspace is an array of RAILSCHED_STATIC_SCRATCH_BYTES bytes inside
+ * the library's device image (every GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates and frees nothing; the first call on a device asks the runtime for the array's address there.
+ * Batches whose railsched_schedule_workspace_bytes(batch, topo) exceeds RAILSCHED_STATIC_SCRATCH_BYTES are
+ * refused with RAILSCHED_ERR_SCRATCH before anything is enqueued (4 MiB covers e.g. 32 matrices of 8 nodes x
+ * 8 rails, or 1024 matrices of 4 x 4).
+ * All calls on one GPU share that GPU's array: calls that can overlap there (different streams, or several
+ * host threads) race on it and must be ordered by the caller; on one stream they are ordered already.
+ * Errors: as railsched_schedule without WORKSPACE, plus SCRATCH, and HIP when the device has no such array.
+ * ------------------------------------------------------------------------------------------- */
+#define RAILSCHED_STATIC_SCRATCH_BYTES (4u << 20)
+int railsched_schedule_static(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off,
+                              uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm, int64_t capacity, uint8_t *rail,
+                              int64_t *S, int64_t *R, int64_t *stats, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Second all-to-all of an MoE layer (Algorithm 1 step 4: expert outputs return to the token owners):

@@ -23,7 +23,7 @@ EXPORTS = (
     "railsched_traffic_matrix_workspace_bytes", "railsched_traffic_matrix",
     "railsched_route_traffic_workspace_bytes", "railsched_route_traffic",
     "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray", "railsched_lpt_spray_chunkwise",
-    "railsched_eval_workspace_bytes", "railsched_eval", "railsched_schedule_workspace_bytes", "railsched_schedule", "railsched_transpose_matrix", "railsched_assign_policy",
+    "railsched_eval_workspace_bytes", "railsched_eval", "railsched_schedule_workspace_bytes", "railsched_schedule", "railsched_schedule_static", "railsched_transpose_matrix", "railsched_assign_policy",
     "railsched_port_round_robin_workspace_bytes", "railsched_port_round_robin",
 )
 
@@ -93,6 +93,8 @@ def load():
     lib.railsched_schedule_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_schedule_workspace_bytes.restype = SZ
     lib.railsched_schedule.argtypes = [P, I32, TP, P, P, P, P, I64, P, P, P, P, P, SZ, P]
+    lib.railsched_schedule_static.argtypes = [P, I32, TP, P, P, P, P, I64, P, P, P, P, P]
+    lib.railsched_schedule_static.restype = C.c_int
     lib.railsched_transpose_matrix.argtypes = [P, I32, TP, P, P]
     lib.railsched_assign_policy.argtypes = [I32, C.c_uint64, P, P, P, I32, TP, I64, P, P, P]
     lib.railsched_port_round_robin_workspace_bytes.argtypes = [I32, TP, I64]
@@ -398,6 +400,20 @@ def schedule(D1: torch.Tensor, topo: Topo, capacity: int, want_perm: bool = True
     t = topo.c()
     _check(load().railsched_schedule(_ptr(D1), batch, C.byref(t), _ptr(off), _ptr(w), _ptr(flow), _ptr(perm), capacity, _ptr(rail),
                                      _ptr(S), _ptr(R), _ptr(stats), _ptr(ws), ws.numel(), _stream()), "railsched_schedule")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def schedule_static(D1: torch.Tensor, topo: Topo, capacity: int, out):
+    """railsched_schedule_static: stages 3-5 with the library's own static scratch buffer instead of a workspace.
+    `out` = (chunk_off, chunk_w, chunk_flow, perm or None, rail, S, R, stats), preallocated: nothing is allocated here."""
+    _dev(D1, torch.int64, "D1")
+    off, w, flow, perm, rail, S, R, stats = out
+    t = topo.c()
+    _check(load().railsched_schedule_static(_ptr(D1), D1.shape[0], C.byref(t), _ptr(off), _ptr(w), _ptr(flow), _ptr(perm), capacity,
+                                            _ptr(rail), _ptr(S), _ptr(R), _ptr(stats), _stream()), "railsched_schedule_static")
     return out
 
 

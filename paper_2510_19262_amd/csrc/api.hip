@@ -13,6 +13,7 @@ extern "C" const char *railsched_strerror(int status)
         case RAILSCHED_ERR_CAPACITY: return "more chunks than the record arrays hold";
         case RAILSCHED_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case RAILSCHED_ERR_HIP: return "HIP runtime error";
+        case RAILSCHED_ERR_SCRATCH: return "the batch needs more scratch memory than the library's static buffer holds";
         default: return "unknown status";
     }
 }

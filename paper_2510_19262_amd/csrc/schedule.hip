@@ -18,7 +18,32 @@
 #include "eval_core.h"
 #include "lpt_core.h"
 
+#include <mutex>
+
 namespace rs {
+
+// Workspace of railsched_schedule_static: one array per GPU, part of the library's device image, so the call needs no
+// allocation.  The name below is only a handle for host code; the array's device address is asked for once per device
+// (static_scratch) and that address is what kernels and every other use get.
+static __device__ __align__(256) unsigned char scratch[RAILSCHED_STATIC_SCRATCH_BYTES];
+
+constexpr int kScratchDevices = 64;
+static void *g_scratch_ptr[kScratchDevices];       // device address of `scratch` on each GPU, once known
+static std::mutex g_scratch_mutex;
+
+// address of the current device's copy of `scratch`; nullptr if the runtime refuses
+static void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kScratchDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;   // this device is the current one
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
 
 void launch_cs_count(const CsArgs &a, hipStream_t st);          // chunk_sort.hip
 int lpt_serial_after_leading_runs(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
@@ -398,6 +423,24 @@ extern "C" int railsched_schedule(const int64_t *D1, int32_t batch, const railsc
     if (nothing) return RAILSCHED_OK;
     if (!ws || ws_bytes < railsched_schedule_workspace_bytes(batch, h_topo) || reinterpret_cast<uintptr_t>(ws) % 256)
         return RAILSCHED_ERR_WORKSPACE;
+    return schedule_run(D1, batch, h_topo, chunk_off, chunk_w, chunk_flow, perm, capacity, rail, S, R, stats, ws,
+                        static_cast<hipStream_t>(stream));
+}
+
+extern "C" int railsched_schedule_static(const int64_t *D1, int32_t batch, const railsched_topo_t *h_topo, int64_t *chunk_off,
+                                         uint32_t *chunk_w, uint32_t *chunk_flow, uint32_t *perm, int64_t capacity, uint8_t *rail,
+                                         int64_t *S, int64_t *R, int64_t *stats, void *stream)
+{
+    using namespace rs;
+    bool nothing = false;
+    if (int rc = schedule_check(D1, batch, h_topo, chunk_off, chunk_w, chunk_flow, capacity, rail, S, R, stats, &nothing)) return rc;
+    if (nothing) return RAILSCHED_OK;
+    const size_t need = railsched_schedule_workspace_bytes(batch, h_topo);
+    if (need == 0 || need > (size_t)RAILSCHED_STATIC_SCRATCH_BYTES) return RAILSCHED_ERR_SCRATCH;
+    void *ws = static_scratch();
+    if (!ws) return RAILSCHED_ERR_HIP;
+    // every word of the workspace that a kernel reads was written earlier in the same call (counts and scans by the count
+    // and scan kernels, one slot of receive loads per instance or slice), so what the last call left needs no clearing
     return schedule_run(D1, batch, h_topo, chunk_off, chunk_w, chunk_flow, perm, capacity, rail, S, R, stats, ws,
                         static_cast<hipStream_t>(stream));
 }

@@ -212,3 +212,19 @@ def test_schedule_validation():
     assert f(FAKE, 0, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, need, None) == 0
     big = _topo(M=64, N=32)
     assert f(FAKE, 1, C.byref(big), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == -3
+
+
+def test_schedule_static_validation():
+    lib = rs.load()
+    t = _topo()
+    f = lib.railsched_schedule_static   # railsched_schedule without (ws, ws_bytes)
+    assert f(FAKE, -1, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, None) == -1
+    assert f(None, 2, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, None) == -2
+    assert f(FAKE, 2, None, FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, None) == -2
+    assert f(FAKE, 0, C.byref(t), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, None) == 0
+    big = _topo(M=32, N=8, Cb=65536)                                   # 64 matrices of 256 x 256: far more scratch than 4 MiB
+    assert lib.railsched_schedule_workspace_bytes(64, C.byref(big)) > rs.STATIC_SCRATCH_BYTES
+    assert f(FAKE, 64, C.byref(big), FAKE, FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, None) == -7
+    assert "static" in rs.strerror(-7)
+    header = open(os.path.join(ROOT, "include", "railsched.h")).read()
+    assert re.search(r"#define\s+RAILSCHED_STATIC_SCRATCH_BYTES\s+\(4u\s*<<\s*20\)", header) and rs.STATIC_SCRATCH_BYTES == 4 << 20
