@@ -1,20 +1,28 @@
 #!/usr/bin/env python3
-"""Benchmark of the whole rail-spraying path on one MI355X (default: the c2 workload; --config picks another).
+"""Benchmark of the rail-spraying path on one MI355X.  Prints ONE JSON line.
 
-A step is one pass of all five stages (route_topk -> traffic_matrix -> chunk_sort -> lpt_spray ->
-eval) over one batch of the Mixtral-8x7B-shaped workload, through two calls: railsched_route_traffic
-(stages 1-2 in one pass over the logits) and railsched_schedule (stages 3-5, one workgroup per
-instance).  Both write the same bytes as the separate calls - asserted here on every output array;
-the same step through the five separate calls is timed too and reported as "staged", and the
-throughput with two steps in flight on two streams as "two_steps_in_flight".  Workload: 8 nodes x
-8 rails, 8 experts top-2, 16384 tokens per GPU, 8 KiB tokens, 256 KiB chunks, 32 layers = 32
-traffic matrices of 64x64.
-Inputs (1 GiB of fp32 router logits, synthetic, seeded) are resident in HBM before timing starts.
-Prints ONE JSON line.
+Headline (metric, value, ms_per_step): the Mixtral-8x7B-shaped workload c2 - 8 nodes x 8 rails, 8 experts
+top-2, 16384 tokens per GPU, 8 KiB tokens, 256 KiB chunks, 32 layers = 32 traffic matrices of 64x64 - with its
+1 GiB of fp32 router logits resident in HBM before timing starts.  A step is one pass of all five stages
+(route_topk -> traffic_matrix -> chunk_sort -> lpt_spray -> eval) through two calls: railsched_route_traffic
+(stages 1-2 in one pass over the logits) and railsched_schedule (stages 3-5).  Both write the same bytes as
+the five separate calls - asserted here on every output array; the five calls are timed too ("staged").
+
+Beside it, under "workloads", one record for each larger workload, each with the rooflines of its calls, the
+per-chunk LPT kernel against the VALU issue rate, and the CPU oracle timed in the same run on a stated sample:
+  c3  sparse synthetic flows, 32 x 8, 1024 matrices of 256x256 resident (3.9e9 chunks, 32 768 instances): stages 3-5
+  c4  DeepSeek-V3-shaped, 64 x 8, 256 experts top-8, 61 layers of 4 194 304 rows: whole path, one layer's 4 GiB of
+      logits resident at a time (regenerated between layers, untimed)
+  c5  stress, 128 x 8, all 256 matrices of 1024x1024, one matrix (3.9e9 chunks) resident at a time: stages 3-5
+--config c1|c2|c3|c4|c5 runs that workload alone (its record is the whole line); used for the profiles.
+Stage times are medians over the repetitions (hipEvents on the stream the calls are enqueued on).
 """
 import argparse
+import hashlib
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -22,11 +30,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes the launches of one route_traffic call (main kernel + reduction of the slice counts) move on this
-# workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy of known traffic (profiles/c2_whole_path.md).
-# route_traffic_kernel 1043.54 MiB read + 272.00 MiB written, rt_reduce_kernel 16.04 MiB read + 1.00 MiB written.
-ROUTE_TRAFFIC_C2_TRAFFIC_BYTES = int((1043.54 + 272.00 + 16.04 + 1.00) * 1024 * 1024)
+HBM_PEAK_GBPS = 8000.0                      # MI355X published HBM3E bandwidth
+VALU_PEAK_GIPS = 256 * 4 * 2.4e9 / 4 / 1e9  # G wave-instructions/s: 256 CUs x 4 SIMDs, one wave64 VALU instruction per 4 clocks at 2.4 GHz
 
 
 def parse():
@@ -34,41 +39,211 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="c2",
-                    help="workload: c2 (default, the benchmark workload) or c1 = whole path with resident logits; c4 = whole path, "
-                         "logits streamed layer by layer; c3, c5 = stages 3-5 on synthetic flow matrices")
-    ap.add_argument("--matrices", type=int, default=0,
-                    help="c3/c5: matrices per step (0 = all of c3, one of c5: a c5 matrix alone is 3.9e9 chunks)")
+    ap.add_argument("--config", default="all",
+                    help="all (default): c2 as the headline and c3, c4, c5 as sub-records; c1..c5: that workload alone")
+    ap.add_argument("--matrices", type=int, default=0, help="c3/c5: matrices to run (0 = all)")
+    ap.add_argument("--layers", type=int, default=0, help="c4: layers to run (0 = all 61)")
     ap.add_argument("--cpu-layers", type=int, default=-1,
-                    help="layers of the workload the CPU oracle is timed on (-1 = all, 0 = skip)")
+                    help="c1/c2: layers the CPU oracle is timed on (-1 = all, 0 = skip every CPU baseline)")
     ap.add_argument("--skip-extras", action="store_true",
-                    help="only the two timed regions (fused and staged step): no supplementary measurements; used for profiles, "
-                         "so that a kernel's average duration is that of the timed region")
+                    help="only the timed regions: no supplementary measurements (used for profiles, so that a kernel's "
+                         "average duration is that of the timed region)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device copy first: a kernel of known traffic to scale profiler byte counters by")
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (the rails and the other GPUs are simulated "
-              "arithmetically); --gpus N with N > 1 is not supported", file=sys.stderr)
-        sys.exit(2)
+# ------------------------------------------------------------------------------------------------ helpers
+def _event(torch):
+    e = torch.cuda.Event(enable_timing=True)
+    e.record()
+    return e
 
-    import numpy as np
-    import torch
-    import workloads as W
-    import paper_2510_19262_amd as rs
 
-    rs.load()                                       # fails loudly if the HIP library is missing
+def _median(xs):
+    return float(statistics.median(xs)) if xs else None
+
+
+def _sha12(relpath):
+    with open(os.path.join(ROOT, relpath), "rb") as fh:
+        return hashlib.sha256(fh.read()).hexdigest()[:12]
+
+
+def counter_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` on `workload` from the rocprofv3 counter runs summarised under profiles/
+    (FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a copy of known size).  The summaries carry lines
+      TRAFFIC <kernel> <workload> read_MiB=<x> written_MiB=<y> source=<file under csrc> sha=<first 12 hex of its sha256>
+    and this is the one place the benchmark takes the figure from.  None when there is no such line, or when the
+    kernel's source file has changed since the counters were taken."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    pat = re.compile(r"^TRAFFIC\s+(\S+)\s+(\S+)\s+read_MiB=([0-9.]+)\s+written_MiB=([0-9.]+)\s+source=(\S+)\s+sha=([0-9a-f]+)")
+    for name in sorted(os.listdir(pdir)):
+        if not name.endswith((".md", ".txt")):
+            continue
+        for line in open(os.path.join(pdir, name)):
+            m = pat.match(line.strip())
+            if m and m.group(1) == kernel and m.group(2) == workload:
+                src = os.path.join("paper_2510_19262_amd", "csrc", m.group(5))
+                if not os.path.exists(os.path.join(ROOT, src)) or _sha12(src) != m.group(6):
+                    return None
+                return int((float(m.group(3)) + float(m.group(4))) * 1024 * 1024)
+    return None
+
+
+def copy_probe(torch, dev):
+    """One 1 GiB device-to-device copy: a kernel whose traffic is known, to scale the profiler's byte counters by."""
+    src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
+def hbm_roofline(kernel, workload, algorithmic_bytes, ms, note=None):
+    gbps = algorithmic_bytes / (ms * 1e-3) / 1e9
+    r = {"kernel": kernel, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+         "traffic": counter_traffic(kernel.split(" ")[0], workload), "algorithmic_bytes_per_launch": int(algorithmic_bytes),
+         "avg_launch_ms": ms}
+    if note:
+        r["note"] = note
+    return r
+
+
+def lpt_alu_roofline(total_chunks, n_inst, N, ms):
+    """The per-chunk LPT kernel against the VALU issue rate.  Per greedy step and wavefront: ceil(log2 GW) cross-lane mins,
+    the add, compare, select and the instruction that files the decision (+ the weight broadcast in the wide shape);
+    the packed shape advances 64/GW instances with every instruction."""
+    gw = 4 if N <= 4 else 8 if N <= 8 else 16 if N <= 16 else 32 if N <= 32 else 64
+    ipw = 64 // gw if (gw < 64 and n_inst >= 2048 * 64 // gw) else 1
+    instr = (gw.bit_length() - 1) + (4 if ipw > 1 else 5)
+    ach = total_chunks / ipw * instr / (ms * 1e-3) / 1e9
+    return {"kernel": "lpt_packed_kernel<GW,false>" if ipw > 1 else "lpt_wide_kernel<GW,false>", "bound": "alu", "unit": "G wave-instr/s",
+            "peak": VALU_PEAK_GIPS, "achieved": ach, "frac": ach / VALU_PEAK_GIPS, "avg_launch_ms": ms,
+            "instructions_per_step": instr, "instances_per_wavefront": ipw, "wavefronts": -(-n_inst // ipw),
+            "note": "algorithmic VALU instructions of the greedy chain; with fewer wavefronts than 4 per SIMD (1024 SIMDs) the "
+                    "latency of the chain, not the issue rate, bounds the kernel"}
+
+
+def stage_bytes(total_chunks, n_inst, topo, want_perm):
+    """Algorithmic HBM bytes of stages 3-5: D1 read + 8 (12 with perm) B written per chunk; 4 B read + 1 B written; 9 B read."""
+    NG = topo.rails * topo.G
+    return {"chunk_sort": 8 * NG * n_inst + (12 if want_perm else 8) * total_chunks, "lpt_spray": 5 * total_chunks,
+            "eval": 9 * total_chunks, "schedule": 8 * NG * n_inst + (13 if want_perm else 9) * total_chunks}
+
+
+STAGE_KERNEL = {"chunk_sort": "cs_fill_kernel (with the count, scan and tail-sort kernels of the call)",
+                "lpt_spray": "lpt_prefix_kernel (with the serial kernel behind the leading runs)",
+                "eval": "eval_partial_kernel (with the reduction of the call)",
+                "schedule": "cs_fill_kernel (railsched_schedule: records and leading-run rails written once; count, scan, tail sort, "
+                            "serial LPT behind the leading runs, closed-form receive loads and reduction in the same call)"}
+
+
+def time_stages_3_5(rs, torch, plan, D1, topo, B, reps, warmup):
+    """Medians of the three separate calls and of railsched_schedule on the same input; asserts identical outputs."""
+    names = ("chunk_sort", "lpt_spray", "eval")
+    t = {n: [] for n in names}
+    for it in range(warmup + reps):
+        e = [_event(torch)]
+        rs.chunk_sort(D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
+        e.append(_event(torch))
+        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S), capacity=plan.capacity)
+        e.append(_event(torch))
+        rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.rail, plan.S, B, topo, out=(plan.R, plan.stats), ws=plan.ws_eval,
+                capacity=plan.capacity)
+        e.append(_event(torch))
+        torch.cuda.synchronize()
+        if it >= warmup:
+            for i, n in enumerate(names):
+                t[n].append(e[i].elapsed_time(e[i + 1]))
+    small = [x.clone() for x in (plan.chunk_off, plan.S, plan.R, plan.stats)]
+    rail3 = plan.rail.clone()
+    for x in (plan.rail, plan.S, plan.R, plan.stats):
+        x.zero_()
+    one = []
+    for it in range(warmup + reps):
+        e0 = _event(torch)
+        plan.schedule_one_call(D1)
+        e1 = _event(torch)
+        torch.cuda.synchronize()
+        if it >= warmup:
+            one.append(e0.elapsed_time(e1))
+    assert all(torch.equal(a, b) for a, b in zip(small, (plan.chunk_off, plan.S, plan.R, plan.stats))) and torch.equal(rail3, plan.rail)
+    del rail3
+    return {n: _median(v) for n, v in t.items()}, _median(one)
+
+
+def time_chunkwise(rs, torch, plan, B, topo, reps):
+    """The plain per-chunk LPT kernel (every chunk through the cross-lane argmin) on the records in `plan`; same outputs."""
+    rail2, S2 = torch.empty_like(plan.rail), torch.empty_like(plan.S)
+    t = []
+    for it in range(1 + reps):
+        e0 = _event(torch)
+        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(rail2, S2), chunkwise=True, capacity=plan.capacity)
+        e1 = _event(torch)
+        torch.cuda.synchronize()
+        if it >= 1:
+            t.append(e0.elapsed_time(e1))
+    total = int(plan.chunk_off[-1].item())
+    assert torch.equal(rail2[:total], plan.rail[:total]) and torch.equal(S2, plan.S)
+    del rail2, S2
+    return _median(t)
+
+
+def ratio_stats(np, stats):
+    r = stats[:, 0] / np.maximum(stats[:, 3], 1)
+    return {"max": float(r.max()), "mean": float(r.mean())}
+
+
+def exact_mse_over_wmax2(S, wmax):
+    """max over matrices and nodes of MSE / w_max^2 with MSE = (1/N) sum_j (L_j - mean)^2 (Algorithm 2 step 6; Theorem 4
+    bounds it by w_max^2), in exact integer arithmetic: sum_j (N L_j - T)^2 / (N^3 w_max^2) with T = sum_j L_j."""
+    from fractions import Fraction
+    best = Fraction(0)
+    for b in range(S.shape[0]):
+        wm = int(wmax[b])
+        if wm == 0:
+            continue
+        for k in range(S.shape[1]):
+            L = [int(x) for x in S[b, k]]
+            N, T = len(L), sum(L)
+            best = max(best, Fraction(sum((N * x - T) ** 2 for x in L), N ** 3 * wm * wm))
+    return float(best)
+
+
+def cpu_stages_3_5(oracle, np, D1_host, M, N, C, plan_slices):
+    """The oracle on a sample of whole matrices: all threads on D1_host, one thread on its first eighth.  plan_slices(n_matrices,
+    n_chunks) returns the GPU's (rail[:n_chunks], S, R, stats) of the first n_matrices matrices, to compare."""
+    nb = D1_host.shape[0]
+    c0 = time.perf_counter()
+    off, w, flow, _ = oracle.chunk_sort_batch(D1_host, M, N, C, want_perm=False)
+    rail, S = oracle.lpt_batch(off, w, nb, M, N)
+    _, R, stats = oracle.eval_batch(off, w, flow, rail, nb, M, N)
+    c1 = time.perf_counter()
+    n = int(off[-1])
+    g_rail, g_S, g_R, g_stats = plan_slices(nb, n)
+    same = bool(np.array_equal(g_rail, rail) and np.array_equal(g_S, S) and np.array_equal(g_R, R) and np.array_equal(g_stats, stats))
+    del w, flow, rail
+    n1 = max(nb // 8, 1)
+    allt = oracle.num_threads()
+    oracle.set_threads(1)
+    s0 = time.perf_counter()
+    off1, w1, flow1, _ = oracle.chunk_sort_batch(D1_host[:n1], M, N, C, want_perm=False)
+    rail1, _ = oracle.lpt_batch(off1, w1, n1, M, N)
+    oracle.eval_batch(off1, w1, flow1, rail1, n1, M, N)
+    s1 = time.perf_counter()
+    oracle.set_threads(allt)
+    return {"value": n / (c1 - c0), "unit": "chunks/s", "cores": allt, "kind": "oracle",
+            "sample": f"first {nb} matrices ({nb * M} instances, {n} chunks), stages 3-5, {c1 - c0:.2f} s",
+            "matches_gpu": same,
+            "single_thread": {"value": int(off1[-1]) / (s1 - s0), "unit": "chunks/s", "cores": 1,
+                              "sample": f"first {n1} matrices ({int(off1[-1])} chunks), {s1 - s0:.2f} s"}}
+
+
+# ------------------------------------------------------------------------------------------------ c1 / c2: resident logits
+def bench_resident(cfg, args, rs, W, torch, np):
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    cfg = W.get_config(args.config)
-    if cfg.kind == "flows":
-        return bench_flows(cfg, args, rs, W, torch, np)
-    if cfg.rows_per_layer * cfg.batch * cfg.E * 4 > 64 << 30:
-        return bench_streamed(cfg, args, rs, W, torch, np)
     topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes, cfg.rail_bw_Bps)
     B, G = cfg.batch, cfg.G
     rows = B * cfg.rows_per_layer
@@ -79,46 +254,39 @@ def main():
         logits[b * cfg.rows_per_layer:(b + 1) * cfg.rows_per_layer] = W.gen_logits(cfg, b, device=dev)
     eg_np = W.expert_gpu_table(cfg)
     expert_gpu = torch.from_numpy(eg_np).to(dev)
-
     if args.copy_probe:
-        probe = torch.empty(1 << 28, dtype=torch.float32, device=dev)
-        probe.copy_(logits.view(-1)[: 1 << 28])
-        torch.cuda.synchronize()
-        del probe
+        copy_probe(torch, dev)
 
     # ---- size the record arrays once (count query), then a plan that allocates nothing per step
     idx0 = rs.route_topk(logits, cfg.k)
     D10 = rs.traffic_matrix(idx0, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo)
-    total_chunks = int(rs.chunk_count(D10, topo)[-1].item())
+    total_chunks = rs.chunk_total(D10, topo)
     del idx0, D10
     plan = rs.Plan(topo, B, total_chunks, dev, rows=rows, k=cfg.k, want_perm=True)
-
     ws_rt = torch.empty(max(rs.route_traffic_workspace_bytes(B, cfg.tokens_per_gpu, cfg.E, cfg.k, topo), 256), dtype=torch.uint8, device=dev)
+    ws_tm = torch.empty(max(rs.traffic_matrix_workspace_bytes(B, cfg.tokens_per_gpu, cfg.k, topo), 256), dtype=torch.uint8, device=dev)
     names = {True: ("route_traffic", "schedule"),
              False: ("route_topk", "traffic_matrix", "chunk_sort", "lpt_spray", "eval")}
 
     def step(fused, events=None):
         marks = []
+
         def mark():
             if events is not None:
-                e = torch.cuda.Event(enable_timing=True)
-                e.record()
-                marks.append(e)
+                marks.append(_event(torch))
         mark()
         if fused:
             rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo,
                              out=(plan.topk_idx, plan.D1), ws=ws_rt); mark()
-        else:
-            rs.route_topk(logits, cfg.k, out=plan.topk_idx); mark()
-            rs.traffic_matrix(plan.topk_idx, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=plan.D1); mark()
-        if fused:
             plan.schedule_one_call(); mark()
         else:
+            rs.route_topk(logits, cfg.k, out=plan.topk_idx); mark()
+            rs.traffic_matrix(plan.topk_idx, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=plan.D1, ws=ws_tm); mark()
             rs.chunk_sort(plan.D1, topo, capacity=plan.capacity,
                           out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort); mark()
-            rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S)); mark()
+            rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S), capacity=plan.capacity); mark()
             rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.rail, plan.S, B, topo,
-                    out=(plan.R, plan.stats), ws=plan.ws_eval); mark()
+                    out=(plan.R, plan.stats), ws=plan.ws_eval, capacity=plan.capacity); mark()
         if events is not None:
             events.append(marks)
 
@@ -132,29 +300,29 @@ def main():
             step(fused, ev)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        ms = {n: 0.0 for n in names[fused]}
+        per = {n: [] for n in names[fused]}
+        whole = []
         for marks in ev:
             for i, n in enumerate(names[fused]):
-                ms[n] += marks[i].elapsed_time(marks[i + 1])
-        return (t1 - t0) * 1e3 / args.steps, {n: v / args.steps for n, v in ms.items()}
+                per[n].append(marks[i].elapsed_time(marks[i + 1]))
+            whole.append(marks[0].elapsed_time(marks[-1]))
+        return (t1 - t0) * 1e3 / args.steps, {n: _median(v) for n, v in per.items()}, _median(whole)
 
-    staged_ms_per_step, staged_ms = run(False)
+    staged_ms_per_step, staged_ms, staged_median = run(False)
     keep = ("topk_idx", "D1", "chunk_off", "chunk_w", "chunk_flow", "perm", "rail", "S", "R", "stats")
     staged_out = {n: getattr(plan, n).clone() for n in keep}
     for n in keep[2:]:
         getattr(plan, n).fill_(0)
-    ms_per_step, stage_ms = run(True)                # the timed region the headline value comes from
+    ms_per_step, stage_ms, step_median = run(True)   # the timed region the headline value comes from
     for n in keep:                                   # both ways give the same bytes
         m = total_chunks if n in ("chunk_w", "chunk_flow", "perm", "rail") else None
         assert torch.equal(staged_out[n][:m], getattr(plan, n)[:m]), n
     del staged_out
-
     assert int(plan.chunk_off[-1].item()) == total_chunks
 
     piped_ms = chunkwise_ms = graph_ms = None
     schemes = combine = sweep = placement = None
     stats = plan.stats.cpu().numpy()
-    ratio = stats[:, 0] / np.maximum(stats[:, 3], 1)
     if not args.skip_extras:
         # ---- supplementary: throughput with two steps in flight (two streams of default priority, outputs double-buffered):
         # the latency-bound stages 3-5 of one step run beside the bandwidth-bound stages 1-2 of the next
@@ -180,13 +348,14 @@ def main():
 
         # ---- supplementary: the same step replayed from a HIP graph (the library enqueues kernels only: no allocation,
         # no host synchronisation, no memset nodes), which takes the host's launch calls out of the step
-        want_g = [t.clone() for t in (plan.topk_idx, plan.D1, plan.chunk_off, plan.rail, plan.S, plan.R, plan.stats)]
+        outs = (plan.topk_idx, plan.D1, plan.chunk_off, plan.rail, plan.S, plan.R, plan.stats)
+        want_g = [t.clone() for t in outs]
         graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
         with torch.cuda.stream(side):
             with torch.cuda.graph(graph, stream=side):
                 step(True)
         torch.cuda.synchronize()
-        for t in (plan.topk_idx, plan.D1, plan.chunk_off, plan.rail, plan.S, plan.R, plan.stats):
+        for t in outs:
             t.zero_()
         for _ in range(max(args.warmup, 1)):
             graph.replay()
@@ -196,92 +365,75 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        assert all(torch.equal(a, b) for a, b in zip(want_g, (plan.topk_idx, plan.D1, plan.chunk_off, plan.rail, plan.S, plan.R, plan.stats)))
+        assert all(torch.equal(a, b) for a, b in zip(want_g, outs))
         del graph, want_g
 
-        # ---- supplementary: the plain per-chunk LPT kernel on the same records (same outputs, no closed-form periods)
-        rail2, S2 = torch.empty_like(plan.rail), torch.empty_like(plan.S)
-        cw = []
-        for i in range(3 + min(args.steps, 10)):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(rail2, S2), chunkwise=True)
-            e1.record()
-            cw.append((e0, e1))
-        torch.cuda.synchronize()
-        chunkwise_ms = sum(a.elapsed_time(b) for a, b in cw[3:]) / max(len(cw) - 3, 1)
-        assert torch.equal(rail2[:total_chunks], plan.rail[:total_chunks]) and torch.equal(S2, plan.S)
-        stats = plan.stats.cpu().numpy()
-        ratio = stats[:, 0] / np.maximum(stats[:, 3], 1)
+        chunkwise_ms = time_chunkwise(rs, torch, plan, B, topo, max(min(args.steps, 10), 3))
 
         # ---- supplementary: the comparison schemes on the same chunk records, and the second all-to-all (transposed traffic)
         def timed(fn):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            fn(); e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+            fn()
+            e0 = _event(torch); fn(); e1 = _event(torch)
+            torch.cuda.synchronize()
             return e0.elapsed_time(e1)
+        rail2, S2 = torch.empty_like(plan.rail), torch.empty_like(plan.S)
         R2, stats2 = torch.empty_like(plan.R), torch.empty_like(plan.stats)
-        schemes = {"lpt": {"makespan_over_lb_max": float(ratio.max()), "makespan_over_lb_mean": float(ratio.mean())}}
+        schemes = {"lpt": {"makespan_over_lb_" + k_: v for k_, v in ratio_stats(np, stats).items()}}
         for pol in ("nic_direct", "flow_hash", "random_spray", "round_robin"):
-            ms = timed(lambda: rs.assign_policy(pol, 1, plan.chunk_off, plan.chunk_w, plan.chunk_flow, B, topo, out=(rail2, S2)))
-            rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, rail2, S2, B, topo, out=(R2, stats2), ws=plan.ws_eval)
-            st2 = stats2.cpu().numpy()
-            r2 = st2[:, 0] / np.maximum(st2[:, 3], 1)
-            schemes[pol] = {"makespan_over_lb_max": float(r2.max()), "makespan_over_lb_mean": float(r2.mean()), "assign_ms": ms}
+            ms = timed(lambda: rs.assign_policy(pol, 1, plan.chunk_off, plan.chunk_w, plan.chunk_flow, B, topo, out=(rail2, S2),
+                                                capacity=plan.capacity))
+            rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, rail2, S2, B, topo, out=(R2, stats2), ws=plan.ws_eval, capacity=plan.capacity)
+            r2 = ratio_stats(np, stats2.cpu().numpy())
+            schemes[pol] = {"makespan_over_lb_max": r2["max"], "makespan_over_lb_mean": r2["mean"], "assign_ms": ms}
         D1T = torch.empty_like(plan.D1)
         tr_ms = timed(lambda: rs.transpose_matrix(plan.D1, topo, out=D1T))
-        n_comb = int(rs.chunk_count(D1T, topo, plan.ws_sort)[-1].item())
+        n_comb = rs.chunk_total(D1T, topo, plan.ws_sort)
         plan_c = rs.Plan(topo, B, n_comb, dev, want_perm=True)
         comb_ms = timed(lambda: plan_c.schedule_one_call(D1T))
-        st_c = plan_c.stats.cpu().numpy()
-        r_c = st_c[:, 0] / np.maximum(st_c[:, 3], 1)
-        combine = {"transpose_ms": tr_ms, "schedule_ms": comb_ms, "chunks": n_comb, "makespan_over_lb_max": float(r_c.max())}
+        combine = {"transpose_ms": tr_ms, "schedule_ms": comb_ms, "chunks": n_comb,
+                   "makespan_over_lb_max": ratio_stats(np, plan_c.stats.cpu().numpy())["max"]}
+        del plan_c
         # ---- chunk granularity (Theorem 4): the same traffic matrices cut at other chunk sizes
         sweep = []
         for cb in (16384, 65536, 262144, 1048576, 4194304):
             topo_g = rs.Topo(cfg.M, cfg.N, cb, cfg.rail_bw_Bps)
-            n_g = int(rs.chunk_count(plan.D1, topo_g)[-1].item())
+            n_g = rs.chunk_total(plan.D1, topo_g)
             plan_g = rs.Plan(topo_g, B, n_g, dev, want_perm=True)
             ms_g = timed(lambda: plan_g.schedule_one_call(plan.D1))
-            st_g, S_g = plan_g.stats.cpu().numpy(), plan_g.S.cpu().numpy().astype(np.float64)
-            mse = ((S_g - S_g.mean(axis=2, keepdims=True)) ** 2).mean(axis=2).max(axis=1)      # worst node of each matrix
-            wmax = np.maximum(st_g[:, 5], 1).astype(np.float64)
+            st_g, S_g = plan_g.stats.cpu().numpy(), plan_g.S.cpu().numpy()
+            wmax = np.maximum(st_g[:, 5], 1)
             sweep.append({"chunk_bytes": cb, "chunks": n_g, "schedule_ms": ms_g,
-                          "makespan_over_lb_max": float((st_g[:, 0] / np.maximum(st_g[:, 3], 1)).max()),
+                          "makespan_over_lb_max": ratio_stats(np, st_g)["max"],
                           "send_spread_over_wmax_max": float((st_g[:, 7] / wmax).max()),
-                          "mse_over_wmax2_max": float((mse / (wmax * wmax)).max())})
+                          "mse_over_wmax2_max": exact_mse_over_wmax2(S_g, st_g[:, 5])})
             del plan_g
         # ---- expert placement (Section 6.3, sparse against dense): the first R replica groups of the placement table only
         placement = []
         for R_ in sorted({1, 2, max(cfg.replicas // 2, 1), cfg.replicas}):
             eg_R = torch.from_numpy(np.ascontiguousarray(eg_np[:, :R_])).to(dev)
             _, D1_R = rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, eg_R, cfg.payload_bytes, topo, out=(plan.topk_idx, D1T), ws=ws_rt)
-            n_R = int(rs.chunk_count(D1_R, topo)[-1].item())
+            n_R = rs.chunk_total(D1_R, topo)
             plan_R = rs.Plan(topo, B, n_R, dev, want_perm=True)
             ms_R = timed(lambda: plan_R.schedule_one_call(D1_R))
             st_R = plan_R.stats.cpu().numpy()
             placement.append({"replicas": R_, "gpus_with_experts": R_ * (cfg.E // cfg.experts_per_gpu), "chunks": n_R, "schedule_ms": ms_R,
-                              "makespan_over_lb_max": float((st_R[:, 0] / np.maximum(st_R[:, 3], 1)).max()),
+                              "makespan_over_lb_max": ratio_stats(np, st_R)["max"],
                               "completion_time_us_max": float(st_R[:, 0].max() / cfg.rail_bw_Bps * 1e6)})
             del plan_R
-        rs.chunk_sort(plan.D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
+        # leave the plan holding this workload's own outputs again
+        rs.route_traffic(logits, cfg.k, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=(plan.topk_idx, plan.D1), ws=ws_rt)
+        plan.schedule_one_call()
+        torch.cuda.synchronize()
+        stats = plan.stats.cpu().numpy()
 
-    # ---- roofline of the dominant kernel (route_traffic streams the logits once and writes the indices once)
+    # ---- rooflines (route_traffic streams the logits once and writes the indices once)
     k1_bytes = rows * (4 * cfg.E + 4 * cfg.k)
     k2_bytes = rows * 4 * cfg.k + 8 * B * G * G
     rt_bytes = k1_bytes + 8 * B * G * G
-    rt_gbps = rt_bytes / (stage_ms["route_traffic"] * 1e-3) / 1e9
-    k1_gbps = k1_bytes / (staged_ms["route_topk"] * 1e-3) / 1e9
-    staged_routing_gbps = (k1_bytes + k2_bytes) / ((staged_ms["route_topk"] + staged_ms["traffic_matrix"]) * 1e-3) / 1e9
-    dominant = max(stage_ms, key=stage_ms.get)
-    # the per-chunk LPT kernel against the VALU issue rate: ceil(log2 N) cross-lane mins + add, compare, select and the
-    # shift that files the decision, per greedy step and wavefront (one instance per wavefront at this instance count);
-    # 256 CUs x 4 SIMDs issue one wave64 VALU instruction per 4 cycles at 2.4 GHz
-    gw = 4 if cfg.N <= 4 else 8 if cfg.N <= 8 else 16 if cfg.N <= 16 else 32 if cfg.N <= 32 else 64
-    ipw = 64 // gw if B * cfg.M >= 2048 * 64 // gw else 1
-    instr_per_step = gw.bit_length() - 1 + 5
-    valu_peak = 256 * 4 * 2.4e9 / 4 / 1e9            # G wave-instructions/s
-    lpt_rate = total_chunks / (staged_ms["lpt_spray"] * 1e-3)
-
+    sb = stage_bytes(total_chunks, B * cfg.M, topo, True)
+    rt_roof = hbm_roofline("route_traffic_kernel (with rt_reduce_kernel, the sum of its slice counts, in the same call)", cfg.name,
+                           rt_bytes, stage_ms["route_traffic"])
+    rt_roof["slowest_stage"] = max(stage_ms, key=stage_ms.get)
     out = {
         "metric": "LPT-sprayed chunks/s over the whole path (route_topk, traffic_matrix, chunk_sort, lpt_spray, eval; stages 1-2 and 3-5 fused into two calls)",
         "value": total_chunks / (ms_per_step * 1e-3),
@@ -293,38 +445,41 @@ def main():
         "config": {"workload": f"{cfg.name}: Mixtral-8x7B-shaped, M={cfg.M} nodes x N={cfg.N} rails, E={cfg.E} top-{cfg.k}, "
                                f"{cfg.tokens_per_gpu} tokens/GPU x {cfg.payload_bytes} B, C={cfg.chunk_bytes} B, {B} matrices of {G}x{G}",
                    "rows": rows, "chunks": total_chunks, "instances": B * cfg.M},
+        "timing": "ms_per_step = wall time of the K steps / K; stage_ms and median_step_ms = medians of per-step hipEvent times",
+        "median_step_ms": step_median,
         "stage_ms": stage_ms,
-        "staged": {"ms_per_step": staged_ms_per_step, "value": total_chunks / (staged_ms_per_step * 1e-3), "stage_ms": staged_ms,
+        "staged": {"ms_per_step": staged_ms_per_step, "median_step_ms": staged_median, "value": total_chunks / (staged_ms_per_step * 1e-3),
+                   "stage_ms": staged_ms,
                    "note": "the same step through the five separate calls (indices written, then read back)",
-                   "route_topk_GBps": k1_gbps, "routing_to_traffic_matrix_GBps": staged_routing_gbps},
+                   "stage_rooflines": {
+                       "route_topk": hbm_roofline("route_topk_kernel", cfg.name, k1_bytes, staged_ms["route_topk"]),
+                       "traffic_matrix": hbm_roofline("traffic_matrix_kernel (with the sum of its slice counts)", cfg.name, k2_bytes,
+                                                      staged_ms["traffic_matrix"]),
+                       **{n: hbm_roofline(STAGE_KERNEL[n], cfg.name, sb[n], staged_ms[n],
+                                          note="latency-bound at this size: a few tens of MB through dependent launches")
+                          for n in ("chunk_sort", "lpt_spray", "eval")}},
+                   "routing_to_traffic_matrix_GBps": (k1_bytes + k2_bytes) / ((staged_ms["route_topk"] + staged_ms["traffic_matrix"]) * 1e-3) / 1e9},
         "two_steps_in_flight": None if piped_ms is None else {
             "ms_per_step": piped_ms, "value": total_chunks / (piped_ms * 1e-3),
             "note": "same two calls per step, consecutive steps alternating between two streams and two sets of outputs"},
         "graph_replay": None if graph_ms is None else {
             "ms_per_step": graph_ms, "value": total_chunks / (graph_ms * 1e-3),
             "note": "the same two calls captured once into a HIP graph and replayed; outputs checked against the eager step"},
-        "routing_to_traffic_matrix_GBps": rt_gbps,
-        "routing_frac_of_hbm_peak": rt_gbps / HBM_PEAK_GBPS,
-        "lpt_spray_chunks_per_s": lpt_rate,
-        "lpt_roofline": None if chunkwise_ms is None else {
-            "kernel": "railsched_lpt_spray_chunkwise", "bound": "alu", "unit": "G wave-instr/s", "peak": valu_peak,
-            "achieved": total_chunks / ipw * instr_per_step / (chunkwise_ms * 1e-3) / 1e9,
-            "frac": total_chunks / ipw * instr_per_step / (chunkwise_ms * 1e-3) / 1e9 / valu_peak,
-            "note": f"{B * cfg.M} instances are {B * cfg.M // ipw} wavefronts on 1024 SIMDs: the latency of the serial chain "
-                    f"({instr_per_step} instructions per step), not the issue rate, bounds this workload"},
+        "routing_to_traffic_matrix_GBps": rt_roof["achieved"],
+        "routing_frac_of_hbm_peak": rt_roof["frac"],
+        "lpt_spray_chunks_per_s": None if chunkwise_ms is None else total_chunks / (chunkwise_ms * 1e-3),
+        "lpt_spray_runs_chunks_per_s": total_chunks / (staged_ms["lpt_spray"] * 1e-3),
+        "lpt_spray_note": "lpt_spray_chunks_per_s: railsched_lpt_spray_chunkwise, every chunk through the cross-lane argmin (the kernel "
+                          "lpt_roofline prices); lpt_spray_runs_chunks_per_s: railsched_lpt_spray, which assigns runs of equal weights in closed form",
+        "lpt_roofline": None if chunkwise_ms is None else lpt_alu_roofline(total_chunks, B * cfg.M, cfg.N, chunkwise_ms),
         "lpt_spray_chunkwise_ms": chunkwise_ms,
-        "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
+        "makespan_over_lower_bound": ratio_stats(np, stats),
         "schemes": schemes,
         "granularity_sweep": sweep,
         "placement_sweep": placement,
         "second_all_to_all": combine,
         "completion_time_us_max": float(stats[:, 0].max() / cfg.rail_bw_Bps * 1e6),
-        "roofline": {"kernel": "route_traffic_kernel (with rt_reduce_kernel, the sum of its slice counts, in the same call)",
-                     "bound": "hbm", "achieved": rt_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": rt_gbps / HBM_PEAK_GBPS,
-                     "traffic": ROUTE_TRAFFIC_C2_TRAFFIC_BYTES if cfg.name == "c2" else None,
-                     "algorithmic_bytes_per_launch": rt_bytes, "avg_launch_ms": stage_ms["route_traffic"],
-                     "slowest_stage": dominant},
+        "roofline": rt_roof,
     }
 
     # ---- CPU baseline: the oracle as it stands, on the first layers of the same workload
@@ -338,14 +493,13 @@ def main():
             D1c = oracle.traffic_matrix(idx, layers, cfg.tokens_per_gpu, eg_np, cfg.payload_bytes, cfg.M, cfg.N)
             off, w, flow, _ = oracle.chunk_sort_batch(D1c, cfg.M, cfg.N, cfg.chunk_bytes)
             rail, S = oracle.lpt_batch(off, w, layers, cfg.M, cfg.N)
-            _, R, stats = oracle.eval_batch(off, w, flow, rail, layers, cfg.M, cfg.N)
-            return off, rail, R, stats
+            _, R, stats_ = oracle.eval_batch(off, w, flow, rail, layers, cfg.M, cfg.N)
+            return off, rail, R, stats_
         c0 = time.perf_counter()
         off_c, rail_c, R_c, stats_c = cpu_path(x, L)
         c1 = time.perf_counter()
         n_c = int(off_c[-1])
-        # the same oracle on one thread, on the first quarter of the sample
-        L1 = max(L // 4, 1)
+        L1 = max(L // 4, 1)                          # the same oracle on one thread, on the first quarter of the sample
         all_threads = oracle.num_threads()
         oracle.set_threads(1)
         s0 = time.perf_counter()
@@ -360,171 +514,305 @@ def main():
                                          f"{c1 - c0:.2f} s", "matches_gpu": bool(same),
                                "single_thread": {"value": int(off_1[-1]) / (s1 - s0), "unit": "chunks/s", "cores": 1,
                                                  "sample": f"first {L1} layers, {s1 - s0:.2f} s"}}
-    print(json.dumps(out))
+    del logits, plan
+    return out
 
 
-def _events(torch):
-    e = torch.cuda.Event(enable_timing=True)
-    e.record()
-    return e
-
-
-def _stage_rooflines(total_chunks, n_inst, topo, ms, want_perm):
-    """GB/s of stages 3-5 on their algorithmic bytes: D1 read + 8 (12 with perm) B per chunk; 4 + 1 B; 9 B."""
-    NG = topo.rails * topo.G
-    by = {"chunk_sort": 8 * NG * n_inst + (12 if want_perm else 8) * total_chunks,
-          "lpt_spray": 5 * total_chunks, "eval": 9 * total_chunks}
-    return {n: {"GBps": by[n] / (ms[n] * 1e-3) / 1e9, "frac_of_hbm_peak": by[n] / (ms[n] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                "algorithmic_bytes": by[n]} for n in by}
-
-
-def _schedule_steps(rs, torch, plan, D1, topo, B, steps, warmup):
-    """Per-stage times of stages 3-5 through the three calls, and the time of railsched_schedule on the same input."""
-    names = ("chunk_sort", "lpt_spray", "eval")
-    ms = {n: 0.0 for n in names}
-    for it in range(warmup + steps):
-        e = [_events(torch)]
-        rs.chunk_sort(D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
-        e.append(_events(torch))
-        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S))
-        e.append(_events(torch))
-        rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.rail, plan.S, B, topo, out=(plan.R, plan.stats), ws=plan.ws_eval)
-        e.append(_events(torch))
-        torch.cuda.synchronize()
-        if it >= warmup:
-            for i, n in enumerate(names):
-                ms[n] += e[i].elapsed_time(e[i + 1]) / steps
-    small = [t.clone() for t in (plan.chunk_off, plan.S, plan.R, plan.stats)]
-    rail3 = plan.rail.clone()
-    for t in (plan.rail, plan.S, plan.R, plan.stats):
-        t.zero_()
-    one = 0.0
-    for it in range(warmup + steps):
-        e0 = _events(torch)
-        plan.schedule_one_call(D1)
-        e1 = _events(torch)
-        torch.cuda.synchronize()
-        if it >= warmup:
-            one += e0.elapsed_time(e1) / steps
-    assert all(torch.equal(a, b) for a, b in zip(small, (plan.chunk_off, plan.S, plan.R, plan.stats))) and torch.equal(rail3, plan.rail)
-    return ms, one
-
-
-def bench_flows(cfg, args, rs, W, torch, np):
-    """c3 / c5: no routing stage; a step is stages 3-5 over `--matrices` synthetic flow matrices resident in HBM."""
+# ------------------------------------------------------------------------------------------------ c3: resident flow matrices
+def bench_flows_resident(cfg, args, rs, W, torch, np):
+    """c3: no routing stage; a step is stages 3-5 over all matrices, resident in HBM."""
     dev = "cuda:0"
     topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes, cfg.rail_bw_Bps)
-    B = args.matrices if args.matrices > 0 else (cfg.batch if cfg.G <= 256 else 1)
-    want_perm = cfg.G <= 256                       # the permutation of a 3.9e9-chunk matrix is left out (16 GB more)
+    B = args.matrices if args.matrices > 0 else cfg.batch
     D1 = W.gen_flow_matrices_device(cfg, dev, first=0, count=B)
-    total = int(rs.chunk_count(D1, topo)[-1].item())
-    plan = rs.Plan(topo, B, total, dev, want_perm=want_perm)
-    steps, warmup = min(args.steps, 5), min(args.warmup, 2)
-    ms, one_ms = _schedule_steps(rs, torch, plan, D1, topo, B, steps, warmup)
-    step_ms = one_ms
+    if args.copy_probe:
+        copy_probe(torch, dev)
+    total = rs.chunk_total(D1, topo)
+    plan = rs.Plan(topo, B, total, dev, want_perm=True)
+    reps, warmup = max(min(args.steps, 10), 3), min(args.warmup, 2)
+    ms, one_ms = time_stages_3_5(rs, torch, plan, D1, topo, B, reps, warmup)
     st = plan.stats.cpu().numpy()
-    ratio = st[:, 0] / np.maximum(st[:, 3], 1)
-    per_chunk = None
-    if not args.skip_extras:
-        # the per-chunk kernel (every chunk through the cross-lane argmin) on the same records, against the VALU issue rate
-        rail2, S2 = torch.empty_like(plan.rail), torch.empty_like(plan.S)
-        t = []
-        for _ in range(3):
-            e0, e1 = _events(torch), None
-            rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(rail2, S2), chunkwise=True)
-            e1 = _events(torch)
-            torch.cuda.synchronize()
-            t.append(e0.elapsed_time(e1))
-        assert torch.equal(rail2, plan.rail) and torch.equal(S2, plan.S)
-        del rail2, S2
-        gw = 4 if cfg.N <= 4 else 8 if cfg.N <= 8 else 16 if cfg.N <= 16 else 32 if cfg.N <= 32 else 64
-        ipw = 64 // gw if B * cfg.M >= 2048 * 64 // gw else 1                      # instances per wavefront (packed or wide shape)
-        instr = (gw.bit_length() - 1) + (4 if ipw > 1 else 5)                     # cross-lane mins + add, compare, select, decision filed (+ weight broadcast)
-        valu_peak = 256 * 4 * 2.4e9 / 4
-        per_chunk = {"ms": min(t[1:]), "chunks_per_s": total / (min(t[1:]) * 1e-3), "instances_per_wavefront": ipw,
-                     "roofline": {"bound": "alu", "unit": "G wave-instr/s", "peak": valu_peak / 1e9,
-                                  "achieved": total / ipw * instr / (min(t[1:]) * 1e-3) / 1e9,
-                                  "frac": total / ipw * instr / (min(t[1:]) * 1e-3) / valu_peak,
-                                  "note": f"{instr} VALU instructions per greedy step and wavefront, {ipw} instance(s) per wavefront; "
-                                          "256 CUs x 4 SIMDs x 2.4 GHz / 4 clocks per wave64 instruction"}}
-    roof = _stage_rooflines(total, B * cfg.M, topo, ms, want_perm)
-    one_bytes = 8 * topo.rails * topo.G * B * cfg.M + (13 if want_perm else 9) * total
-    slow = max(ms, key=ms.get)
-    print(json.dumps({
+    n_inst = B * cfg.M
+    sb = stage_bytes(total, n_inst, topo, True)
+    chunkwise_ms = None if args.skip_extras else time_chunkwise(rs, torch, plan, B, topo, 3)
+    rec = {
         "metric": "LPT-sprayed chunks/s over stages 3-5 (chunk_sort, lpt_spray, eval, in one call); the workload has no routing stage",
-        "value": total / (step_ms * 1e-3), "unit": "chunks/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": total / (one_ms * 1e-3), "unit": "chunks/s", "n_gpus": 1, "steps": reps, "warmup": warmup,
+        "ms_per_step": one_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int64 loads / uint32 weights", "data": "synthetic (seeded lognormal flow matrices)",
         "config": {"workload": f"{cfg.name}: M={cfg.M} nodes x N={cfg.N} rails, {B} of {cfg.batch} matrices of {cfg.G}x{cfg.G}, "
-                               f"C={cfg.chunk_bytes} B, p_zero={cfg.p_zero}", "chunks": total, "instances": B * cfg.M, "perm": want_perm},
-        "timing": "event time of railsched_schedule (stages 3-5 in one call); the three separate calls under `staged`",
+                               f"C={cfg.chunk_bytes} B, p_zero={cfg.p_zero}", "chunks": total, "instances": n_inst, "perm": True},
+        "timing": "medians of hipEvent times: railsched_schedule (stages 3-5 in one call) is the step; the three separate calls under `staged`",
         "stage_ms": {"schedule": one_ms},
-        "staged": {"ms_per_step": sum(ms.values()), "stage_ms": ms, "stage_rooflines": roof},
-        "lpt_spray_chunks_per_s": total / (ms["lpt_spray"] * 1e-3),
-        "lpt_spray_per_chunk_kernel": per_chunk,
-        "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
-        "roofline": {"kernel": "railsched_schedule (cs_fill_kernel dominates: records and leading-run rails written once)",
-                     "bound": "hbm", "achieved": one_bytes / (one_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": one_bytes / (one_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
-                     "algorithmic_bytes_per_launch": one_bytes},
-    }))
+        "staged": {"ms_per_step": sum(ms.values()), "stage_ms": ms,
+                   "stage_rooflines": {n: hbm_roofline(STAGE_KERNEL[n], cfg.name, sb[n], ms[n]) for n in ms}},
+        "lpt_spray_chunks_per_s": None if chunkwise_ms is None else total / (chunkwise_ms * 1e-3),
+        "lpt_spray_runs_chunks_per_s": total / (ms["lpt_spray"] * 1e-3),
+        "lpt_roofline": None if chunkwise_ms is None else lpt_alu_roofline(total, n_inst, cfg.N, chunkwise_ms),
+        "lpt_spray_chunkwise_ms": chunkwise_ms,
+        "makespan_over_lower_bound": ratio_stats(np, st),
+        "roofline": hbm_roofline(STAGE_KERNEL["schedule"], cfg.name, sb["schedule"], one_ms),
+    }
+    if args.cpu_layers != 0:
+        import oracle
+        nb = min(B, 128)
+        off_g = plan.chunk_off.cpu().numpy()
+
+        def slices(nm, n):
+            assert int(off_g[nm * cfg.M]) == n
+            return plan.rail[:n].cpu().numpy(), plan.S[:nm].cpu().numpy(), plan.R[:nm].cpu().numpy(), plan.stats[:nm].cpu().numpy()
+        rec["cpu_baseline"] = cpu_stages_3_5(oracle, np, D1[:nb].cpu().numpy(), cfg.M, cfg.N, cfg.chunk_bytes, slices)
+    del D1, plan
+    return rec
 
 
-def bench_streamed(cfg, args, rs, W, torch, np):
-    """c4: the logits of all layers do not fit beside the records, so each layer's logits are generated into one
-    buffer (untimed), stages 1-2 are timed per layer, and stages 3-5 run once over all matrices."""
+# ------------------------------------------------------------------------------------------------ c5: one matrix resident at a time
+def bench_flows_streamed(cfg, args, rs, W, torch, np):
+    """c5: every matrix is ~3.9e9 chunks (35 GB of records), so the matrices go through one at a time: each is generated on
+    the device (untimed), then stages 3-5 run on it through railsched_schedule (timed).  Matrix 0 also gets the repeated
+    measurement of the three separate calls and of the per-chunk LPT kernel."""
     dev = "cuda:0"
     topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes, cfg.rail_bw_Bps)
-    B, G = cfg.batch, cfg.G
-    expert_gpu = torch.from_numpy(W.expert_gpu_table(cfg)).to(dev)
+    B = args.matrices if args.matrices > 0 else cfg.batch
+    n_inst = cfg.M
+    per_matrix, chunks, ratios = [], [], []
+    first = None
+    plan = None
+    for b in range(B):
+        D1 = W.gen_flow_matrices_device(cfg, dev, first=b, count=1)
+        total = rs.chunk_total(D1, topo)
+        if plan is None or plan.capacity < total:
+            plan = None
+            torch.cuda.empty_cache()
+            plan = rs.Plan(topo, 1, total + total // 8, dev, want_perm=False)   # room for the larger matrices to come
+        if b == 0:
+            if args.copy_probe:
+                copy_probe(torch, dev)
+            reps, warmup = max(min(args.steps, 10), 3), 1
+            ms, one_ms = time_stages_3_5(rs, torch, plan, D1, topo, 1, reps, warmup)
+            chunkwise_ms = None if args.skip_extras else time_chunkwise(rs, torch, plan, 1, topo, 2)
+            sb = stage_bytes(total, n_inst, topo, False)
+            first = {"chunks": total, "stage_ms": {"schedule": one_ms}, "reps": reps,
+                     "staged": {"ms_per_step": sum(ms.values()), "stage_ms": ms,
+                                "stage_rooflines": {n: hbm_roofline(STAGE_KERNEL[n], cfg.name, sb[n], ms[n]) for n in ms}},
+                     "lpt_spray_chunks_per_s": None if chunkwise_ms is None else total / (chunkwise_ms * 1e-3),
+                     "lpt_spray_runs_chunks_per_s": total / (ms["lpt_spray"] * 1e-3),
+                     "lpt_roofline": None if chunkwise_ms is None else lpt_alu_roofline(total, n_inst, cfg.N, chunkwise_ms),
+                     "lpt_spray_chunkwise_ms": chunkwise_ms,
+                     "roofline": hbm_roofline(STAGE_KERNEL["schedule"], cfg.name, sb["schedule"], one_ms)}
+            if args.cpu_layers != 0:
+                import oracle
+                D1_h = D1[0].cpu().numpy()
+                c0 = time.perf_counter()
+                off_c, S_c, R_c, stats_c = oracle.schedule_matrix_by_node(D1_h, cfg.M, cfg.N, cfg.chunk_bytes)
+                c1 = time.perf_counter()
+                same = bool(np.array_equal(plan.chunk_off.cpu().numpy(), off_c) and np.array_equal(plan.S[0].cpu().numpy(), S_c)
+                            and np.array_equal(plan.R[0].cpu().numpy(), R_c) and np.array_equal(plan.stats[0].cpu().numpy(), stats_c))
+                sizes = np.diff(off_c)
+                k1 = int(np.argsort(sizes)[len(sizes) // 2])             # one thread: the median instance
+                s0 = time.perf_counter()
+                cw, cf = oracle.chunk_split(D1_h, cfg.M, cfg.N, cfg.chunk_bytes, k1)
+                sw, sf, _ = oracle.sort_desc(cw, cf)
+                oracle.lpt(sw, cfg.N)
+                s1 = time.perf_counter()
+                first["cpu_baseline"] = {"value": int(off_c[-1]) / (c1 - c0), "unit": "chunks/s", "cores": oracle.num_threads(), "kind": "oracle",
+                                         "sample": f"matrix 0 of {cfg.batch} (all {cfg.M} instances, {int(off_c[-1])} chunks), stages 3-5 one node "
+                                                   f"at a time, {c1 - c0:.2f} s", "matches_gpu": same,
+                                         "single_thread": {"value": int(sizes[k1]) / (s1 - s0), "unit": "chunks/s", "cores": 1,
+                                                           "sample": f"the median instance ({int(sizes[k1])} chunks), split + sort + LPT, "
+                                                                     f"{s1 - s0:.2f} s"}}
+                del D1_h, cw, cf, sw, sf
+        e0 = _event(torch)
+        plan.schedule_one_call(D1)
+        e1 = _event(torch)
+        torch.cuda.synchronize()
+        per_matrix.append(e0.elapsed_time(e1))
+        chunks.append(total)
+        st = plan.stats.cpu().numpy()
+        assert int(st[0, 6]) == total and int(st[0, 0]) >= int(st[0, 3]) > 0
+        ratios.append(st[0, 0] / st[0, 3])
+        del D1
+    step_ms = sum(per_matrix)
+    total_all = sum(chunks)
+    sb_all = 8 * topo.rails * topo.G * n_inst * B + 9 * total_all
+    rec = {
+        "metric": "LPT-sprayed chunks/s over stages 3-5 (chunk_sort, lpt_spray, eval, in one call); the workload has no routing stage",
+        "value": total_all / (step_ms * 1e-3), "unit": "chunks/s", "n_gpus": 1, "steps": 1, "warmup": 0,
+        "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64 loads / uint32 weights", "data": "synthetic (seeded lognormal flow matrices)",
+        "config": {"workload": f"{cfg.name}: M={cfg.M} nodes x N={cfg.N} rails, {B} of {cfg.batch} matrices of {cfg.G}x{cfg.G}, one resident at a "
+                               f"time, C={cfg.chunk_bytes} B, p_zero={cfg.p_zero}", "chunks": total_all, "instances": n_inst * B, "perm": False},
+        "timing": "sum over the matrices of the hipEvent time of railsched_schedule on each (generated on the device between the calls, untimed)",
+        "per_matrix_ms": {"median": _median(per_matrix), "min": min(per_matrix), "max": max(per_matrix)},
+        "chunks_per_matrix": {"median": _median(chunks), "min": min(chunks), "max": max(chunks)},
+        "makespan_over_lower_bound": {"max": float(max(ratios)), "mean": float(sum(ratios) / len(ratios))},
+        "roofline": hbm_roofline(STAGE_KERNEL["schedule"], cfg.name, sb_all / B, step_ms / B,
+                                 note="average over the matrices: algorithmic bytes and time per matrix"),
+        "matrix_0": first,
+    }
+    if first and "cpu_baseline" in first:
+        rec["cpu_baseline"] = first["cpu_baseline"]
+    del plan
+    return rec
+
+
+# ------------------------------------------------------------------------------------------------ c4: logits streamed layer by layer
+def bench_streamed(cfg, args, rs, W, torch, np):
+    """c4: 244 GiB of logits in all, so each layer's 4 GiB is generated into HBM (untimed), stages 1-2 are timed on it,
+    and stages 3-5 run once over the 61 matrices."""
+    dev = "cuda:0"
+    topo = rs.Topo(cfg.M, cfg.N, cfg.chunk_bytes, cfg.rail_bw_Bps)
+    B, G = (args.layers if args.layers > 0 else cfg.batch), cfg.G
+    eg_np = W.expert_gpu_table(cfg)
+    expert_gpu = torch.from_numpy(eg_np).to(dev)
     D1 = torch.empty((B, G, G), dtype=torch.int64, device=dev)
     idx = torch.empty((cfg.rows_per_layer, cfg.k), dtype=torch.int32, device=dev)
-    t1 = t2 = 0.0
+    ws_tm = torch.empty(max(rs.traffic_matrix_workspace_bytes(1, cfg.tokens_per_gpu, cfg.k, topo), 256), dtype=torch.uint8, device=dev)
+    ws_rt = torch.empty(max(rs.route_traffic_workspace_bytes(1, cfg.tokens_per_gpu, cfg.E, cfg.k, topo), 256), dtype=torch.uint8, device=dev)
+    D1_one = torch.empty((1, G, G), dtype=torch.int64, device=dev)
+    idx_one = torch.empty_like(idx)
+    t1, t2, t12 = [], [], []
+    keep_logits = []
     for b in range(B):
         lg = W.gen_logits(cfg, b, device=dev)
         if b == 0:
-            rs.route_topk(lg, cfg.k, out=idx)           # warm-up launch
-        e0 = _events(torch)
+            if args.copy_probe:
+                copy_probe(torch, dev)
+            rs.route_topk(lg, cfg.k, out=idx)           # warm-up launches
+            rs.route_traffic(lg, cfg.k, 1, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=(idx_one, D1_one), ws=ws_rt)
+        e0 = _event(torch)
         rs.route_topk(lg, cfg.k, out=idx)
-        e1 = _events(torch)
-        rs.traffic_matrix(idx, 1, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=D1[b:b + 1])
-        e2 = _events(torch)
+        e1 = _event(torch)
+        rs.traffic_matrix(idx, 1, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=D1[b:b + 1], ws=ws_tm)
+        e2 = _event(torch)
+        rs.route_traffic(lg, cfg.k, 1, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=(idx_one, D1_one), ws=ws_rt)
+        e3 = _event(torch)
         torch.cuda.synchronize()
-        t1 += e0.elapsed_time(e1)
-        t2 += e1.elapsed_time(e2)
+        t1.append(e0.elapsed_time(e1)); t2.append(e1.elapsed_time(e2)); t12.append(e2.elapsed_time(e3))
+        assert torch.equal(D1_one[0], D1[b]) and torch.equal(idx_one, idx)
+        if b < 2 and args.cpu_layers != 0:
+            keep_logits.append(lg.cpu().numpy())
         del lg
-    del idx
-    total = int(rs.chunk_count(D1, topo)[-1].item())
+    del idx, idx_one, D1_one
+    total = rs.chunk_total(D1, topo)
     plan = rs.Plan(topo, B, total, dev, want_perm=True)
-    steps, warmup = min(args.steps, 5), min(args.warmup, 2)
-    ms3, one_ms = _schedule_steps(rs, torch, plan, D1, topo, B, steps, warmup)
-    ms = {"route_topk": t1, "traffic_matrix": t2, "schedule": one_ms}
+    reps, warmup = max(min(args.steps, 10), 3), min(args.warmup, 2)
+    ms3, one_ms = time_stages_3_5(rs, torch, plan, D1, topo, B, reps, warmup)
+    chunkwise_ms = None if args.skip_extras else time_chunkwise(rs, torch, plan, B, topo, 3)
+    ms = {"route_traffic": sum(t12), "schedule": one_ms}
     step_ms = sum(ms.values())
     rows = B * cfg.rows_per_layer
-    k1_bytes = rows * (4 * cfg.E + 4 * cfg.k)
-    k2_bytes = rows * 4 * cfg.k + 8 * B * G * G
+    k1_bytes = cfg.rows_per_layer * (4 * cfg.E + 4 * cfg.k)             # per layer = per launch
+    k2_bytes = cfg.rows_per_layer * 4 * cfg.k + 8 * G * G
+    rt_bytes = k1_bytes + 8 * G * G
     st = plan.stats.cpu().numpy()
-    ratio = st[:, 0] / np.maximum(st[:, 3], 1)
-    k1_gbps = k1_bytes / (t1 * 1e-3) / 1e9
-    print(json.dumps({
-        "metric": "LPT-sprayed chunks/s over the whole path (route_topk, traffic_matrix, chunk_sort, lpt_spray, eval)",
+    n_inst = B * cfg.M
+    sb = stage_bytes(total, n_inst, topo, True)
+    rec = {
+        "metric": "LPT-sprayed chunks/s over the whole path (route_topk, traffic_matrix, chunk_sort, lpt_spray, eval; stages 1-2 and 3-5 fused into two calls)",
         "value": total / (step_ms * 1e-3), "unit": "chunks/s", "n_gpus": 1, "steps": 1, "warmup": 1,
         "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int64 loads / uint32 weights / fp32 compare-only", "data": "synthetic (seeded counter-based logits, Zipf expert bias)",
-        "config": {"workload": f"{cfg.name}: M={cfg.M} nodes x N={cfg.N} rails, E={cfg.E} top-{cfg.k}, {cfg.tokens_per_gpu} tokens/GPU x "
-                               f"{cfg.payload_bytes} B, C={cfg.chunk_bytes} B, {B} matrices of {G}x{G}", "rows": rows, "chunks": total,
-                   "instances": B * cfg.M},
-        "timing": "sum of event times: stages 1-2 once per layer (logits regenerated between layers, untimed), stages 3-5 (one call) averaged over steps",
-        "stage_ms": ms, "staged": {"stage_ms": ms3, "stage_rooflines": _stage_rooflines(total, B * cfg.M, topo, ms3, True)},
-        "routing_to_traffic_matrix_GBps": (k1_bytes + k2_bytes) / ((t1 + t2) * 1e-3) / 1e9,
-        "makespan_over_lower_bound": {"max": float(ratio.max()), "mean": float(ratio.mean())},
-        "roofline": {"kernel": "route_topk_merge_kernel", "bound": "hbm", "achieved": k1_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": k1_gbps / HBM_PEAK_GBPS, "traffic": None, "algorithmic_bytes_per_launch": k1_bytes // B,
-                     "avg_launch_ms": t1 / B,
-                     "note": "for E = 256, k = 8 the kernel issues 925 VALU instructions per wavefront of 8 rows: "
-                             "rows/8 x 925 x 4 clocks / (1024 SIMDs x 2.4 GHz) is within a few percent of the launch time, "
-                             "so it is bound by VALU issue as much as by HBM"},
-    }))
+        "config": {"workload": f"{cfg.name}: DeepSeek-V3-shaped, M={cfg.M} nodes x N={cfg.N} rails, E={cfg.E} top-{cfg.k}, {cfg.tokens_per_gpu} "
+                               f"tokens/GPU x {cfg.payload_bytes} B, C={cfg.chunk_bytes} B, {B} of {cfg.batch} matrices of {G}x{G}", "rows": rows,
+                   "chunks": total, "instances": n_inst},
+        "timing": "sum of hipEvent times: railsched_route_traffic once per layer (logits regenerated between layers, untimed), "
+                  "railsched_schedule over all matrices (median of the repetitions)",
+        "stage_ms": ms,
+        "per_layer_ms": {"route_traffic": _median(t12), "route_topk": _median(t1), "traffic_matrix": _median(t2)},
+        "staged": {"ms_per_step": sum(t1) + sum(t2) + sum(ms3.values()),
+                   "stage_ms": {"route_topk": sum(t1), "traffic_matrix": sum(t2), **ms3},
+                   "stage_rooflines": {
+                       "route_topk": hbm_roofline("route_topk_insert_kernel", cfg.name, k1_bytes, _median(t1)),
+                       "traffic_matrix": hbm_roofline("traffic_matrix_kernel (with the sum of its slice counts)", cfg.name, k2_bytes, _median(t2)),
+                       **{n: hbm_roofline(STAGE_KERNEL[n], cfg.name, sb[n], ms3[n]) for n in ms3}},
+                   "routing_to_traffic_matrix_GBps": (k1_bytes + k2_bytes) / ((_median(t1) + _median(t2)) * 1e-3) / 1e9},
+        "routing_to_traffic_matrix_GBps": rt_bytes / (_median(t12) * 1e-3) / 1e9,
+        "routing_frac_of_hbm_peak": rt_bytes / (_median(t12) * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "schedule_roofline": hbm_roofline(STAGE_KERNEL["schedule"], cfg.name, sb["schedule"], one_ms),
+        "lpt_spray_chunks_per_s": None if chunkwise_ms is None else total / (chunkwise_ms * 1e-3),
+        "lpt_spray_runs_chunks_per_s": total / (ms3["lpt_spray"] * 1e-3),
+        "lpt_roofline": None if chunkwise_ms is None else lpt_alu_roofline(total, n_inst, cfg.N, chunkwise_ms),
+        "lpt_spray_chunkwise_ms": chunkwise_ms,
+        "makespan_over_lower_bound": ratio_stats(np, st),
+        "roofline": hbm_roofline("route_topk_insert_kernel (railsched_route_traffic on one layer)", cfg.name, rt_bytes, _median(t12),
+                                 note="per layer: median over the layers"),
+    }
+    if keep_logits:
+        import oracle
+        x = np.concatenate(keep_logits)
+        L = len(keep_logits)
+        keep_logits.clear()
+        c0 = time.perf_counter()
+        idx_c = oracle.route_topk(x, cfg.k)
+        ctop = time.perf_counter()
+        D1c = oracle.traffic_matrix(idx_c, L, cfg.tokens_per_gpu, eg_np, cfg.payload_bytes, cfg.M, cfg.N)
+        off, w, flow, _ = oracle.chunk_sort_batch(D1c, cfg.M, cfg.N, cfg.chunk_bytes, want_perm=False)
+        rail, S = oracle.lpt_batch(off, w, L, cfg.M, cfg.N)
+        _, R, stats_c = oracle.eval_batch(off, w, flow, rail, L, cfg.M, cfg.N)
+        c1 = time.perf_counter()
+        n_c = int(off[-1])
+        same = bool(np.array_equal(D1[:L].cpu().numpy(), D1c) and np.array_equal(plan.rail[:n_c].cpu().numpy(), rail)
+                    and np.array_equal(plan.S[:L].cpu().numpy(), S) and np.array_equal(plan.R[:L].cpu().numpy(), R)
+                    and np.array_equal(plan.stats[:L].cpu().numpy(), stats_c))
+        r1 = cfg.rows_per_layer // 16                                    # one thread: stage 1 on a sixteenth of a layer
+        allt = oracle.num_threads()
+        oracle.set_threads(1)
+        s0 = time.perf_counter()
+        oracle.route_topk(x[:r1], cfg.k)
+        s1 = time.perf_counter()
+        oracle.set_threads(allt)
+        rec["cpu_baseline"] = {"value": n_c / (c1 - c0), "unit": "chunks/s", "cores": allt, "kind": "oracle",
+                               "sample": f"first {L} of {cfg.batch} layers ({L * cfg.rows_per_layer} rows, {n_c} chunks), whole path, "
+                                         f"{c1 - c0:.2f} s, of which stage 1 {ctop - c0:.2f} s", "matches_gpu": same,
+                               "single_thread": {"value": r1 / (s1 - s0), "unit": "rows/s", "cores": 1,
+                                                 "sample": f"stage 1 (top-{cfg.k} of {cfg.E}) on {r1} rows, {s1 - s0:.2f} s"}}
+        del x
+    del D1, plan
+    return rec
+
+
+def run_config(name, args, rs, W, torch, np):
+    cfg = W.get_config(name)
+    if cfg.kind == "flows":
+        return bench_flows_resident(cfg, args, rs, W, torch, np) if cfg.G <= 256 else bench_flows_streamed(cfg, args, rs, W, torch, np)
+    if cfg.rows_per_layer * cfg.batch * cfg.E * 4 > 64 << 30:
+        return bench_streamed(cfg, args, rs, W, torch, np)
+    return bench_resident(cfg, args, rs, W, torch, np)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the rails and the other GPUs are simulated "
+              "arithmetically); --gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import gc
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2510_19262_amd as rs
+
+    rs.load()                                       # fails loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    if args.config != "all":
+        print(json.dumps(run_config(args.config, args, rs, W, torch, np)))
+        return
+    out = run_config("c2", args, rs, W, torch, np)
+    out["workloads"] = {}
+    for name in ("c3", "c4", "c5"):
+        gc.collect()
+        torch.cuda.empty_cache()
+        t0 = time.perf_counter()
+        try:
+            rec = run_config(name, args, rs, W, torch, np)
+        except Exception as exc:                    # the headline stands on its own: a sub-record that fails says so
+            rec = {"error": f"{type(exc).__name__}: {exc}"}
+        rec["wall_s"] = time.perf_counter() - t0
+        out["workloads"][name] = rec
+        print(f"bench: {name} done in {rec['wall_s']:.1f} s", file=sys.stderr, flush=True)
+    print(json.dumps(out))
 
 
 if __name__ == "__main__":
