@@ -163,10 +163,16 @@ int railsched_chunk_sort(const int64_t *D1, int32_t batch, const railsched_topo_
  *   rail      [capacity] uint8, values in [0,N)            (out; the first chunk_off[batch*M] are written)
  *   S         [batch][M][N] int64                          (out; every entry -1 if chunk_off[batch*M] > capacity,
  *                                                           and then chunk_w is not read and rail not written)
- * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (N > 64).
+ *   ws        optional (NULL, 0 = none): railsched_lpt_spray_workspace_bytes(batch, topo) bytes, 256-byte aligned.
+ *             Instances are independent (Sections 1 and 3.2), so the order they are worked on is free: with a
+ *             workspace, batches of thousands of instances are taken longest chain first from a queue, which evens
+ *             out the load of the SIMDs; the outputs do not depend on it.
+ * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (N > 64), WORKSPACE (ws given but misaligned or too small).
  * ------------------------------------------------------------------------------------------- */
+size_t railsched_lpt_spray_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo);
 int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
-                        const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S, void *stream);
+                        const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S, void *ws,
+                        size_t ws_bytes, void *stream);
 
 /* Same function, same arguments, same outputs bit for bit (Algorithm 2 step 3), but every single chunk
  * goes through the cross-lane argmin; railsched_lpt_spray above additionally assigns whole periods of
@@ -174,7 +180,8 @@ int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32
  * bound L_max <= L_opt + w_max of the Theorem 4 proof is what makes that state the common one).
  * Kept as the plain reference kernel for measurements and cross-checks. */
 int railsched_lpt_spray_chunkwise(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
-                                  const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S, void *stream);
+                                  const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S, void *ws,
+                                  size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Stage 5 - load evaluation (Section 4.1 load matrices S and R; Theorem 2; Theorem 3).

@@ -22,7 +22,8 @@ EXPORTS = (
     "railsched_version", "railsched_strerror", "railsched_check_capacity", "railsched_route_topk",
     "railsched_traffic_matrix_workspace_bytes", "railsched_traffic_matrix",
     "railsched_route_traffic_workspace_bytes", "railsched_route_traffic",
-    "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray", "railsched_lpt_spray_chunkwise",
+    "railsched_chunk_sort_workspace_bytes", "railsched_chunk_sort", "railsched_lpt_spray_workspace_bytes", "railsched_lpt_spray",
+    "railsched_lpt_spray_chunkwise",
     "railsched_eval_workspace_bytes", "railsched_eval", "railsched_schedule_workspace_bytes", "railsched_schedule", "railsched_schedule_static", "railsched_transpose_matrix", "railsched_assign_policy",
     "railsched_port_round_robin_workspace_bytes", "railsched_port_round_robin",
 )
@@ -85,8 +86,10 @@ def load():
     lib.railsched_chunk_sort_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_chunk_sort_workspace_bytes.restype = SZ
     lib.railsched_chunk_sort.argtypes = [P, I32, TP, P, P, P, P, I64, P, SZ, P]
-    lib.railsched_lpt_spray.argtypes = [P, P, I32, TP, I64, P, P, P]
-    lib.railsched_lpt_spray_chunkwise.argtypes = [P, P, I32, TP, I64, P, P, P]
+    lib.railsched_lpt_spray_workspace_bytes.argtypes = [I32, TP]
+    lib.railsched_lpt_spray_workspace_bytes.restype = SZ
+    lib.railsched_lpt_spray.argtypes = [P, P, I32, TP, I64, P, P, P, SZ, P]
+    lib.railsched_lpt_spray_chunkwise.argtypes = [P, P, I32, TP, I64, P, P, P, SZ, P]
     lib.railsched_eval_workspace_bytes.argtypes = [I32, TP]
     lib.railsched_eval_workspace_bytes.restype = SZ
     lib.railsched_eval.argtypes = [P, P, P, P, P, I32, TP, I64, P, P, P, SZ, P]
@@ -297,11 +300,17 @@ def chunk_sort(D1: torch.Tensor, topo: Topo, want_perm: bool = True, capacity: O
 
 
 # ---------------------------------------------------------------------------------- stage 4
+def lpt_spray_workspace_bytes(batch: int, topo: Topo) -> int:
+    t = topo.c()
+    return int(load().railsched_lpt_spray_workspace_bytes(batch, C.byref(t)))
+
+
 def lpt_spray(chunk_off: torch.Tensor, chunk_w: torch.Tensor, batch: int, topo: Topo, out=None, chunkwise: bool = False,
-              capacity: Optional[int] = None):
+              capacity: Optional[int] = None, ws="auto"):
     """Greedy least-loaded-rail assignment per instance -> (rail uint8 [capacity], S int64 [batch][M][N]).
     chunkwise=True calls railsched_lpt_spray_chunkwise (same result, no closed-form periods).
-    capacity = records chunk_w and rail hold (default: the length of chunk_w)."""
+    capacity = records chunk_w and rail hold (default: the length of chunk_w).
+    ws: workspace tensor, None for none, "auto" to allocate one here (instances are then taken longest first)."""
     _dev(chunk_off, torch.int64, "chunk_off")
     if chunk_w.dtype not in (torch.int32, torch.uint32):
         raise ValueError("chunk_w must be a 32-bit integer tensor")
@@ -315,8 +324,11 @@ def lpt_spray(chunk_off: torch.Tensor, chunk_w: torch.Tensor, batch: int, topo: 
     if min(chunk_w.numel(), rail.numel()) < capacity:
         raise ValueError("chunk_w and rail must hold `capacity` records")
     t = topo.c()
+    if isinstance(ws, str):
+        ws = _ws(lpt_spray_workspace_bytes(batch, topo), chunk_off.device)
     fn = load().railsched_lpt_spray_chunkwise if chunkwise else load().railsched_lpt_spray
-    _check(fn(_ptr(chunk_off), _ptr(chunk_w), batch, C.byref(t), capacity, _ptr(rail), _ptr(S), _stream()), "railsched_lpt_spray")
+    _check(fn(_ptr(chunk_off), _ptr(chunk_w), batch, C.byref(t), capacity, _ptr(rail), _ptr(S), _ptr(ws),
+              0 if ws is None else ws.numel(), _stream()), "railsched_lpt_spray")
     return rail, S
 
 
@@ -438,6 +450,7 @@ class Plan:
         self.ws_sort = _ws(chunk_sort_workspace_bytes(batch, topo), device)
         self.ws_eval = _ws(eval_workspace_bytes(batch, topo), device)
         self.ws_sched = _ws(schedule_workspace_bytes(batch, topo), device)
+        self.ws_lpt = _ws(lpt_spray_workspace_bytes(batch, topo), device)
         self.ws_tm = None
 
     def route(self, logits, tokens_per_gpu, expert_gpu, payload_bytes):
@@ -461,7 +474,7 @@ class Plan:
         D1 = self.D1 if D1 is None else D1
         chunk_sort(D1, self.topo, capacity=self.capacity,
                    out=(self.chunk_off, self.chunk_w, self.chunk_flow, self.perm), ws=self.ws_sort)
-        lpt_spray(self.chunk_off, self.chunk_w, self.batch, self.topo, out=(self.rail, self.S), capacity=self.capacity)
+        lpt_spray(self.chunk_off, self.chunk_w, self.batch, self.topo, out=(self.rail, self.S), capacity=self.capacity, ws=self.ws_lpt)
         eval(self.chunk_off, self.chunk_w, self.chunk_flow, self.rail, self.S, self.batch, self.topo,
              out=(self.R, self.stats), ws=self.ws_eval, capacity=self.capacity)
         return self.stats

@@ -30,6 +30,7 @@
 // every lane group, all 64 lanes streaming weights and writing rails - the shape for few instances,
 // where the latency of the chain and of HBM is the limit and more wavefronts hide more of it.
 #include "common.h"
+#include "chunk_core.h"
 #include "lpt_core.h"
 
 namespace rs {
@@ -262,11 +263,15 @@ __device__ __forceinline__ void exact_steps(unsigned long long &load, const unsi
     }
 }
 
-template <int GW, bool RUNS>
+// QUEUE: the wavefronts of a small resident grid fetch groups of 64/GW instances from a counter, in the order `order` lists the
+// instances (longest first): chains of similar length share a wavefront, long chains start first and short ones fill in behind
+// them - list scheduling of the instances over the SIMDs.  Without it wavefront g takes instances g*IPW .. g*IPW + IPW - 1.
+template <int GW, bool RUNS, bool QUEUE>
 __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_t *__restrict__ chunk_off,
                                                                     const uint32_t *__restrict__ chunk_w, int n_inst, int N,
                                                                     uint8_t *__restrict__ rail, int64_t *__restrict__ S_out,
-                                                                    int64_t capacity)
+                                                                    int64_t capacity, const uint32_t *__restrict__ order,
+                                                                    unsigned *next_group)
 {
     constexpr int S = GroupBits<GW>::S;
     constexpr int IPW = 64 / GW;                    // instances per wavefront
@@ -279,13 +284,23 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
     const int lane = threadIdx.x & 63;
     const unsigned q = (unsigned)(lane % GW);
     const int wave = (int)((blockIdx.x * (unsigned)kLptWaves) + (threadIdx.x >> 6));
-    const int inst = wave * IPW + lane / GW;
-    const bool has_inst = inst < n_inst;
-    const bool has_rail = has_inst && (int)q < N;
     if (chunk_off[n_inst] > capacity) {             // more chunks than the record arrays hold: touch none, mark the loads
-        if (has_rail) S_out[(int64_t)inst * N + q] = -1;
+        const int64_t n = (int64_t)n_inst * N, stride = (int64_t)gridDim.x * blockDim.x;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) S_out[i] = -1;
         return;
     }
+    const int n_groups = (n_inst + IPW - 1) / IPW;
+    auto next = [&]() {
+        unsigned g = 0;
+        if (lane == 0) g = atomicAdd(next_group, 1u);
+        return (int)__builtin_amdgcn_readfirstlane((int)g);
+    };
+    const int64_t mean_len = chunk_off[n_inst] / n_inst;
+    for (int group = QUEUE ? next() : wave; group < n_groups; group = QUEUE ? next() : n_groups) {
+    const int slot = group * IPW + lane / GW;
+    const bool has_inst = slot < n_inst;
+    const int inst = has_inst ? (QUEUE ? (int)order[slot] : slot) : 0;
+    const bool has_rail = has_inst && (int)q < N;
     int64_t beg = has_inst ? chunk_off[inst] : 0;
     int64_t len = has_inst ? chunk_off[inst + 1] - beg : 0;
     unsigned long long base = 0;
@@ -305,7 +320,7 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) { const int64_t o = __shfl_xor(max_len, d); max_len = o > max_len ? o : max_len; }
 
-    if (!RUNS) prioritise_long_chain(max_len, chunk_off[n_inst] / n_inst);
+    if (!RUNS) prioritise_long_chain(max_len, mean_len);
 
     unsigned key = has_rail ? q : 0xFFFFFFFFu;
     unsigned long long load = has_rail ? 0ull : ~0ull;
@@ -406,6 +421,48 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
         left = left_nxt; left_nxt = left_far;
     }
     if (has_rail) S_out[(int64_t)inst * N + q] = (int64_t)(exact ? load : base + (unsigned long long)(key >> S));
+    if (!RUNS) __builtin_amdgcn_s_setprio(0);
+    }
+}
+
+// Instances in descending order of chain length, to within the resolution of 512 buckets (a sixteenth of the length): counting
+// sort by one workgroup.  RUNS: S[inst*N] holds the length of the instance's leading run, which the serial kernel skips.
+// Also clears the group counter of the queue.
+constexpr int kOrdBuckets = 512;
+__device__ __forceinline__ int order_bucket(uint64_t len)
+{
+    if (len < 32) return (int)len;                                      // exact below 32
+    if (len >> 32) return kOrdBuckets - 1;
+    const int e = 31 - __clz((int)(uint32_t)len);                       // 5 .. 31
+    return 32 + (e - 5) * 16 + (int)((len >> (e - 4)) & 15u);           // 16 steps per power of two: 32 .. 463
+}
+template <bool RUNS>
+__global__ __launch_bounds__(1024) void lpt_order_kernel(const int64_t *__restrict__ chunk_off, const int64_t *__restrict__ S, int n_inst, int N,
+                                                         uint32_t *__restrict__ order, unsigned *next_group)
+{
+    __shared__ unsigned hist[kOrdBuckets];
+    for (int i = threadIdx.x; i < kOrdBuckets; i += 1024) hist[i] = 0;
+    if (threadIdx.x == 0) *next_group = 0;
+    __syncthreads();
+    auto length = [&](int i) {
+        int64_t len = chunk_off[i + 1] - chunk_off[i];
+        if (RUNS) { int64_t r0 = S[(int64_t)i * N]; r0 = r0 < len ? r0 : len; len -= r0 - r0 % N; }
+        return (uint64_t)(len < 0 ? 0 : len);
+    };
+    for (int i = threadIdx.x; i < n_inst; i += 1024) atomicAdd(&hist[order_bucket(length(i))], 1u);
+    __syncthreads();
+    if (threadIdx.x < 64) {                                             // exclusive scan from the longest bucket down: 8 buckets per lane
+        const int hi = kOrdBuckets - 1 - (int)threadIdx.x * 8;
+        unsigned v[8], sum = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { v[j] = hist[hi - j]; sum += v[j]; }
+        unsigned total;
+        unsigned ex = wave_exscan(sum, total);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { hist[hi - j] = ex; ex += v[j]; }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < n_inst; i += 1024) order[atomicAdd(&hist[order_bucket(length(i))], 1u)] = (uint32_t)i;
 }
 
 // ================================================================================ wide shape (loop in lpt_core.h)
@@ -442,18 +499,34 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t 
 
 
 // serial kernels only: every instance's S_out[inst*N] must hold the length of its leading run (or less)
+// workspace of the serial kernels: the instance order (one word per instance) and, 256 bytes behind it, the group counter
+static size_t lpt_ws_bytes(int64_t n_inst) { return align_up(sizeof(uint32_t) * (size_t)n_inst, 256) + 256; }
+
 template <int GW, bool RUNS>
 static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
-                             int64_t *S, int64_t capacity, hipStream_t st)
+                             int64_t *S, int64_t capacity, void *ws, hipStream_t st)
 {
     constexpr int IPW = 64 / GW;
     // packed once it yields at least two wavefronts per SIMD (256 CUs x 4 SIMDs); wide below that
     const bool packed = IPW > 1 && n_inst >= (int64_t)2048 * IPW;
-    if (packed) {
+    if (packed && ws) {
+        // Two resident wavefronts per SIMD issue as many VALU instructions as four do (the chain of one wavefront leaves
+        // room for exactly one more), and half as many wavefronts means twice as many groups each: room to even out.
+        uint32_t *order = static_cast<uint32_t *>(ws);
+        unsigned *counter = reinterpret_cast<unsigned *>(static_cast<char *>(ws) + align_up(sizeof(uint32_t) * (size_t)n_inst, 256));
+        hipLaunchKernelGGL((lpt_order_kernel<RUNS>), dim3(1), dim3(1024), 0, st, chunk_off, S, (int)n_inst, N, order, counter);
+        if (int rc = launch_status()) return rc;
+        const int64_t waves = (n_inst + IPW - 1) / IPW;
+        int64_t blocks = (waves + kLptWaves - 1) / kLptWaves;
+        const int64_t resident = 256 * 4 * 2 / kLptWaves;
+        if (blocks > resident) blocks = resident;
+        hipLaunchKernelGGL((lpt_packed_kernel<GW, RUNS, true>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
+                           chunk_w, (int)n_inst, N, rail, S, capacity, order, counter);
+    } else if (packed) {
         const int64_t waves = (n_inst + IPW - 1) / IPW;
         const int64_t blocks = (waves + kLptWaves - 1) / kLptWaves;
-        hipLaunchKernelGGL((lpt_packed_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
-                           chunk_w, (int)n_inst, N, rail, S, capacity);
+        hipLaunchKernelGGL((lpt_packed_kernel<GW, RUNS, false>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
+                           chunk_w, (int)n_inst, N, rail, S, capacity, nullptr, nullptr);
     } else {
         const int64_t blocks = (n_inst + kLptWaves - 1) / kLptWaves;
         hipLaunchKernelGGL((lpt_wide_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
@@ -464,7 +537,7 @@ static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, 
 
 template <int GW, bool RUNS>
 static int launch_lpt(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
-                      int64_t *S, int64_t capacity, hipStream_t st)
+                      int64_t *S, int64_t capacity, void *ws, hipStream_t st)
 {
     if (RUNS) {
         hipLaunchKernelGGL(lpt_prefix_init_kernel, dim3((unsigned)((n_inst + 255) / 256 > 1024 ? 1024 : (n_inst + 255) / 256)), dim3(256),
@@ -474,23 +547,23 @@ static int launch_lpt(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t
                            is_pow2(N) ? N - 1 : -1, rail, S, wide_ok, capacity);
         if (int rc = launch_status()) return rc;
     }
-    return launch_lpt_serial<GW, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    return launch_lpt_serial<GW, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, ws, st);
 }
 
 // for the one-call scheduler, which knows every leading run from stage 3 and has written its rails
 int lpt_serial_after_leading_runs(const int64_t *chunk_off, const uint32_t *chunk_w, int64_t n_inst, int N, uint8_t *rail,
                                   int64_t *S, int64_t capacity, hipStream_t st)
 {
-    if (N <= 4) return launch_lpt_serial<4, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
-    if (N <= 8) return launch_lpt_serial<8, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
-    if (N <= 16) return launch_lpt_serial<16, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
-    if (N <= 32) return launch_lpt_serial<32, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
-    return launch_lpt_serial<64, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    if (N <= 4) return launch_lpt_serial<4, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, nullptr, st);
+    if (N <= 8) return launch_lpt_serial<8, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, nullptr, st);
+    if (N <= 16) return launch_lpt_serial<16, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, nullptr, st);
+    if (N <= 32) return launch_lpt_serial<32, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, nullptr, st);
+    return launch_lpt_serial<64, true>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, nullptr, st);
 }
 
 template <bool RUNS>
 static int lpt_entry(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch, const railsched_topo_t *h_topo,
-                     int64_t capacity, uint8_t *rail, int64_t *S, void *stream)
+                     int64_t capacity, uint8_t *rail, int64_t *S, void *ws, size_t ws_bytes, void *stream)
 {
     if (int rc = check_topo(h_topo)) return rc;
     if (batch < 0 || capacity < 0) return RAILSCHED_ERR_INVALID_ARG;
@@ -498,26 +571,35 @@ static int lpt_entry(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t 
     if (n_inst > 0x7FFFFFFFll / 64) return RAILSCHED_ERR_UNSUPPORTED;
     if (n_inst == 0) return RAILSCHED_OK;
     if (!chunk_off || !S || (capacity > 0 && (!chunk_w || !rail))) return RAILSCHED_ERR_NULL_PTR;
+    if (ws && (ws_bytes < lpt_ws_bytes(n_inst) || reinterpret_cast<uintptr_t>(ws) % 256)) return RAILSCHED_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int N = h_topo->rails;
-    if (N <= 4) return launch_lpt<4, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
-    if (N <= 8) return launch_lpt<8, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
-    if (N <= 16) return launch_lpt<16, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
-    if (N <= 32) return launch_lpt<32, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
-    return launch_lpt<64, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, st);
+    if (N <= 4) return launch_lpt<4, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, ws, st);
+    if (N <= 8) return launch_lpt<8, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, ws, st);
+    if (N <= 16) return launch_lpt<16, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, ws, st);
+    if (N <= 32) return launch_lpt<32, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, ws, st);
+    return launch_lpt<64, RUNS>(chunk_off, chunk_w, n_inst, N, rail, S, capacity, ws, st);
 }
 
 }  // namespace rs
 
-extern "C" int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
-                                   const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S, void *stream)
+extern "C" size_t railsched_lpt_spray_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo)
 {
-    return rs::lpt_entry<true>(chunk_off, chunk_w, batch, h_topo, capacity, rail, S, stream);
+    using namespace rs;
+    if (check_topo(h_topo) != RAILSCHED_OK || batch < 0) return 0;
+    return lpt_ws_bytes((int64_t)batch * h_topo->nodes);
+}
+
+extern "C" int railsched_lpt_spray(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
+                                   const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S, void *ws,
+                                   size_t ws_bytes, void *stream)
+{
+    return rs::lpt_entry<true>(chunk_off, chunk_w, batch, h_topo, capacity, rail, S, ws, ws_bytes, stream);
 }
 
 extern "C" int railsched_lpt_spray_chunkwise(const int64_t *chunk_off, const uint32_t *chunk_w, int32_t batch,
                                              const railsched_topo_t *h_topo, int64_t capacity, uint8_t *rail, int64_t *S,
-                                             void *stream)
+                                             void *ws, size_t ws_bytes, void *stream)
 {
-    return rs::lpt_entry<false>(chunk_off, chunk_w, batch, h_topo, capacity, rail, S, stream);
+    return rs::lpt_entry<false>(chunk_off, chunk_w, batch, h_topo, capacity, rail, S, ws, ws_bytes, stream);
 }

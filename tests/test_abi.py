@@ -53,10 +53,10 @@ def test_topology_validation():
     lib = rs.load()
     for t, want in ((_topo(M=0), -1), (_topo(N=0), -1), (_topo(Cb=0), -1), (_topo(reserved=1), -1), (_topo(intra=2), -1),
                     (_topo(N=65), -3), (_topo(M=4096, N=8), -3), (_topo(Cb=1 << 32), -3)):
-        assert lib.railsched_lpt_spray(FAKE, FAKE, 1, C.byref(t), 10, FAKE, FAKE, None) == want
+        assert lib.railsched_lpt_spray(FAKE, FAKE, 1, C.byref(t), 10, FAKE, FAKE, None, 0, None) == want
         assert lib.railsched_chunk_sort_workspace_bytes(1, C.byref(t)) == 0
         assert lib.railsched_eval_workspace_bytes(1, C.byref(t)) == 0
-    assert lib.railsched_lpt_spray(FAKE, FAKE, 1, None, 10, FAKE, FAKE, None) == -2
+    assert lib.railsched_lpt_spray(FAKE, FAKE, 1, None, 10, FAKE, FAKE, None, 0, None) == -2
 
 
 def test_traffic_matrix_validation():
@@ -147,11 +147,16 @@ def test_chunk_sort_and_eval_validation():
     assert ev(FAKE, FAKE, None, FAKE, FAKE, 2, C.byref(t), 10, FAKE, FAKE, FAKE, need, None) == -2
     assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 2, C.byref(t), 10, FAKE, FAKE, FAKE, need - 1, None) == -5
     assert ev(FAKE, FAKE, FAKE, FAKE, FAKE, 0, C.byref(t), 10, FAKE, FAKE, FAKE, need, None) == 0
-    assert lib.railsched_lpt_spray(FAKE, FAKE, 0, C.byref(t), 10, FAKE, FAKE, None) == 0
-    assert lib.railsched_lpt_spray(None, FAKE, 1, C.byref(t), 10, FAKE, FAKE, None) == -2
-    assert lib.railsched_lpt_spray(FAKE, FAKE, 1, C.byref(t), -1, FAKE, FAKE, None) == -1
-    assert lib.railsched_lpt_spray(FAKE, None, 1, C.byref(t), 10, FAKE, FAKE, None) == -2     # records without arrays
-    assert lib.railsched_lpt_spray_chunkwise(FAKE, FAKE, 1, C.byref(t), 10, None, FAKE, None) == -2
+    lp = lib.railsched_lpt_spray   # (chunk_off, chunk_w, batch, topo, capacity, rail, S, ws, ws_bytes, stream)
+    assert lp(FAKE, FAKE, 0, C.byref(t), 10, FAKE, FAKE, None, 0, None) == 0
+    assert lp(None, FAKE, 1, C.byref(t), 10, FAKE, FAKE, None, 0, None) == -2
+    assert lp(FAKE, FAKE, 1, C.byref(t), -1, FAKE, FAKE, None, 0, None) == -1
+    assert lp(FAKE, None, 1, C.byref(t), 10, FAKE, FAKE, None, 0, None) == -2     # records without arrays
+    assert lib.railsched_lpt_spray_chunkwise(FAKE, FAKE, 1, C.byref(t), 10, None, FAKE, None, 0, None) == -2
+    need_l = lib.railsched_lpt_spray_workspace_bytes(2, C.byref(t))
+    assert need_l >= 4 * 2 * 4 + 4 and need_l % 256 == 0 and lib.railsched_lpt_spray_workspace_bytes(-1, C.byref(t)) == 0
+    assert lp(FAKE, FAKE, 2, C.byref(t), 10, FAKE, FAKE, FAKE, need_l - 1, None) == -5      # a workspace is optional, but not a short one
+    assert lp(FAKE, FAKE, 2, C.byref(t), 10, FAKE, FAKE, P(0x1001), need_l, None) == -5
 
 
 def test_extras_validation():
