@@ -671,7 +671,7 @@ def bench_streamed(cfg, args, rs, W, torch, np):
     ws_rt = torch.empty(max(rs.route_traffic_workspace_bytes(1, cfg.tokens_per_gpu, cfg.E, cfg.k, topo), 256), dtype=torch.uint8, device=dev)
     D1_one = torch.empty((1, G, G), dtype=torch.int64, device=dev)
     idx_one = torch.empty_like(idx)
-    t1, t2, t12 = [], [], []
+    t1, t2, t12, t12n = [], [], [], []
     keep_logits = []
     for b in range(B):
         lg = W.gen_logits(cfg, b, device=dev)
@@ -690,6 +690,13 @@ def bench_streamed(cfg, args, rs, W, torch, np):
         torch.cuda.synchronize()
         t1.append(e0.elapsed_time(e1)); t2.append(e1.elapsed_time(e2)); t12.append(e2.elapsed_time(e3))
         assert torch.equal(D1_one[0], D1[b]) and torch.equal(idx_one, idx)
+        if not args.skip_extras:                    # the same call without the indices: one pass over the logits
+            e4 = _event(torch)
+            rs.route_traffic(lg, cfg.k, 1, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=(None, D1_one), ws=ws_rt)
+            e5 = _event(torch)
+            torch.cuda.synchronize()
+            t12n.append(e4.elapsed_time(e5))
+            assert torch.equal(D1_one[0], D1[b])
         if b < 2 and args.cpu_layers != 0:
             keep_logits.append(lg.cpu().numpy())
         del lg
@@ -719,7 +726,8 @@ def bench_streamed(cfg, args, rs, W, torch, np):
         "timing": "sum of hipEvent times: railsched_route_traffic once per layer (logits regenerated between layers, untimed), "
                   "railsched_schedule over all matrices (median of the repetitions)",
         "stage_ms": ms,
-        "per_layer_ms": {"route_traffic": _median(t12), "route_topk": _median(t1), "traffic_matrix": _median(t2)},
+        "per_layer_ms": {"route_traffic": _median(t12), "route_topk": _median(t1), "traffic_matrix": _median(t2),
+                         "route_traffic_without_indices": _median(t12n)},
         "staged": {"ms_per_step": sum(t1) + sum(t2) + sum(ms3.values()),
                    "stage_ms": {"route_topk": sum(t1), "traffic_matrix": sum(t2), **ms3},
                    "stage_rooflines": {

@@ -110,15 +110,17 @@ int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, int64_t tok
  * Stages 1 and 2 in one call (Algorithm 1 steps 1-2: gate, then selection of input slices by gate
  * and expert assignment).  Same inputs, same rules and bit-identical outputs as
  * railsched_route_topk over all batch*G*tokens_per_gpu rows followed by railsched_traffic_matrix;
- * for E <= 8 both are produced in a single pass over the logits and the indices are never read back.
+ * for E <= 8 both are produced in a single pass over the logits and the indices are never read back; so is D1 for
+ * 32 < E <= 256 with k <= 8 when the indices are not wanted (topk_idx == NULL; 16-byte aligned logits, E a multiple
+ * of 4, G <= 4096); everything else runs the two stages.
  *   logits     [batch*G*tokens_per_gpu][E] fp32                     (in)
  *   expert_gpu [E][R] int32, values in [0,G)                        (in; out-of-range values are ignored)
- *   topk_idx   [batch*G*tokens_per_gpu][k] int32                    (out; may be NULL when E <= 8: the
- *                                                                    picks are then counted but not stored)
+ *   topk_idx   [batch*G*tokens_per_gpu][k] int32                    (out; may be NULL for the single-pass shapes:
+ *                                                                    the picks are then counted but not stored)
  *   D1         [batch][G][G] int64                                  (out, fully overwritten)
  *   ws         railsched_route_traffic_workspace_bytes(...) bytes of device memory, 4-byte aligned
  *              (scratch: per-slice destination counts; contents undefined afterwards)
- * Errors: NULL_PTR (also topk_idx == NULL with E > 8), INVALID_ARG, UNSUPPORTED (E > 1024, G > 16384),
+ * Errors: NULL_PTR (also topk_idx == NULL for a shape that runs the two stages), INVALID_ARG, UNSUPPORTED (E > 1024, G > 16384),
  * WORKSPACE (ws missing, misaligned or smaller than the query's answer).
  * ------------------------------------------------------------------------------------------- */
 size_t railsched_route_traffic_workspace_bytes(int32_t batch, int64_t tokens_per_gpu, int32_t E, int32_t k,

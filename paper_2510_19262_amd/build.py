@@ -21,7 +21,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 # Sources that order floats with v_min/v_max/v_med3 on bit patterns they built themselves: the inputs are finite by
 # contract, and without this the compiler quiets a possible signalling NaN in front of every min and max.
-EXTRA_FLAGS = {"route_topk.hip": ["-fno-honor-nans"]}
+EXTRA_FLAGS = {"route_topk.hip": ["-fno-honor-nans"], "route_traffic.hip": ["-fno-honor-nans"]}
 
 
 def _compile(src: str) -> str:

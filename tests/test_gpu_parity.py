@@ -190,8 +190,6 @@ def test_route_traffic_matches_the_two_stages_of_the_oracle(M, N, E, k, R, tok, 
     rows = batch * G * tok
     x = _coarse_logits(rng, rows, E)
     topo = rs.Topo(M, N, 4096)
-    if E > 8 and not want_idx:
-        pytest.skip("wide rows need the index array")
     idx, D1 = rs.route_traffic(torch.from_numpy(x).to(DEV).view(rows, E), k, batch, tok, torch.from_numpy(eg).to(DEV), 2048, topo,
                                want_idx=want_idx)
     want = oracle.route_topk(x, k) if rows else np.empty((0, k), np.int32)
@@ -200,6 +198,41 @@ def test_route_traffic_matches_the_two_stages_of_the_oracle(M, N, E, k, R, tok, 
     else:
         assert idx is None
     assert np.array_equal(D1.cpu().numpy(), oracle.traffic_matrix(want, batch, tok, eg, 2048, M, N))
+
+
+@pytest.mark.parametrize("M,N,E,k,R,tok,batch,kind", [
+    (4, 4, 256, 8, 2, 700, 1, "normal"), (8, 8, 256, 8, 4, 1031, 2, "normal"), (2, 3, 128, 8, 3, 513, 2, "normal"),
+    (2, 2, 64, 6, 1, 2000, 1, "normal"), (2, 2, 40, 8, 5, 333, 3, "normal"), (3, 2, 200, 5, 2, 129, 2, "normal"),
+    (2, 2, 256, 1, 2, 257, 1, "normal"), (2, 2, 96, 3, 7, 31, 2, "normal"), (4, 4, 256, 8, 2, 300, 1, "lattice"),
+    (2, 2, 128, 4, 2, 300, 2, "lattice"), (2, 2, 64, 8, 3, 100, 1, "lattice"), (2, 2, 256, 8, 1, 64, 1, "bunched"),
+    (64, 8, 256, 8, 4, 40, 1, "normal"), (2, 2, 256, 8, 2048, 600, 1, "normal")])
+def test_route_traffic_wide_rows_with_and_without_indices(M, N, E, k, R, tok, batch, kind):
+    # rows of 33..256 logits with k <= 8: with the indices the two stages run back to back, without them gating and traffic
+    # matrix come out of one pass over the logits.  Token counts that are no multiple of a workgroup's share, replica counts
+    # that are no power of two, a placement table too large for LDS, logits full of exact ties (every wavefront takes the
+    # exact path) and winners bunched in one lane's experts.
+    rng = np.random.default_rng(M * 1000 + N * 100 + E * 10 + k + R)
+    G = M * N
+    eg = rng.integers(0, G, size=(E, R)).astype(np.int32)
+    rows = batch * G * tok
+    if kind == "lattice":
+        x = _coarse_logits(rng, rows, E)
+    else:
+        x = rng.standard_normal((rows, E)).astype(np.float32)
+        if kind == "bunched":
+            x[:, :4] += 9.0
+            x[:, 32:36] += 8.0                                      # experts 0-3 and 32-35 sit in the same lane of the row
+    topo = rs.Topo(M, N, 4096)
+    want = oracle.route_topk(x, k)
+    D1_want = oracle.traffic_matrix(want, batch, tok, eg, 1536, M, N)
+    xd, egd = torch.from_numpy(x).to(DEV).view(rows, E), torch.from_numpy(eg).to(DEV)
+    for want_idx in (True, False):
+        idx, D1 = rs.route_traffic(xd, k, batch, tok, egd, 1536, topo, want_idx=want_idx)
+        if want_idx:
+            assert np.array_equal(idx.cpu().numpy(), want)
+        else:
+            assert idx is None
+        assert np.array_equal(D1.cpu().numpy(), D1_want), f"D1, want_idx={want_idx}"
 
 
 def test_route_traffic_unaligned_logits_and_stale_output():
