@@ -64,32 +64,42 @@ def _median(xs):
     return float(statistics.median(xs)) if xs else None
 
 
-def _sha12(relpath):
-    with open(os.path.join(ROOT, relpath), "rb") as fh:
-        return hashlib.sha256(fh.read()).hexdigest()[:12]
+def _sha12(source):
+    """First 12 hex digits of the sha256 of a kernel source file followed by every header of the library (sorted by name)."""
+    csrc = os.path.join(ROOT, "paper_2510_19262_amd", "csrc")
+    h = hashlib.sha256()
+    for name in [source] + sorted(f for f in os.listdir(csrc) if f.endswith(".h")):
+        with open(os.path.join(csrc, name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:12]
 
 
-def counter_traffic(kernel, workload):
-    """HBM bytes per launch of `kernel` on `workload` from the rocprofv3 counter runs summarised under profiles/
-    (FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a copy of known size).  The summaries carry lines
-      TRAFFIC <kernel> <workload> read_MiB=<x> written_MiB=<y> source=<file under csrc> sha=<first 12 hex of its sha256>
-    and this is the one place the benchmark takes the figure from.  None when there is no such line, or when the
-    kernel's source file has changed since the counters were taken."""
+def counter_traffic(kernels, workload):
+    """HBM bytes per launch of `kernels` (one name, or several whose launches make up one call) on `workload`, from the
+    rocprofv3 counter runs summarised under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a copy
+    of known size).  The summaries carry lines
+      TRAFFIC <kernel> <workload> read_MiB=<x> written_MiB=<y> source=<file under csrc> sha=<see _sha12>
+    and this is the one place the benchmark takes the figure from.  None when a kernel has no such line, or when its
+    source (or a header of the library) has changed since the counters were taken."""
     pdir = os.path.join(ROOT, "profiles")
     if not os.path.isdir(pdir):
         return None
     pat = re.compile(r"^TRAFFIC\s+(\S+)\s+(\S+)\s+read_MiB=([0-9.]+)\s+written_MiB=([0-9.]+)\s+source=(\S+)\s+sha=([0-9a-f]+)")
+    found = {}
     for name in sorted(os.listdir(pdir)):
         if not name.endswith((".md", ".txt")):
             continue
         for line in open(os.path.join(pdir, name)):
             m = pat.match(line.strip())
-            if m and m.group(1) == kernel and m.group(2) == workload:
-                src = os.path.join("paper_2510_19262_amd", "csrc", m.group(5))
-                if not os.path.exists(os.path.join(ROOT, src)) or _sha12(src) != m.group(6):
-                    return None
-                return int((float(m.group(3)) + float(m.group(4))) * 1024 * 1024)
-    return None
+            if m and m.group(2) == workload and m.group(1) not in found:
+                found[m.group(1)] = m
+    total = 0.0
+    for k in ([kernels] if isinstance(kernels, str) else kernels):
+        m = found.get(k) or found.get(k.split(":")[0])   # "<kernel>:one_call" lines exist only where that dispatch differs
+        if m is None or not os.path.exists(os.path.join(ROOT, "paper_2510_19262_amd", "csrc", m.group(5))) or _sha12(m.group(5)) != m.group(6):
+            return None
+        total += float(m.group(3)) + float(m.group(4))
+    return int(total * 1024 * 1024)
 
 
 def copy_probe(torch, dev):
@@ -101,10 +111,31 @@ def copy_probe(torch, dev):
     del src, dst
 
 
-def hbm_roofline(kernel, workload, algorithmic_bytes, ms, note=None):
+def write_probe(torch, plan, total, reps=5):
+    """Plain fills of the record arrays a schedule call writes (weights, flows, the permutation if kept, rails), `total`
+    records each: the same bytes written by kernels that do nothing else, timed in the same run as the record fill.  The
+    arrays are scratch outputs that the next call rewrites."""
+    arrs = [a[:total] for a in (plan.chunk_w, plan.chunk_flow, plan.perm, plan.rail) if a is not None]
+    nbytes = sum(a.numel() * a.element_size() for a in arrs)
+    ts = []
+    for _ in range(reps):
+        e0 = _event(torch)
+        for a in arrs:
+            a.fill_(1)
+        e1 = _event(torch)
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ms = _median(ts)
+    return {"what": "torch fill_ of the record arrays of one schedule call (%d arrays, one launch each)" % len(arrs),
+            "bytes": nbytes, "ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+
+def hbm_roofline(kernel, workload, algorithmic_bytes, ms, note=None, counted=None):
+    """`counted`: the kernels whose counter traffic adds up to the call (default: the kernel named first in `kernel`)."""
     gbps = algorithmic_bytes / (ms * 1e-3) / 1e9
     r = {"kernel": kernel, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
-         "traffic": counter_traffic(kernel.split(" ")[0], workload), "algorithmic_bytes_per_launch": int(algorithmic_bytes),
+         "traffic": counter_traffic(counted or COUNTED.get(kernel, kernel.split(" ")[0]), workload),
+         "algorithmic_bytes_per_launch": int(algorithmic_bytes),
          "avg_launch_ms": ms}
     if note:
         r["note"] = note
@@ -138,6 +169,10 @@ STAGE_KERNEL = {"chunk_sort": "cs_fill_kernel (with the count, scan and tail-sor
                 "eval": "eval_partial_kernel (with the reduction of the call)",
                 "schedule": "cs_fill_kernel (railsched_schedule: records and leading-run rails written once; count, scan, tail sort, "
                             "serial LPT behind the leading runs, closed-form receive loads and reduction in the same call)"}
+
+
+# the record fill launched by railsched_schedule also writes the leading-run rails: its own counter line
+COUNTED = {STAGE_KERNEL["schedule"]: "cs_fill_kernel:one_call"}
 
 
 def time_stages_3_5(rs, torch, plan, D1, topo, B, reps, warmup):
@@ -432,7 +467,7 @@ def bench_resident(cfg, args, rs, W, torch, np):
     rt_bytes = k1_bytes + 8 * B * G * G
     sb = stage_bytes(total_chunks, B * cfg.M, topo, True)
     rt_roof = hbm_roofline("route_traffic_kernel (with rt_reduce_kernel, the sum of its slice counts, in the same call)", cfg.name,
-                           rt_bytes, stage_ms["route_traffic"])
+                           rt_bytes, stage_ms["route_traffic"], counted=("route_traffic_kernel", "rt_reduce_kernel:one_call"))
     rt_roof["slowest_stage"] = max(stage_ms, key=stage_ms.get)
     out = {
         "metric": "LPT-sprayed chunks/s over the whole path (route_topk, traffic_matrix, chunk_sort, lpt_spray, eval; stages 1-2 and 3-5 fused into two calls)",
@@ -535,6 +570,10 @@ def bench_flows_resident(cfg, args, rs, W, torch, np):
     n_inst = B * cfg.M
     sb = stage_bytes(total, n_inst, topo, True)
     chunkwise_ms = None if args.skip_extras else time_chunkwise(rs, torch, plan, B, topo, 3)
+    probe = None if args.skip_extras else write_probe(torch, plan, total)
+    if probe is not None:   # the probe overwrote the records: the outputs checked below come from a fresh call
+        plan.schedule_one_call(D1)
+        torch.cuda.synchronize()
     rec = {
         "metric": "LPT-sprayed chunks/s over stages 3-5 (chunk_sort, lpt_spray, eval, in one call); the workload has no routing stage",
         "value": total / (one_ms * 1e-3), "unit": "chunks/s", "n_gpus": 1, "steps": reps, "warmup": warmup,
@@ -552,6 +591,7 @@ def bench_flows_resident(cfg, args, rs, W, torch, np):
         "lpt_spray_chunkwise_ms": chunkwise_ms,
         "makespan_over_lower_bound": ratio_stats(np, st),
         "roofline": hbm_roofline(STAGE_KERNEL["schedule"], cfg.name, sb["schedule"], one_ms),
+        "write_probe": probe,
     }
     if args.cpu_layers != 0:
         import oracle
@@ -592,7 +632,11 @@ def bench_flows_streamed(cfg, args, rs, W, torch, np):
             ms, one_ms = time_stages_3_5(rs, torch, plan, D1, topo, 1, reps, warmup)
             chunkwise_ms = None if args.skip_extras else time_chunkwise(rs, torch, plan, 1, topo, 2)
             sb = stage_bytes(total, n_inst, topo, False)
-            first = {"chunks": total, "stage_ms": {"schedule": one_ms}, "reps": reps,
+            probe = None if args.skip_extras else write_probe(torch, plan, total)
+            if probe is not None:
+                plan.schedule_one_call(D1)
+                torch.cuda.synchronize()
+            first = {"chunks": total, "write_probe": probe, "stage_ms": {"schedule": one_ms}, "reps": reps,
                      "staged": {"ms_per_step": sum(ms.values()), "stage_ms": ms,
                                 "stage_rooflines": {n: hbm_roofline(STAGE_KERNEL[n], cfg.name, sb[n], ms[n]) for n in ms}},
                      "lpt_spray_chunks_per_s": None if chunkwise_ms is None else total / (chunkwise_ms * 1e-3),
