@@ -112,22 +112,25 @@ def copy_probe(torch, dev):
 
 
 def write_probe(torch, plan, total, reps=5):
-    """Plain fills of the record arrays a schedule call writes (weights, flows, the permutation if kept, rails), `total`
-    records each: the same bytes written by kernels that do nothing else, timed in the same run as the record fill.  The
-    arrays are scratch outputs that the next call rewrites."""
+    """Plain writes of the record arrays a schedule call writes (weights, flows, the permutation if kept, rails), `total`
+    records each: the same bytes written by code that does nothing else, timed in the same run as the record fill.  Two
+    writers: torch's fill kernel, and hipMemsetAsync (torch's zero_()).  The arrays are scratch outputs that the next call
+    rewrites."""
     arrs = [a[:total] for a in (plan.chunk_w, plan.chunk_flow, plan.perm, plan.rail) if a is not None]
     nbytes = sum(a.numel() * a.element_size() for a in arrs)
-    ts = []
-    for _ in range(reps):
-        e0 = _event(torch)
-        for a in arrs:
-            a.fill_(1)
-        e1 = _event(torch)
-        torch.cuda.synchronize()
-        ts.append(e0.elapsed_time(e1))
-    ms = _median(ts)
-    return {"what": "torch fill_ of the record arrays of one schedule call (%d arrays, one launch each)" % len(arrs),
-            "bytes": nbytes, "ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    out = {"what": "plain writes of the record arrays of one schedule call (%d arrays, one launch each)" % len(arrs), "bytes": nbytes}
+    for name, fn in (("fill_kernel", lambda a: a.fill_(1)), ("memset", lambda a: a.zero_())):
+        ts = []
+        for _ in range(reps):
+            e0 = _event(torch)
+            for a in arrs:
+                fn(a)
+            e1 = _event(torch)
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ms = _median(ts)
+        out[name] = {"ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    return out
 
 
 def hbm_roofline(kernel, workload, algorithmic_bytes, ms, note=None, counted=None):
