@@ -58,6 +58,25 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
     const int64_t pair = blockIdx.x / a.splits;                         // b*G + s
     const int part = blockIdx.x % a.splits;
 
+    // this workgroup's slice of the pair's slots, cut at multiples of 4 slots
+    const int64_t quads = (a.slots_per_gpu + 3) / 4;
+    const int64_t qlo = quads * part / a.splits, qhi = quads * (part + 1) / a.splits;
+    const int32_t *src = a.topk_idx + pair * a.slots_per_gpu;
+    const bool aligned = (reinterpret_cast<uintptr_t>(src) % 16) == 0;
+    const int64_t qfull = aligned ? (a.slots_per_gpu / 4 < qhi ? a.slots_per_gpu / 4 : qhi) : qlo;   // whole, aligned quads
+    constexpr int64_t kStep = (int64_t)kTmUnroll * kTmThreads;
+    auto whole_step = [&](int64_t q) { return q + (int64_t)(kTmUnroll - 1) * kTmThreads < qfull; };
+    auto request = [&](int64_t q, int4 (&e)[kTmUnroll]) {
+#pragma unroll
+        for (int u = 0; u < kTmUnroll; ++u) e[u] = *reinterpret_cast<const int4 *>(src + (q + (int64_t)u * kTmThreads) * 4);
+    };
+    // the first step's indices are requested before the histogram is cleared and the table staged, every later step's
+    // before the step in hand is counted: the loads of a short-lived workgroup are in flight from its first instruction on
+    int64_t qd = qlo + threadIdx.x;
+    int4 cur[kTmUnroll];
+    bool have = whole_step(qd);
+    if (have) request(qd, cur);
+
     for (int i = threadIdx.x; i < a.bin_stride * a.copies; i += kTmThreads) all_bins[i] = 0;
     if (TABLE_LDS)
         for (int i = threadIdx.x; i < a.E * a.R; i += kTmThreads) lds_table[i] = a.expert_gpu[i];
@@ -67,24 +86,23 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
     const int32_t *table;
     if constexpr (TABLE_LDS) table = lds_table; else table = a.expert_gpu;
 
-    // this workgroup's slice of the pair's slots, cut at multiples of 4 slots
-    const int64_t quads = (a.slots_per_gpu + 3) / 4;
-    const int64_t qlo = quads * part / a.splits, qhi = quads * (part + 1) / a.splits;
-    const int32_t *src = a.topk_idx + pair * a.slots_per_gpu;
-    const bool aligned = (reinterpret_cast<uintptr_t>(src) % 16) == 0;
-    const int64_t qfull = aligned ? (a.slots_per_gpu / 4 < qhi ? a.slots_per_gpu / 4 : qhi) : qlo;   // whole, aligned quads
-    int64_t qd = qlo + threadIdx.x;
-    for (; qd + (int64_t)(kTmUnroll - 1) * kTmThreads < qfull; qd += (int64_t)kTmUnroll * kTmThreads) {
-        int4 e[kTmUnroll];
-#pragma unroll
-        for (int u = 0; u < kTmUnroll; ++u) e[u] = *reinterpret_cast<const int4 *>(src + (qd + (int64_t)u * kTmThreads) * 4);
+    while (have) {
+        int4 nxt[kTmUnroll];
+        const bool more = whole_step(qd + kStep);
+        if (more) request(qd + kStep, nxt);
 #pragma unroll
         for (int u = 0; u < kTmUnroll; ++u) {
             const int64_t s0 = (qd + (int64_t)u * kTmThreads) * 4;
-            tm_count<FAST>(a, table, bins, s0 + 0, e[u].x);
-            tm_count<FAST>(a, table, bins, s0 + 1, e[u].y);
-            tm_count<FAST>(a, table, bins, s0 + 2, e[u].z);
-            tm_count<FAST>(a, table, bins, s0 + 3, e[u].w);
+            tm_count<FAST>(a, table, bins, s0 + 0, cur[u].x);
+            tm_count<FAST>(a, table, bins, s0 + 1, cur[u].y);
+            tm_count<FAST>(a, table, bins, s0 + 2, cur[u].z);
+            tm_count<FAST>(a, table, bins, s0 + 3, cur[u].w);
+        }
+        qd += kStep;
+        have = more;
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < kTmUnroll; ++u) cur[u] = nxt[u];
         }
     }
     for (; qd < qhi; qd += kTmThreads) {
@@ -153,7 +171,10 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
     a.E = E; a.R = R; a.rmask = is_pow2(R) ? R - 1 : -1;
     a.G = (int32_t)G;
     a.copies = 1;
-    while (a.copies < 8 && (int64_t)a.copies * 2 * (G | 1) <= 8192) a.copies *= 2;
+    // as many copies as keep a workgroup's LDS (bins + table) within 20 KiB: eight workgroups, all the wavefronts a CU takes
+    const int64_t table_words = (int64_t)E * R <= kTmTableMax ? (int64_t)E * R : 0;     // a larger table stays in global memory
+    while (a.copies < 8 && (int64_t)a.copies * 2 * (G | 1) <= 8192 && 4 * ((int64_t)a.copies * 2 * (G | 1) + table_words) <= 20 * 1024)
+        a.copies *= 2;
     // a lane holds 4 consecutive slots, so rho repeats every R*k/4 lanes when that is a whole number
     a.lanes_per_period = ((int64_t)R * k % 4 == 0 && (int64_t)R * k / 4 <= 64) ? (int32_t)((int64_t)R * k / 4) : 1;
     a.bin_stride = (int32_t)(a.copies > 1 ? (G | 1) : G);
