@@ -111,26 +111,51 @@ def copy_probe(torch, dev):
     del src, dst
 
 
-def write_probe(torch, plan, total, reps=5):
-    """Plain writes of the record arrays a schedule call writes (weights, flows, the permutation if kept, rails), `total`
-    records each: the same bytes written by code that does nothing else, timed in the same run as the record fill.  Two
-    writers: torch's fill kernel, and hipMemsetAsync (torch's zero_()).  The arrays are scratch outputs that the next call
-    rewrites."""
-    arrs = [a[:total] for a in (plan.chunk_w, plan.chunk_flow, plan.perm, plan.rail) if a is not None]
-    nbytes = sum(a.numel() * a.element_size() for a in arrs)
-    out = {"what": "plain writes of the record arrays of one schedule call (%d arrays, one launch each)" % len(arrs), "bytes": nbytes}
-    for name, fn in (("fill_kernel", lambda a: a.fill_(1)), ("memset", lambda a: a.zero_())):
+MEASURED = {}
+
+
+def measure_streams(torch, dev, reps=7):
+    """What this machine's HBM sustains for a plain copy (1 GiB read + 1 GiB written) and a plain fill (1 GiB written), timed like
+    the stages: the rooflines quote their rate against the published peak and, as `frac_of_measured_copy`, against the first."""
+    src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    res = {}
+    for name, fn, nbytes in (("copy", lambda: dst.copy_(src), 2 << 30), ("fill", lambda: dst.fill_(1.0), 1 << 30)):
         ts = []
         for _ in range(reps):
             e0 = _event(torch)
-            for a in arrs:
-                fn(a)
+            fn()
             e1 = _event(torch)
             torch.cuda.synchronize()
             ts.append(e0.elapsed_time(e1))
-        ms = _median(ts)
-        out[name] = {"ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
-    return out
+        res[name + "_GBps"] = nbytes / (_median(ts[1:]) * 1e-3) / 1e9
+    del src, dst
+    MEASURED.update(res)
+    return res
+
+
+def write_probe(torch, plan, total, reps=5):
+    """Plain fills of the record arrays a schedule call writes (weights, flows, the permutation if kept, rails), `total`
+    records each: the same bytes written by a kernel that does nothing else (torch's fill, one launch per array; the rail
+    bytes are filled as 32-bit words like the others), timed in the same run as the record fill.  The arrays are scratch
+    outputs that the next call rewrites."""
+    # lengths cut to multiples of 2^20 words: torch splits a tensor of more than 2^31 elements into halves, and halves of an odd
+    # length start off the 16-byte grid, which sends its fill down an unvectorised path (4.8 instead of 6.8 TB/s)
+    cut = lambda n: n - n % (1 << 20)
+    arrs = [a[:cut(total)] for a in (plan.chunk_w, plan.chunk_flow, plan.perm) if a is not None]
+    arrs.append(plan.rail[:4 * cut(total // 4)].view(torch.int32))
+    nbytes = sum(a.numel() * a.element_size() for a in arrs)
+    ts = []
+    for _ in range(reps):
+        e0 = _event(torch)
+        for a in arrs:
+            a.fill_(1)
+        e1 = _event(torch)
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ms = _median(ts)
+    return {"what": "torch fill_ of the record arrays of one schedule call (%d arrays, one launch each)" % len(arrs),
+            "bytes": nbytes, "ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
 
 
 def hbm_roofline(kernel, workload, algorithmic_bytes, ms, note=None, counted=None):
@@ -140,6 +165,8 @@ def hbm_roofline(kernel, workload, algorithmic_bytes, ms, note=None, counted=Non
          "traffic": counter_traffic(counted or COUNTED.get(kernel, kernel.split(" ")[0]), workload),
          "algorithmic_bytes_per_launch": int(algorithmic_bytes),
          "avg_launch_ms": ms}
+    if MEASURED.get("copy_GBps"):
+        r["frac_of_measured_copy"] = gbps / MEASURED["copy_GBps"]
     if note:
         r["note"] = note
     return r
@@ -230,8 +257,10 @@ def time_chunkwise(rs, torch, plan, B, topo, reps):
 
 
 def ratio_stats(np, stats):
+    """makespan / lower bound per matrix: max and mean as doubles, the max also as the exact fraction of the two integers."""
     r = stats[:, 0] / np.maximum(stats[:, 3], 1)
-    return {"max": float(r.max()), "mean": float(r.mean())}
+    i = int(r.argmax())
+    return {"max": float(r.max()), "mean": float(r.mean()), "max_exact": f"{int(stats[i, 0])}/{int(max(stats[i, 3], 1))}", "matrices": int(r.size)}
 
 
 def exact_mse_over_wmax2(S, wmax):
@@ -836,6 +865,27 @@ def run_config(name, args, rs, W, torch, np):
     return bench_resident(cfg, args, rs, W, torch, np)
 
 
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def _name_the_cpu(rec, model):
+    """Every cpu_baseline object says which CPU the oracle ran on."""
+    if isinstance(rec, dict):
+        for k, v in rec.items():
+            if k == "cpu_baseline" and isinstance(v, dict):
+                v["cpu_model"] = model
+                v["host_cpus"] = os.cpu_count()
+            else:
+                _name_the_cpu(v, model)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -851,10 +901,15 @@ def main():
 
     rs.load()                                       # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    streams = measure_streams(torch, "cuda:0")
     if args.config != "all":
-        print(json.dumps(run_config(args.config, args, rs, W, torch, np)))
+        out = run_config(args.config, args, rs, W, torch, np)
+        out["hbm_measured"] = streams
+        _name_the_cpu(out, _cpu_model())
+        print(json.dumps(out))
         return
     out = run_config("c2", args, rs, W, torch, np)
+    out["hbm_measured"] = streams
     out["workloads"] = {}
     for name in ("c3", "c4", "c5"):
         gc.collect()
@@ -867,6 +922,7 @@ def main():
         rec["wall_s"] = time.perf_counter() - t0
         out["workloads"][name] = rec
         print(f"bench: {name} done in {rec['wall_s']:.1f} s", file=sys.stderr, flush=True)
+    _name_the_cpu(out, _cpu_model())
     print(json.dumps(out))
 
 
