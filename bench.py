@@ -889,7 +889,7 @@ def _name_the_cpu(rec, model):
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (the rails and the other GPUs are simulated "
+        print("bench.py: this library runs on exactly one GPU (the rails and the other GPUs are simulated "
               "arithmetically); --gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
 

@@ -44,7 +44,7 @@ typedef enum railsched_status {
     RAILSCHED_OK = 0,
     RAILSCHED_ERR_INVALID_ARG = -1, /* a size or count is out of its documented range           */
     RAILSCHED_ERR_NULL_PTR    = -2, /* a required pointer is NULL                               */
-    RAILSCHED_ERR_UNSUPPORTED = -3, /* valid in the paper's model but beyond this build's limits */
+    RAILSCHED_ERR_UNSUPPORTED = -3, /* valid in the paper's model but beyond this library's limits */
     RAILSCHED_ERR_CAPACITY    = -4, /* railsched_check_capacity: more chunks than the arrays hold */
     RAILSCHED_ERR_WORKSPACE   = -5, /* workspace missing or smaller than *_workspace_bytes()     */
     RAILSCHED_ERR_HIP         = -6, /* the HIP runtime refused a launch                          */

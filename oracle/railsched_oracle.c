@@ -91,8 +91,8 @@ int oracle_route_topk(const float *logits, int64_t rows, int E, int k, int32_t *
 }
 
 /* ------------------------------------------------------------------------
- * Step 2 (Algorithm 1 step 2, "select input slices for local experts according
- * to Gate and the expert assignment"; D^(1) of Section 4.1): every (token,
+ * Step 2 (Algorithm 1 step 2, where every expert's input slices are picked by
+ * the gate and the expert placement; D^(1) of Section 4.1): every (token,
  * slot) sends payload bytes from the token's GPU to the GPU hosting the chosen
  * expert.  Row r of a layer lives on GPU s = r / tokens_per_gpu; replica rho =
  * (r mod tokens_per_gpu) mod R of the expert receives it.
@@ -465,7 +465,7 @@ void oracle_transpose_batch(const int64_t *D1, int batch, int64_t G, int64_t *D1
  * Arithmetic stand-ins for the path-selection schemes RailS is compared with (Sections 1, 2.2 and
  * 6.1): the same chunk records, a different rule for the rail of each chunk.
  *   0 NIC-direct : no spraying, a GPU's traffic leaves through its own NIC: rail = source local GPU
- *                  (flow id div G).  The "direct rails without multipath transport" case.
+ *                  (flow id div G).  Rails used directly, with no multipath transport.
  *   1 flow hash  : static per-flow hashing as in ECMP: every chunk of a GPU-to-GPU flow takes the rail
  *                  hash(instance, flow id) mod N.
  *   2 random spray: every chunk independently, hash(position of the chunk in the record arrays) mod N.
@@ -511,7 +511,7 @@ int oracle_assign_policy(int policy, uint64_t seed, const int64_t *chunk_off, co
 }
 
 /* ------------------------------------------------------------------------
- * Spraying execution, port choice (Algorithm 2 step 4: "select port p from NIC j* by round-robin"):
+ * Spraying execution, port choice (Algorithm 2 step 4: round-robin port choice inside the chosen NIC):
  * every rail of a node hands its chunks to its P ports (queue pairs) in turn, so the chunk that is
  * the c-th one put on its rail within its instance (c = 0, 1, ...) takes port c mod P.
  * ---------------------------------------------------------------------- */

@@ -9,7 +9,7 @@ extern "C" const char *railsched_strerror(int status)
         case RAILSCHED_OK: return "ok";
         case RAILSCHED_ERR_INVALID_ARG: return "invalid argument: a size or count is out of range";
         case RAILSCHED_ERR_NULL_PTR: return "null pointer";
-        case RAILSCHED_ERR_UNSUPPORTED: return "unsupported: beyond the limits of this build";
+        case RAILSCHED_ERR_UNSUPPORTED: return "unsupported: beyond the limits of this library";
         case RAILSCHED_ERR_CAPACITY: return "more chunks than the record arrays hold";
         case RAILSCHED_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case RAILSCHED_ERR_HIP: return "HIP runtime error";
