@@ -167,8 +167,9 @@ int railsched_chunk_sort(const int64_t *D1, int32_t batch, const railsched_topo_
  *                                                           and then chunk_w is not read and rail not written)
  *   ws        optional (NULL, 0 = none): railsched_lpt_spray_workspace_bytes(batch, topo) bytes, 256-byte aligned.
  *             Instances are independent (Sections 1 and 3.2), so the order they are worked on is free: with a
- *             workspace, batches of thousands of instances are taken longest chain first from a queue, which evens
- *             out the load of the SIMDs; the outputs do not depend on it.
+ *             workspace, batches of thousands of instances are taken longest chain first from a queue (the few far
+ *             longer than the rest on a wavefront of their own), which evens out the load of the SIMDs; the outputs
+ *             do not depend on it.
  * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (N > 64), WORKSPACE (ws given but misaligned or too small).
  * ------------------------------------------------------------------------------------------- */
 size_t railsched_lpt_spray_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo);

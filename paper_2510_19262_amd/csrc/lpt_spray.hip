@@ -29,6 +29,7 @@
 // where issue slots are the limit.  "Wide": one instance per wavefront, its state replicated in
 // every lane group, all 64 lanes streaming weights and writing rails - the shape for few instances,
 // where the latency of the chain and of HBM is the limit and more wavefronts hide more of it.
+// With a workspace a packed launch orders its instances by length and gives the few longest the wide shape.
 #include "common.h"
 #include "chunk_core.h"
 #include "lpt_core.h"
@@ -263,9 +264,37 @@ __device__ __forceinline__ void exact_steps(unsigned long long &load, const unsi
     }
 }
 
+// One instance on this wavefront, one chunk per lane and period (the loop is lpt_wide_body in lpt_core.h).
+template <int GW, bool RUNS>
+__device__ __forceinline__ void wide_instance(int inst, const int64_t *__restrict__ chunk_off, const uint32_t *__restrict__ chunk_w,
+                                              int n_inst, int N, uint8_t *__restrict__ rail, int64_t *__restrict__ S_out)
+{
+    int64_t beg = chunk_off[inst];
+    int64_t len = chunk_off[inst + 1] - beg;
+    unsigned long long base = 0;
+    if (RUNS && len > 0) {
+        // skip the leading run (already assigned round robin): start behind it with equal loads
+        const unsigned w0 = chunk_w[beg];
+        int64_t r0 = S_out[(int64_t)inst * N];
+        r0 = r0 < len ? r0 : len;
+        if (w0 != 0u && w0 <= WideLimit<GW>::value) {
+            const int64_t skip = r0 - r0 % N;
+            base = (unsigned long long)w0 * (unsigned long long)(skip / N);
+            beg += skip; len -= skip;
+        }
+    }
+    if (!RUNS) prioritise_long_chain(len, chunk_off[n_inst] / n_inst);
+    lpt_wide_body<GW, RUNS>(chunk_w + beg, rail + beg, len, base, N, S_out + (int64_t)inst * N,
+                            reinterpret_cast<const uint32_t *>(chunk_off));
+    if (!RUNS) __builtin_amdgcn_s_setprio(0);
+}
+
 // QUEUE: the wavefronts of a small resident grid fetch groups of 64/GW instances from a counter, in the order `order` lists the
 // instances (longest first): chains of similar length share a wavefront, long chains start first and short ones fill in behind
-// them - list scheduling of the instances over the SIMDs.  Without it wavefront g takes instances g*IPW .. g*IPW + IPW - 1.
+// them - list scheduling of the instances over the SIMDs.  The first next_group[2] instances of the order (the few far
+// longer than the rest, chosen by the order kernel) are taken one per wavefront before that, through the counter
+// next_group[1]: alone on a wavefront a chain advances in three quarters of the time it needs as one of 64/GW, and the
+// launch lasts as long as its longest chain.  Without QUEUE wavefront g takes instances g*IPW .. g*IPW + IPW - 1.
 template <int GW, bool RUNS, bool QUEUE>
 __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_t *__restrict__ chunk_off,
                                                                     const uint32_t *__restrict__ chunk_w, int n_inst, int N,
@@ -296,6 +325,16 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
         return (int)__builtin_amdgcn_readfirstlane((int)g);
     };
     const int64_t mean_len = chunk_off[n_inst] / n_inst;
+    if constexpr (QUEUE) {
+        const unsigned n_alone = next_group[2];
+        while (true) {
+            unsigned i = 0;
+            if (lane == 0) i = atomicAdd(next_group + 1, 1u);
+            i = (unsigned)__builtin_amdgcn_readfirstlane((int)i);
+            if (i >= n_alone) break;                // every wavefront gets here: the counter only grows
+            wide_instance<GW, RUNS>((int)order[i], chunk_off, chunk_w, n_inst, N, rail, S_out);
+        }
+    }
     for (int group = QUEUE ? next() : wave; group < n_groups; group = QUEUE ? next() : n_groups) {
     const int slot = group * IPW + lane / GW;
     const bool has_inst = slot < n_inst;
@@ -427,7 +466,10 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
 
 // Instances in descending order of chain length, to within the resolution of 512 buckets (a sixteenth of the length): counting
 // sort by one workgroup.  RUNS: S[inst*N] holds the length of the instance's leading run, which the serial kernel skips.
-// Also clears the group counter of the queue.
+// Also sets the counters of the queue: next_group[0] = first group the packed wavefronts take, [1] = 0 (next instance to run
+// alone), [2] = how many of the longest run alone: those at least half as long again as the mean and longer than a
+// 24 576th of all chunks (below that the packed chains are done before the launch's issue slots are), a whole number of
+// groups, at most 64.
 constexpr int kOrdBuckets = 512;
 __device__ __forceinline__ int order_bucket(uint64_t len)
 {
@@ -438,18 +480,22 @@ __device__ __forceinline__ int order_bucket(uint64_t len)
 }
 template <bool RUNS>
 __global__ __launch_bounds__(1024) void lpt_order_kernel(const int64_t *__restrict__ chunk_off, const int64_t *__restrict__ S, int n_inst, int N,
-                                                         uint32_t *__restrict__ order, unsigned *next_group)
+                                                         int ipw, uint32_t *__restrict__ order, unsigned *next_group)
 {
     __shared__ unsigned hist[kOrdBuckets];
+    __shared__ unsigned long long sum_len;
     for (int i = threadIdx.x; i < kOrdBuckets; i += 1024) hist[i] = 0;
-    if (threadIdx.x == 0) *next_group = 0;
+    if (threadIdx.x == 0) sum_len = 0;
     __syncthreads();
     auto length = [&](int i) {
         int64_t len = chunk_off[i + 1] - chunk_off[i];
         if (RUNS) { int64_t r0 = S[(int64_t)i * N]; r0 = r0 < len ? r0 : len; len -= r0 - r0 % N; }
         return (uint64_t)(len < 0 ? 0 : len);
     };
-    for (int i = threadIdx.x; i < n_inst; i += 1024) atomicAdd(&hist[order_bucket(length(i))], 1u);
+    unsigned long long mine = 0;
+    for (int i = threadIdx.x; i < n_inst; i += 1024) { const uint64_t len = length(i); mine += len; atomicAdd(&hist[order_bucket(len)], 1u); }
+    for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d);
+    if ((threadIdx.x & 63) == 0) atomicAdd(&sum_len, mine);
     __syncthreads();
     if (threadIdx.x < 64) {                                             // exclusive scan from the longest bucket down: 8 buckets per lane
         const int hi = kOrdBuckets - 1 - (int)threadIdx.x * 8;
@@ -460,6 +506,20 @@ __global__ __launch_bounds__(1024) void lpt_order_kernel(const int64_t *__restri
         unsigned ex = wave_exscan(sum, total);
 #pragma unroll
         for (int j = 0; j < 8; ++j) { hist[hi - j] = ex; ex += v[j]; }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        // hist[b] = instances in buckets above b = where bucket b starts in the order: everything before the bucket of the
+        // threshold is longer than the threshold
+        const uint64_t total = sum_len, mean = total / (uint64_t)n_inst;
+        uint64_t thresh = mean + mean / 2;
+        if (thresh < total / 24576) thresh = total / 24576;
+        unsigned alone = thresh > 0 ? hist[order_bucket(thresh)] : 0u;
+        alone = alone > 64u ? 64u : alone;
+        alone -= alone % (unsigned)ipw;
+        next_group[0] = alone / (unsigned)ipw;
+        next_group[1] = 0;
+        next_group[2] = alone;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < n_inst; i += 1024) order[atomicAdd(&hist[order_bucket(length(i))], 1u)] = (uint32_t)i;
@@ -478,23 +538,7 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_wide_kernel(const int64_t 
         if ((int)(threadIdx.x & 63) < N) S_out[(int64_t)inst * N + (threadIdx.x & 63)] = -1;
         return;
     }
-    int64_t beg = chunk_off[inst];
-    int64_t len = chunk_off[inst + 1] - beg;
-    unsigned long long base = 0;
-    if (RUNS && len > 0) {
-        // skip the leading run (already assigned round robin): start behind it with equal loads
-        const unsigned w0 = chunk_w[beg];
-        int64_t r0 = S_out[(int64_t)inst * N];
-        r0 = r0 < len ? r0 : len;
-        if (w0 != 0u && w0 <= WideLimit<GW>::value) {
-            const int64_t skip = r0 - r0 % N;
-            base = (unsigned long long)w0 * (unsigned long long)(skip / N);
-            beg += skip; len -= skip;
-        }
-    }
-    if (!RUNS) prioritise_long_chain(len, chunk_off[n_inst] / n_inst);
-    lpt_wide_body<GW, RUNS>(chunk_w + beg, rail + beg, len, base, N, S_out + (int64_t)inst * N,
-                            reinterpret_cast<const uint32_t *>(chunk_off));
+    wide_instance<GW, RUNS>(inst, chunk_off, chunk_w, n_inst, N, rail, S_out);
 }
 
 
@@ -510,15 +554,16 @@ static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, 
     // packed once it yields at least two wavefronts per SIMD (256 CUs x 4 SIMDs); wide below that
     const bool packed = IPW > 1 && n_inst >= (int64_t)2048 * IPW;
     if (packed && ws) {
-        // Two resident wavefronts per SIMD issue as many VALU instructions as four do (the chain of one wavefront leaves
-        // room for exactly one more), and half as many wavefronts means twice as many groups each: room to even out.
+        // Three resident wavefronts per SIMD: with the longest chains alone on a wavefront each (and at a raised issue
+        // priority) a fourth only slows those chains, which the launch waits for, and with two the SIMDs idle between
+        // dependent instructions; fewer wavefronts than groups also leaves every wavefront several groups to even out with.
         uint32_t *order = static_cast<uint32_t *>(ws);
         unsigned *counter = reinterpret_cast<unsigned *>(static_cast<char *>(ws) + align_up(sizeof(uint32_t) * (size_t)n_inst, 256));
-        hipLaunchKernelGGL((lpt_order_kernel<RUNS>), dim3(1), dim3(1024), 0, st, chunk_off, S, (int)n_inst, N, order, counter);
+        hipLaunchKernelGGL((lpt_order_kernel<RUNS>), dim3(1), dim3(1024), 0, st, chunk_off, S, (int)n_inst, N, IPW, order, counter);
         if (int rc = launch_status()) return rc;
         const int64_t waves = (n_inst + IPW - 1) / IPW;
         int64_t blocks = (waves + kLptWaves - 1) / kLptWaves;
-        const int64_t resident = 256 * 4 * 2 / kLptWaves;
+        const int64_t resident = 256 * 4 * 3 / kLptWaves;
         if (blocks > resident) blocks = resident;
         hipLaunchKernelGGL((lpt_packed_kernel<GW, RUNS, true>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
                            chunk_w, (int)n_inst, N, rail, S, capacity, order, counter);
