@@ -174,10 +174,12 @@ template <int GW> struct WideLimit {
     static constexpr unsigned value = (unsigned)((0xFFFFFFFFu >> GroupBits<GW>::S) / (unsigned)(64 + 2)) - 1u;
 };
 
+// Rail-indexed form (lane q of a group holds rail q; the greedy step is a DPP min reduction, a compare and a select):
+// the form for N > 16, where a row of 16 lanes no longer holds the rails.
 template <int GW, bool RUNS>
-__device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc, uint8_t *__restrict__ rdst, int64_t len,
-                                              unsigned long long base, int N, int64_t *__restrict__ S_row,
-                                              const uint32_t *__restrict__ spare)
+__device__ __forceinline__ void lpt_wide_body_by_rail(const uint32_t *__restrict__ wsrc, uint8_t *__restrict__ rdst, int64_t len,
+                                                      unsigned long long base, int N, int64_t *__restrict__ S_row,
+                                                      const uint32_t *__restrict__ spare)
 {
     constexpr int S = GroupBits<GW>::S;
     constexpr int P = 64;                           // chunks per period: one per lane
@@ -280,6 +282,184 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
     }
     if (len > 0) store_rails((len - 1) / ((int64_t)kWideDepth * P) * ((int64_t)kWideDepth * P));
     if (lane < N) S_row[lane] = (int64_t)(exact ? load : base + (unsigned long long)(key >> S));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sorted form, N <= 16.  The N packed keys (delta << S | rail, all different) are kept in ascending order across
+// the first N lanes of a row of 16 - as their complements t = ~key, so the list descends and the lanes behind it,
+// like the lane behind the row's end that DPP reads as zero, hold "nothing" = 0.  The rail that takes the next
+// chunk is then always the one in lane 0, and the greedy step
+//     j* = argmin LoadState,  LoadState[j*] += w
+// is "take lane 0's entry, add w, put it back where it belongs": with y = t[0] - (w << S), the entry of lane r
+// becomes the median of (t[r], t[r+1], y).  Two dependent instructions per step (the subtraction reads lane 0
+// through DPP, v_med3_u32 re-sorts) where the reduction needs five, and six issued where it needs eight: 17 ns per
+// step on a wavefront alone against 22, 26 against 46 with two wavefronts on the SIMD.  All four rows carry the
+// same list, so every lane sees y, whose low bits are the chosen rail.
+__device__ __forceinline__ unsigned umed3(unsigned a, unsigned b, unsigned c)
+{
+    unsigned r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ unsigned row_first(unsigned v)          // lane 0 of this lane's row
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x150, 0xF, 0xF, true);
+}
+__device__ __forceinline__ unsigned row_next(unsigned v)           // the next lane of the row; zero behind the row's last lane
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x101, 0xF, 0xF, true);
+}
+
+constexpr int kSortedBlock = 16;    // steps between two looks at how many chunks are left
+// kSortedBlock steps of a period.  wvS holds the period's weights, shifted past the rail bits, one per lane; the ones the block needs are
+// read out into vector registers ahead of the chain (a scalar read consumed right away stalls the wavefront, step after step).
+template <int T0>
+__device__ __forceinline__ void sorted_steps(unsigned &t, unsigned &won, unsigned wvS)
+{
+    unsigned w[kSortedBlock];
+#pragma unroll
+    for (int j = 0; j < kSortedBlock; ++j) {
+        w[j] = (unsigned)__builtin_amdgcn_readlane((int)wvS, T0 + j);
+        asm volatile("" : "+v"(w[j]));              // into a vector register: the subtraction's other operand comes through DPP
+    }
+#pragma unroll
+    for (int j = 0; j < kSortedBlock; ++j) {
+        const unsigned y = row_first(t) - w[j];
+        const unsigned nb = row_next(t);
+        won = shift_in(won, y);
+        t = umed3(t, nb, y);
+    }
+}
+// steps T0 .. of a period, block by block, for as long as chunks are left
+template <int T0>
+__device__ __forceinline__ void sorted_blocks(unsigned &t, unsigned &won, unsigned wvS, int left)
+{
+    if constexpr (T0 < 64) {
+        if (T0 < left) {                            // wave-uniform
+            sorted_steps<T0>(t, won, wvS);
+            sorted_blocks<T0 + kSortedBlock>(t, won, wvS, left);
+        }
+    }
+}
+
+template <int GW, bool RUNS>
+__device__ __forceinline__ void lpt_wide_body_sorted(const uint32_t *__restrict__ wsrc, uint8_t *__restrict__ rdst, int64_t len,
+                                                     unsigned long long base, int N, int64_t *__restrict__ S_row,
+                                                     const uint32_t *__restrict__ spare)
+{
+    static_assert(GW <= 16, "the rails of an instance fit a row of 16 lanes");
+    constexpr int S = GroupBits<GW>::S;
+    constexpr unsigned MASK = (unsigned)GW - 1u;
+    constexpr int P = 64;                           // chunks per period: one per lane
+    constexpr unsigned W_LIMIT = WideLimit<GW>::value;
+    const int lane = threadIdx.x & 63;
+    const unsigned r = (unsigned)lane & 15u;        // place in the row's list
+    const bool in_list = (int)r < N;
+    const unsigned q = (unsigned)(lane % GW);       // the exact path keeps loads by rail, lane q of a group of GW
+    const bool has_rail = (int)q < N;
+
+    unsigned t = in_list ? ~r : 0u;                 // all deltas 0: ascending rail index
+    unsigned long long load = has_rail ? 0ull : ~0ull;
+    bool exact = false;
+
+    const unsigned per_rank = (unsigned)(P / N), extra = (unsigned)(P % N);
+    const int place_of_chunk = lane % N;                                        // list place that takes chunk `lane` of a closed period
+    const int after_closed = (lane & ~15) | (int)((r + extra) % (unsigned)N);   // lane whose entry moves here when the list rotates by `extra`
+
+    // Weights move in requests of kWideDepth periods, as in the rail-indexed form above.
+    auto weight_at = [&](int64_t i) { const uint32_t *src = (i < len) ? wsrc + i : spare; return *src; };
+    unsigned cur[kWideDepth], nxt[kWideDepth], held[kWideDepth];
+    auto store_rails = [&](int64_t i0) {
+#pragma unroll
+        for (int d = 0; d < kWideDepth; ++d) {
+            const int64_t i = i0 + (int64_t)d * P + lane;
+            if (i < len) rdst[i] = (uint8_t)held[d];
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < kWideDepth; ++d) { nxt[d] = weight_at((int64_t)d * P + lane); held[d] = 0; }
+
+    for (int64_t i0 = 0; i0 < len; i0 += (int64_t)kWideDepth * P) {
+#pragma unroll
+        for (int d = 0; d < kWideDepth; ++d) {
+            asm volatile("" : "+v"(nxt[d]) : : "memory");                 // loads and stores below stay behind this wait
+            cur[d] = nxt[d];
+        }
+#pragma unroll
+        for (int d = 0; d < kWideDepth; ++d) nxt[d] = weight_at(i0 + (int64_t)(kWideDepth + d) * P + lane);
+        if (i0 > 0) store_rails(i0 - (int64_t)kWideDepth * P);
+#pragma unroll
+        for (int d = 0; d < kWideDepth; ++d) {
+            const int64_t p0 = i0 + (int64_t)d * P;
+            if (p0 >= len) break;                   // wave-uniform
+            const unsigned wv = (p0 + lane < len) ? cur[d] : 0u;
+            unsigned won = 0;
+            if (!exact && __ballot(wv > W_LIMIT) != 0ull) {
+                // leave the packed keys for good: loads by rail, 64 bits each.  Lane q takes the entry of its rail.
+                exact = true;
+                for (int place = 0; place < N; ++place) {
+                    const unsigned key = ~(unsigned)__builtin_amdgcn_readlane((int)t, place);
+                    if (has_rail && (key & MASK) == q) load = base + (unsigned long long)(key >> S);
+                }
+            }
+            bool closed = false;
+            unsigned w0 = 0;
+            if (RUNS && !exact) {
+                w0 = (unsigned)__builtin_amdgcn_readfirstlane((int)wv);
+                const unsigned dmin = (~(unsigned)__builtin_amdgcn_readfirstlane((int)t)) >> S;
+                const unsigned dmax = (~(unsigned)__builtin_amdgcn_readlane((int)t, N - 1)) >> S;
+                const bool ok = (wv == w0) && w0 != 0u && (p0 + P <= len) && (dmax - dmin) < w0;
+                closed = __ballot(!ok) == 0ull;
+            }
+            if (closed) {
+                // Equal weights from loads within one weight of each other: the list is visited front to back, round
+                // after round (see closed_period), so chunk i goes to place i mod N, place s takes floor(P/N) + (s < P mod N)
+                // chunks, and afterwards the places that took one chunk fewer come first, both parts in their old order:
+                // the list rotated by P mod N.
+                won = (~(unsigned)__shfl((int)t, place_of_chunk)) & MASK;
+                const unsigned grown = t - ((w0 * (per_rank + (r < extra ? 1u : 0u))) << S);
+                const unsigned moved = (unsigned)__shfl((int)grown, after_closed);
+                t = in_list ? moved : 0u;
+            } else if (!exact) {
+                const int left = __builtin_amdgcn_readfirstlane((len - p0 < P) ? (int)(len - p0) : P);   // the last period stops where the chunks do
+                sorted_blocks<0>(t, won, wv << S, left);
+                const int ran = (left + kSortedBlock - 1) & ~(kSortedBlock - 1);
+                if (ran < P) won = (unsigned)__shfl((int)won, lane + (P - ran));   // a short period leaves step t in lane t + P - ran
+                won = ~won & MASK;
+            } else {
+#pragma unroll 2
+                for (int s = 0; s < P; ++s) {
+                    const unsigned w = (unsigned)__builtin_amdgcn_readlane((int)wv, s);
+                    const unsigned js = group_argmin_u64<GW>(load, q);
+                    load += (q == js) ? (unsigned long long)w : 0ull;
+                    won = shift_in(won, js);
+                }
+            }
+            if (!exact) {
+                // the emptiest rail's delta moves into the base, so deltas stay below the packing limit
+                const unsigned adv = (~(unsigned)__builtin_amdgcn_readfirstlane((int)t)) >> S;
+                if (in_list) t += adv << S;
+                base += adv;
+            }
+            held[d] = won;
+        }
+    }
+    if (len > 0) store_rails((len - 1) / ((int64_t)kWideDepth * P) * ((int64_t)kWideDepth * P));
+    if (exact) {
+        if (lane < N) S_row[lane] = (int64_t)load;
+    } else if (lane < N) {
+        const unsigned key = ~t;                    // row 0's list: place `lane` holds rail key & MASK
+        S_row[key & MASK] = (int64_t)(base + (unsigned long long)(key >> S));
+    }
+}
+
+template <int GW, bool RUNS>
+__device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc, uint8_t *__restrict__ rdst, int64_t len,
+                                              unsigned long long base, int N, int64_t *__restrict__ S_row,
+                                              const uint32_t *__restrict__ spare)
+{
+    if constexpr (GW <= 16) lpt_wide_body_sorted<GW, RUNS>(wsrc, rdst, len, base, N, S_row, spare);
+    else lpt_wide_body_by_rail<GW, RUNS>(wsrc, rdst, len, base, N, S_row, spare);
 }
 
 }  // namespace rs
