@@ -180,7 +180,7 @@ def lpt_alu_roofline(total_chunks, n_inst, N, ms):
     head through DPP, neighbour through DPP, median of three, file the decision); for N > 16 the reduction form + the
     weight broadcast."""
     gw = 4 if N <= 4 else 8 if N <= 8 else 16 if N <= 16 else 32 if N <= 32 else 64
-    ipw = 64 // gw if (gw < 64 and n_inst >= 2048 * 64 // gw) else 1
+    ipw = 64 // gw if (gw < 64 and n_inst > 3 * 1024) else 1
     instr = (gw.bit_length() - 1) + 4 if ipw > 1 else 6 if N <= 16 else (gw.bit_length() - 1) + 5
     ach = total_chunks / ipw * instr / (ms * 1e-3) / 1e9
     return {"kernel": "lpt_packed_kernel<GW,false>" if ipw > 1 else "lpt_wide_kernel<GW,false>", "bound": "alu", "unit": "G wave-instr/s",

@@ -551,8 +551,10 @@ static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, 
                              int64_t *S, int64_t capacity, void *ws, hipStream_t st)
 {
     constexpr int IPW = 64 / GW;
-    // packed once it yields at least two wavefronts per SIMD (256 CUs x 4 SIMDs); wide below that
-    const bool packed = IPW > 1 && n_inst >= (int64_t)2048 * IPW;
+    // Wide while the instances make at most three wavefronts per SIMD (256 CUs x 4 SIMDs): a wide chain takes 16 ns per
+    // step alone on its SIMD, 25 with a second wavefront, 35 with a third, 46 with a fourth, and a packed wavefront
+    // 34-38 ns per step however few there are (measured, N = 4, 8, 16; N = 32: 62-74 against 64-66).
+    const bool packed = IPW > 1 && n_inst > (int64_t)3 * 1024;
     if (packed && ws) {
         // Three resident wavefronts per SIMD: with the longest chains alone on a wavefront each (and at a raised issue
         // priority) a fourth only slows those chains, which the launch waits for, and with two the SIMDs idle between
