@@ -150,9 +150,10 @@ __device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsi
 }
 
 // ================================================================================ wide shape
-// One instance per wavefront.  Every GW-lane group carries a copy of the N rail loads and runs the
-// same reduction, so all 64 lanes know each decision; lane t keeps the decision for chunk t of the
-// 64-chunk period, and weights reach the chain through v_readlane (a scalar broadcast).
+// One instance per wavefront.  Every group of lanes (GW lanes in the rail-indexed form, a row of 16 in the
+// sorted form further down) carries a copy of the N rail loads and runs the same step, so all 64 lanes know
+// each decision; lane t keeps the decision for chunk t of the 64-chunk period, and weights reach the chain
+// through v_readlane (a scalar broadcast).
 //
 // lpt_wide_body schedules the `len` chunks whose weights start at wsrc (rails to rdst) from rails that
 // all hold `base` bytes, and leaves the final loads in S_row[0..N).  Called by a whole wavefront.

@@ -28,7 +28,9 @@
 // instruction stream advances several schedulers - the shape for tens of thousands of instances,
 // where issue slots are the limit.  "Wide": one instance per wavefront, its state replicated in
 // every lane group, all 64 lanes streaming weights and writing rails - the shape for few instances,
-// where the latency of the chain and of HBM is the limit and more wavefronts hide more of it.
+// where the latency of the chain and of HBM is the limit and more wavefronts hide more of it.  For
+// N <= 16 the wide shape keeps the keys sorted across lanes instead (lpt_core.h): the argmin is then
+// always in lane 0 and a step is a subtraction and a median of three.
 // With a workspace a packed launch orders its instances by length and gives the few longest the wide shape.
 #include "common.h"
 #include "chunk_core.h"
