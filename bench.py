@@ -216,7 +216,7 @@ def time_stages_3_5(rs, torch, plan, D1, topo, B, reps, warmup):
         e = [_event(torch)]
         rs.chunk_sort(D1, topo, capacity=plan.capacity, out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort)
         e.append(_event(torch))
-        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S), capacity=plan.capacity)
+        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S), capacity=plan.capacity, ws=plan.ws_lpt)
         e.append(_event(torch))
         rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.rail, plan.S, B, topo, out=(plan.R, plan.stats), ws=plan.ws_eval,
                 capacity=plan.capacity)
@@ -248,7 +248,7 @@ def time_chunkwise(rs, torch, plan, B, topo, reps):
     t = []
     for it in range(1 + reps):
         e0 = _event(torch)
-        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(rail2, S2), chunkwise=True, capacity=plan.capacity)
+        rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(rail2, S2), chunkwise=True, capacity=plan.capacity, ws=plan.ws_lpt)
         e1 = _event(torch)
         torch.cuda.synchronize()
         if it >= 1:
@@ -354,7 +354,7 @@ def bench_resident(cfg, args, rs, W, torch, np):
             rs.traffic_matrix(plan.topk_idx, B, cfg.tokens_per_gpu, expert_gpu, cfg.payload_bytes, topo, out=plan.D1, ws=ws_tm); mark()
             rs.chunk_sort(plan.D1, topo, capacity=plan.capacity,
                           out=(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.perm), ws=plan.ws_sort); mark()
-            rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S), capacity=plan.capacity); mark()
+            rs.lpt_spray(plan.chunk_off, plan.chunk_w, B, topo, out=(plan.rail, plan.S), capacity=plan.capacity, ws=plan.ws_lpt); mark()
             rs.eval(plan.chunk_off, plan.chunk_w, plan.chunk_flow, plan.rail, plan.S, B, topo,
                     out=(plan.R, plan.stats), ws=plan.ws_eval, capacity=plan.capacity); mark()
         if events is not None:

@@ -169,7 +169,8 @@ int railsched_chunk_sort(const int64_t *D1, int32_t batch, const railsched_topo_
  *             Instances are independent (Sections 1 and 3.2), so the order they are worked on is free: with a
  *             workspace, batches of thousands of instances are taken longest chain first from a queue (the few far
  *             longer than the rest on a wavefront of their own), which evens out the load of the SIMDs; the outputs
- *             do not depend on it.
+ *             do not depend on it.  It pays for railsched_lpt_spray_chunkwise; railsched_lpt_spray, whose chains
+ *             are what the closed forms leave over, accepts it and leaves it unused.
  * Errors: NULL_PTR, INVALID_ARG, UNSUPPORTED (N > 64), WORKSPACE (ws given but misaligned or too small).
  * ------------------------------------------------------------------------------------------- */
 size_t railsched_lpt_spray_workspace_bytes(int32_t batch, const railsched_topo_t *h_topo);

@@ -557,7 +557,7 @@ static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, 
     // step alone on its SIMD, 25 with a second wavefront, 35 with a third, 46 with a fourth, and a packed wavefront
     // 34-38 ns per step however few there are (measured, N = 4, 8, 16; N = 32: 62-74 against 64-66).
     const bool packed = IPW > 1 && n_inst > (int64_t)3 * 1024;
-    if (packed && ws) {
+    if (packed && ws && !RUNS) {                    // behind the closed forms the chains are a few hundred tails each: nothing to order
         // Three resident wavefronts per SIMD: with the longest chains alone on a wavefront each (and at a raised issue
         // priority) a fourth only slows those chains, which the launch waits for, and with two the SIMDs idle between
         // dependent instructions; fewer wavefronts than groups also leaves every wavefront several groups to even out with.
