@@ -50,7 +50,8 @@ int lpt_serial_after_leading_runs(const int64_t *chunk_off, const uint32_t *chun
                                   int64_t *S, int64_t capacity, hipStream_t st);   // lpt_spray.hip
 void cs_ws_layout(int64_t n_inst, int64_t NF, size_t off[6]);  // chunk_sort.hip
 
-constexpr int kSsThreads = 256;
+constexpr int kSsThreads = 512;         // one wavefront on the chain, seven on the records (three: 6 us more per call on 256 instances of 7 K chunks)
+constexpr int kSlThreads = 256;         // closed-form receive loads of large batches
 constexpr int kSsMaxInst = 1024;        // instances whose counts one workgroup adds up
 constexpr int kSsMaxFlows = 2048;       // N*G of an instance held in LDS
 constexpr int kSsMaxAvg = 32768;        // chunks per instance (capacity / instances) above which one workgroup is too few
@@ -252,19 +253,19 @@ __global__ void sl_run_end_kernel(CsArgs a, int64_t *S)
 
 // Receive loads of one instance into its workspace slot [G + 1]: the leading run (positions below
 // n_full - n_full mod N, rails i mod N) flow by flow in closed form, the chunks behind it from their records.
-__global__ __launch_bounds__(kSsThreads) void sl_recv_kernel(CsArgs a, SsArgs x)
+__global__ __launch_bounds__(kSlThreads) void sl_recv_kernel(CsArgs a, SsArgs x)
 {
     extern __shared__ unsigned long long sl_bins[];
     if (a.chunk_off[a.n_inst] > a.capacity) return;                      // the record arrays hold nothing
     const int inst = blockIdx.x, tid = threadIdx.x, N = a.N;
-    for (int i = tid; i < a.G; i += kSsThreads) sl_bins[i] = 0;
+    for (int i = tid; i < a.G; i += kSlThreads) sl_bins[i] = 0;
     __syncthreads();
     const uint32_t n_full = (uint32_t)a.cnt_full[inst], n_all = (uint32_t)a.cnt_all[inst];
     const uint32_t lead = n_full - n_full % (uint32_t)N;
     const uint32_t cw = (uint32_t)a.C;
     const int64_t out0 = a.chunk_off[inst];
     const uint32_t *fs = a.full_start + (int64_t)inst * a.NF;
-    for (int f = tid; f < a.NF; f += kSsThreads) {
+    for (int f = tid; f < a.NF; f += kSlThreads) {
         const uint32_t s = fs[f];
         uint32_t e = f + 1 < a.NF ? fs[f + 1] : n_full;
         e = e < lead ? e : lead;
@@ -276,14 +277,14 @@ __global__ __launch_bounds__(kSsThreads) void sl_recv_kernel(CsArgs a, SsArgs x)
             if (c) atomicAdd(&sl_bins[node * N + n], (unsigned long long)c * (unsigned long long)cw);
         }
     }
-    for (uint32_t p = lead + tid; p < n_all; p += kSsThreads) {
+    for (uint32_t p = lead + tid; p < n_all; p += kSlThreads) {
         const unsigned r = x.rail[out0 + p];
         const int node = ss_dst_node(a, x, a.chunk_flow[out0 + p]);
         if (node < a.M && r < (unsigned)N) atomicAdd(&sl_bins[node * N + r], (unsigned long long)a.chunk_w[out0 + p]);
     }
     __syncthreads();
     int64_t *slot = x.partial + (int64_t)inst * (a.G + 1);
-    for (int i = tid; i < a.G; i += kSsThreads) slot[i] = (int64_t)sl_bins[i];
+    for (int i = tid; i < a.G; i += kSlThreads) slot[i] = (int64_t)sl_bins[i];
     if (tid == 0) slot[a.G] = n_all ? (int64_t)a.chunk_w[out0] : 0;      // records are sorted: the first is the largest
 }
 
@@ -361,7 +362,7 @@ static int schedule_run(const int64_t *D1, int32_t batch, const railsched_topo_t
                                     (int)lds) != hipSuccess)
                 return RAILSCHED_ERR_HIP;
         }
-        hipLaunchKernelGGL(sl_recv_kernel, dim3((unsigned)n_inst), dim3(kSsThreads), lds, st, a, x);
+        hipLaunchKernelGGL(sl_recv_kernel, dim3((unsigned)n_inst), dim3(kSlThreads), lds, st, a, x);
         if (int rc = launch_status()) return rc;
         return launch_eval_reduce(e, batch, st);
     }
