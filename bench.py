@@ -177,11 +177,11 @@ def lpt_alu_roofline(total_chunks, n_inst, N, ms):
     Packed shape (64/GW instances per wavefront, rail loads by lane): ceil(log2 GW) cross-lane mins, the add, compare, select
     and the instruction that files the decision.  Wide shape (one instance per wavefront): for N <= 16 the loads are kept as a
     sorted list across lanes and a step is 6 instructions (weight out of its lane, into a vector register, subtract from the
-    head through DPP, neighbour through DPP, median of three, file the decision); for N > 16 the reduction form + the
-    weight broadcast."""
+    head through DPP, neighbour through DPP, median of three, file the decision); for N > 16 the list spans the wavefront and
+    its head takes one more instruction (v_readfirstlane)."""
     gw = 4 if N <= 4 else 8 if N <= 8 else 16 if N <= 16 else 32 if N <= 32 else 64
-    ipw = 64 // gw if (gw < 64 and n_inst > 3 * 1024) else 1
-    instr = (gw.bit_length() - 1) + 4 if ipw > 1 else 6 if N <= 16 else (gw.bit_length() - 1) + 5
+    ipw = 64 // gw if (gw < 64 and n_inst > (3 if gw <= 16 else 5) * 1024) else 1
+    instr = (gw.bit_length() - 1) + 4 if ipw > 1 else 6 if N <= 16 else 7
     ach = total_chunks / ipw * instr / (ms * 1e-3) / 1e9
     return {"kernel": "lpt_packed_kernel<GW,false>" if ipw > 1 else "lpt_wide_kernel<GW,false>", "bound": "alu", "unit": "G wave-instr/s",
             "peak": VALU_PEAK_GIPS, "achieved": ach, "frac": ach / VALU_PEAK_GIPS, "avg_launch_ms": ms,

@@ -150,10 +150,9 @@ __device__ __forceinline__ unsigned rail_of_rank(unsigned rank, unsigned q, unsi
 }
 
 // ================================================================================ wide shape
-// One instance per wavefront.  Every group of lanes (GW lanes in the rail-indexed form, a row of 16 in the
-// sorted form further down) carries a copy of the N rail loads and runs the same step, so all 64 lanes know
-// each decision; lane t keeps the decision for chunk t of the 64-chunk period, and weights reach the chain
-// through v_readlane (a scalar broadcast).
+// One instance per wavefront.  Every row of 16 lanes (the whole wavefront for N > 16) carries the N rail
+// loads and runs the same step, so all 64 lanes know each decision; lane t keeps the decision for chunk t of
+// the 64-chunk period, and weights reach the chain through v_readlane (a scalar broadcast).
 //
 // lpt_wide_body schedules the `len` chunks whose weights start at wsrc (rails to rdst) from rails that
 // all hold `base` bytes, and leaves the final loads in S_row[0..N).  Called by a whole wavefront.
@@ -175,146 +174,42 @@ template <int GW> struct WideLimit {
     static constexpr unsigned value = (unsigned)((0xFFFFFFFFu >> GroupBits<GW>::S) / (unsigned)(64 + 2)) - 1u;
 };
 
-// Rail-indexed form (lane q of a group holds rail q; the greedy step is a DPP min reduction, a compare and a select):
-// the form for N > 16, where a row of 16 lanes no longer holds the rails.
-template <int GW, bool RUNS>
-__device__ __forceinline__ void lpt_wide_body_by_rail(const uint32_t *__restrict__ wsrc, uint8_t *__restrict__ rdst, int64_t len,
-                                                      unsigned long long base, int N, int64_t *__restrict__ S_row,
-                                                      const uint32_t *__restrict__ spare)
-{
-    constexpr int S = GroupBits<GW>::S;
-    constexpr int P = 64;                           // chunks per period: one per lane
-    constexpr unsigned W_LIMIT = WideLimit<GW>::value;
-    const int lane = threadIdx.x & 63;
-    const unsigned q = (unsigned)(lane % GW);
-    const bool has_rail = (int)q < N;
-
-    unsigned key = has_rail ? q : 0xFFFFFFFFu;
-    unsigned long long load = has_rail ? 0ull : ~0ull;
-    bool exact = false;
-
-    const unsigned per_rank = (unsigned)(P / N), extra = (unsigned)(P % N);
-    const unsigned want = (unsigned)lane % (unsigned)N;
-
-    // Weights move in requests of kWideDepth periods: the request for the next periods is issued before the chains of
-    // the current ones and taken in behind them, so its loads have kWideDepth chains (about 3 us) to arrive.  Lanes
-    // past the end load *spare (any word that exists, in the memory wsrc points into) instead of skipping the load,
-    // and the value is masked where it is used: a branch around the loads made the compiler wait for everything in
-    // flight in front of every chain.  The rails of the periods just done are stored right behind the point where
-    // the request is taken in, so they are never the newest thing in flight at a wait.
-    auto weight_at = [&](int64_t i) { const uint32_t *src = (i < len) ? wsrc + i : spare; return *src; };
-    unsigned cur[kWideDepth], nxt[kWideDepth], held[kWideDepth];
-    auto store_rails = [&](int64_t i0) {
-#pragma unroll
-        for (int d = 0; d < kWideDepth; ++d) {
-            const int64_t i = i0 + (int64_t)d * P + lane;
-            if (i < len) rdst[i] = (uint8_t)held[d];
-        }
-    };
-#pragma unroll
-    for (int d = 0; d < kWideDepth; ++d) { nxt[d] = weight_at((int64_t)d * P + lane); held[d] = 0; }
-
-    for (int64_t i0 = 0; i0 < len; i0 += (int64_t)kWideDepth * P) {
-#pragma unroll
-        for (int d = 0; d < kWideDepth; ++d) {
-            asm volatile("" : "+v"(nxt[d]) : : "memory");                 // loads and stores below stay behind this wait
-            cur[d] = nxt[d];
-        }
-#pragma unroll
-        for (int d = 0; d < kWideDepth; ++d) nxt[d] = weight_at(i0 + (int64_t)(kWideDepth + d) * P + lane);
-        if (i0 > 0) store_rails(i0 - (int64_t)kWideDepth * P);
-#pragma unroll
-        for (int d = 0; d < kWideDepth; ++d) {
-            const int64_t p0 = i0 + (int64_t)d * P;
-            if (p0 >= len) break;                   // wave-uniform
-            const unsigned wv = (p0 + lane < len) ? cur[d] : 0u;
-            unsigned won = 0;
-            if (!exact && __ballot(wv > W_LIMIT) != 0ull) {
-                exact = true;
-                if (has_rail) load = base + (unsigned long long)(key >> S);
-            }
-            bool closed = false;
-            unsigned w0 = 0;
-            if (RUNS && !exact) {
-                w0 = (unsigned)__builtin_amdgcn_readfirstlane((int)wv);
-                const unsigned dmin = group_min_u32<GW>(key) >> S;
-                const unsigned dmax = group_max_u32<GW>(has_rail ? (key >> S) : 0u);
-                const bool ok = (wv == w0) && w0 != 0u && (p0 + P <= len) && (dmax - dmin) < w0;
-                closed = __ballot(!ok) == 0ull;
-            }
-            if (closed) {
-                const unsigned rank = closed_period<GW>(key, has_rail, w0, per_rank, extra);
-                won = rail_of_rank<GW>(rank, q, want);
-            } else if (!exact) {
-                const int left = __builtin_amdgcn_readfirstlane((len - p0 < P) ? (int)(len - p0) : P);   // the last period stops where the chunks do
-                // unrolled over the whole period, so that every weight is read out of a fixed lane (a lane index in
-                // a register costs the chain an eighth more per step); left in blocks of 8 steps when the chunks end
-#pragma unroll
-                for (int t0 = 0; t0 < P; t0 += 8) {
-                    if (t0 >= left) break;          // wave-uniform
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const unsigned wS = (unsigned)__builtin_amdgcn_readlane((int)wv, t0 + u) << S;
-                        unsigned bumped = key + wS;
-                        asm volatile("" : "+v"(bumped));   // keep the sum off the chain: stops the rewrite into key + select(w, 0)
-                        const unsigned m = group_min_u32<GW>(key);
-                        won = shift_in(won, m);
-                        key = (key == m) ? bumped : key;
-                    }
-                }
-                const int ran = (left + 7) & ~7;
-                if (ran < P) won = (unsigned)__shfl((int)won, lane + (P - ran));   // a short period leaves step t in lane t + P - ran
-                won &= (unsigned)(GW - 1);
-            } else {
-#pragma unroll 2
-                for (int t = 0; t < P; ++t) {
-                    const unsigned w = (unsigned)__builtin_amdgcn_readlane((int)wv, t);
-                    const unsigned js = group_argmin_u64<GW>(load, q);
-                    load += (q == js) ? (unsigned long long)w : 0ull;
-                    won = shift_in(won, js);
-                }
-            }
-            if (!exact) {
-                const unsigned adv = group_min_u32<GW>(key) >> S;
-                if (has_rail) { key -= adv << S; base += adv; }
-            }
-            held[d] = won;
-        }
-    }
-    if (len > 0) store_rails((len - 1) / ((int64_t)kWideDepth * P) * ((int64_t)kWideDepth * P));
-    if (lane < N) S_row[lane] = (int64_t)(exact ? load : base + (unsigned long long)(key >> S));
-}
-
 // ---------------------------------------------------------------------------------------------
-// Sorted form, N <= 16.  The N packed keys (delta << S | rail, all different) are kept in ascending order across
-// the first N lanes of a row of 16 - as their complements t = ~key, so the list descends and the lanes behind it,
-// like the lane behind the row's end that DPP reads as zero, hold "nothing" = 0.  The rail that takes the next
-// chunk is then always the one in lane 0, and the greedy step
+// Sorted form.  The N packed keys (delta << S | rail, all different) are kept in ascending order across the first N
+// lanes of a row of 16 (N <= 16; of the wavefront otherwise) - as their complements t = ~key, so the list descends and
+// the lanes behind it, like the lane behind the end that DPP reads as zero, hold "nothing" = 0.  The rail that takes
+// the next chunk is then always the one in lane 0, and the greedy step
 //     j* = argmin LoadState,  LoadState[j*] += w
 // is "take lane 0's entry, add w, put it back where it belongs": with y = t[0] - (w << S), the entry of lane r
 // becomes the median of (t[r], t[r+1], y).  Two dependent instructions per step (the subtraction reads lane 0
-// through DPP, v_med3_u32 re-sorts) where the reduction needs five, and six issued where it needs eight: 17 ns per
-// step on a wavefront alone against 22, 26 against 46 with two wavefronts on the SIMD.  All four rows carry the
-// same list, so every lane sees y, whose low bits are the chosen rail.
+// through DPP, v_med3_u32 re-sorts) where a min reduction over the lanes, a compare and a select need five, and six
+// issued where those need eight: 16 ns per step on a wavefront alone against 22, 26 against 46 with two wavefronts on
+// the SIMD.  With N <= 16 all four rows carry the same list, so every lane sees y, whose low bits are the chosen rail.
 __device__ __forceinline__ unsigned umed3(unsigned a, unsigned b, unsigned c)
 {
     unsigned r;
     asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
-__device__ __forceinline__ unsigned row_first(unsigned v)          // lane 0 of this lane's row
+// ROW: the list lives in a row of 16 lanes (N <= 16; the wavefront's four rows carry copies); otherwise it spans the wavefront
+// (N <= 64), its head comes through the scalar unit and a step costs 30 ns instead of 16 - still half the reduction form's 62.
+template <bool ROW>
+__device__ __forceinline__ unsigned list_head(unsigned v)          // the list's first entry
 {
-    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x150, 0xF, 0xF, true);
+    if constexpr (ROW) return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x150, 0xF, 0xF, true);   // row_newbcast:0
+    else return (unsigned)__builtin_amdgcn_readfirstlane((int)v);
 }
-__device__ __forceinline__ unsigned row_next(unsigned v)           // the next lane of the row; zero behind the row's last lane
+template <bool ROW>
+__device__ __forceinline__ unsigned list_next(unsigned v)          // the next lane's entry; zero behind the last lane of the row / wavefront
 {
-    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x101, 0xF, 0xF, true);
+    if constexpr (ROW) return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x101, 0xF, 0xF, true);   // row_shl:1
+    else return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x130, 0xF, 0xF, true);                  // wave_shl:1
 }
 
 constexpr int kSortedBlock = 16;    // steps between two looks at how many chunks are left
 // kSortedBlock steps of a period.  wvS holds the period's weights, shifted past the rail bits, one per lane; the ones the block needs are
 // read out into vector registers ahead of the chain (a scalar read consumed right away stalls the wavefront, step after step).
-template <int T0>
+template <bool ROW, int T0>
 __device__ __forceinline__ void sorted_steps(unsigned &t, unsigned &won, unsigned wvS)
 {
     unsigned w[kSortedBlock];
@@ -325,20 +220,20 @@ __device__ __forceinline__ void sorted_steps(unsigned &t, unsigned &won, unsigne
     }
 #pragma unroll
     for (int j = 0; j < kSortedBlock; ++j) {
-        const unsigned y = row_first(t) - w[j];
-        const unsigned nb = row_next(t);
+        const unsigned y = list_head<ROW>(t) - w[j];
+        const unsigned nb = list_next<ROW>(t);
         won = shift_in(won, y);
         t = umed3(t, nb, y);
     }
 }
 // steps T0 .. of a period, block by block, for as long as chunks are left
-template <int T0>
+template <bool ROW, int T0>
 __device__ __forceinline__ void sorted_blocks(unsigned &t, unsigned &won, unsigned wvS, int left)
 {
     if constexpr (T0 < 64) {
         if (T0 < left) {                            // wave-uniform
-            sorted_steps<T0>(t, won, wvS);
-            sorted_blocks<T0 + kSortedBlock>(t, won, wvS, left);
+            sorted_steps<ROW, T0>(t, won, wvS);
+            sorted_blocks<ROW, T0 + kSortedBlock>(t, won, wvS, left);
         }
     }
 }
@@ -348,13 +243,13 @@ __device__ __forceinline__ void lpt_wide_body_sorted(const uint32_t *__restrict_
                                                      unsigned long long base, int N, int64_t *__restrict__ S_row,
                                                      const uint32_t *__restrict__ spare)
 {
-    static_assert(GW <= 16, "the rails of an instance fit a row of 16 lanes");
+    constexpr bool ROW = GW <= 16;
     constexpr int S = GroupBits<GW>::S;
     constexpr unsigned MASK = (unsigned)GW - 1u;
     constexpr int P = 64;                           // chunks per period: one per lane
     constexpr unsigned W_LIMIT = WideLimit<GW>::value;
     const int lane = threadIdx.x & 63;
-    const unsigned r = (unsigned)lane & 15u;        // place in the row's list
+    const unsigned r = ROW ? (unsigned)lane & 15u : (unsigned)lane;   // place in the list
     const bool in_list = (int)r < N;
     const unsigned q = (unsigned)(lane % GW);       // the exact path keeps loads by rail, lane q of a group of GW
     const bool has_rail = (int)q < N;
@@ -365,7 +260,7 @@ __device__ __forceinline__ void lpt_wide_body_sorted(const uint32_t *__restrict_
 
     const unsigned per_rank = (unsigned)(P / N), extra = (unsigned)(P % N);
     const int place_of_chunk = lane % N;                                        // list place that takes chunk `lane` of a closed period
-    const int after_closed = (lane & ~15) | (int)((r + extra) % (unsigned)N);   // lane whose entry moves here when the list rotates by `extra`
+    const int after_closed = (ROW ? (lane & ~15) : 0) | (int)((r + extra) % (unsigned)N);   // lane whose entry moves here when the list rotates by `extra`
 
     // Weights move in requests of kWideDepth periods, as in the rail-indexed form above.
     auto weight_at = [&](int64_t i) { const uint32_t *src = (i < len) ? wsrc + i : spare; return *src; };
@@ -423,7 +318,7 @@ __device__ __forceinline__ void lpt_wide_body_sorted(const uint32_t *__restrict_
                 t = in_list ? moved : 0u;
             } else if (!exact) {
                 const int left = __builtin_amdgcn_readfirstlane((len - p0 < P) ? (int)(len - p0) : P);   // the last period stops where the chunks do
-                sorted_blocks<0>(t, won, wv << S, left);
+                sorted_blocks<ROW, 0>(t, won, wv << S, left);
                 const int ran = (left + kSortedBlock - 1) & ~(kSortedBlock - 1);
                 if (ran < P) won = (unsigned)__shfl((int)won, lane + (P - ran));   // a short period leaves step t in lane t + P - ran
                 won = ~won & MASK;
@@ -459,8 +354,7 @@ __device__ __forceinline__ void lpt_wide_body(const uint32_t *__restrict__ wsrc,
                                               unsigned long long base, int N, int64_t *__restrict__ S_row,
                                               const uint32_t *__restrict__ spare)
 {
-    if constexpr (GW <= 16) lpt_wide_body_sorted<GW, RUNS>(wsrc, rdst, len, base, N, S_row, spare);
-    else lpt_wide_body_by_rail<GW, RUNS>(wsrc, rdst, len, base, N, S_row, spare);
+    lpt_wide_body_sorted<GW, RUNS>(wsrc, rdst, len, base, N, S_row, spare);
 }
 
 }  // namespace rs

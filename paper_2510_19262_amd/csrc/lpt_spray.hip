@@ -27,9 +27,9 @@
 // Two launch shapes.  "Packed": 64/GW instances share a wavefront, one per lane group, so one
 // instruction stream advances several schedulers - the shape for tens of thousands of instances,
 // where issue slots are the limit.  "Wide": one instance per wavefront, its state replicated in
-// every lane group, all 64 lanes streaming weights and writing rails - the shape for few instances,
-// where the latency of the chain and of HBM is the limit and more wavefronts hide more of it.  For
-// N <= 16 the wide shape keeps the keys sorted across lanes instead (lpt_core.h): the argmin is then
+// every row of lanes, all 64 lanes streaming weights and writing rails - the shape for few instances,
+// where the latency of the chain and of HBM is the limit and more wavefronts hide more of it.  The
+// wide shape keeps the keys sorted across lanes instead of by rail (lpt_core.h): the argmin is then
 // always in lane 0 and a step is a subtraction and a median of three.
 // With a workspace a packed launch orders its instances by length and gives the few longest the wide shape.
 #include "common.h"
@@ -555,8 +555,9 @@ static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, 
     constexpr int IPW = 64 / GW;
     // Wide while the instances make at most three wavefronts per SIMD (256 CUs x 4 SIMDs): a wide chain takes 16 ns per
     // step alone on its SIMD, 25 with a second wavefront, 35 with a third, 46 with a fourth, and a packed wavefront
-    // 34-38 ns per step however few there are (measured, N = 4, 8, 16; N = 32: 62-74 against 64-66).
-    const bool packed = IPW > 1 && n_inst > (int64_t)3 * 1024;
+    // 34-38 ns per step however few there are (measured, N = 4, 8, 16).  N = 32: 22, 28, 42, 53, 75 (six) against
+    // 64-74 packed, so up to five.
+    const bool packed = IPW > 1 && n_inst > (int64_t)(GW <= 16 ? 3 : 5) * 1024;
     if (packed && ws && !RUNS) {                    // behind the closed forms the chains are a few hundred tails each: nothing to order
         // Three resident wavefronts per SIMD: with the longest chains alone on a wavefront each (and at a raised issue
         // priority) a fourth only slows those chains, which the launch waits for, and with two the SIMDs idle between
