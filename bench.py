@@ -173,17 +173,24 @@ def hbm_roofline(kernel, workload, algorithmic_bytes, ms, note=None, counted=Non
 
 
 def lpt_alu_roofline(total_chunks, n_inst, N, ms):
-    """The per-chunk LPT kernel against the VALU issue rate, in instructions the greedy step needs per wavefront.
-    Packed shape (64/GW instances per wavefront, rail loads by lane): ceil(log2 GW) cross-lane mins, the add, compare, select
-    and the instruction that files the decision.  Wide shape (one instance per wavefront): for N <= 16 the loads are kept as a
-    sorted list across lanes and a step is 6 instructions (weight out of its lane, into a vector register, subtract from the
-    head through DPP, neighbour through DPP, median of three, file the decision); for N > 16 the list spans the wavefront and
-    its head takes one more instruction (v_readfirstlane)."""
+    """The per-chunk LPT kernel against the VALU issue rate, in instructions the greedy step needs per wavefront.  The
+    library picks the shape by the number of instances (mirrored here):
+    wide (one instance per wavefront, loads kept as a sorted list across lanes): 6 instructions per step (weight out of
+      its lane, into a vector register, subtract from the head through DPP, neighbour through DPP, median of three, file
+      the decision), 7 for N > 16 (the head through v_readfirstlane);
+    rows (N <= 16, four instances per wavefront, one sorted list per row of 16 lanes): 5 per step for the four;
+    packed (64/GW instances per wavefront, loads by rail): ceil(log2 GW) cross-lane mins, the add, compare, select and the
+      instruction that files the decision, for the 64/GW."""
     gw = 4 if N <= 4 else 8 if N <= 8 else 16 if N <= 16 else 32 if N <= 32 else 64
-    ipw = 64 // gw if (gw < 64 and n_inst > (3 if gw <= 16 else 5) * 1024) else 1
-    instr = (gw.bit_length() - 1) + 4 if ipw > 1 else 6 if N <= 16 else 7
+    if gw <= 16:
+        shape = "wide" if n_inst <= 1024 else "rows" if (gw == 16 or n_inst <= 16384) else "packed"
+    else:
+        shape = "packed" if (gw == 32 and n_inst > 5 * 1024) else "wide"
+    ipw = {"wide": 1, "rows": 4, "packed": 64 // gw}[shape]
+    instr = {"wide": 6 if N <= 16 else 7, "rows": 5, "packed": (gw.bit_length() - 1) + 4}[shape]
     ach = total_chunks / ipw * instr / (ms * 1e-3) / 1e9
-    return {"kernel": "lpt_packed_kernel<GW,false>" if ipw > 1 else "lpt_wide_kernel<GW,false>", "bound": "alu", "unit": "G wave-instr/s",
+    return {"kernel": {"wide": "lpt_wide_kernel<GW,false>", "rows": "lpt_rows_kernel<GW,false,...>", "packed": "lpt_packed_kernel<GW,false,...>"}[shape],
+            "bound": "alu", "unit": "G wave-instr/s",
             "peak": VALU_PEAK_GIPS, "achieved": ach, "frac": ach / VALU_PEAK_GIPS, "avg_launch_ms": ms,
             "instructions_per_step": instr, "instances_per_wavefront": ipw, "wavefronts": -(-n_inst // ipw),
             "note": "algorithmic VALU instructions of the greedy step; with fewer wavefronts than 4 per SIMD (1024 SIMDs) the "

@@ -466,6 +466,216 @@ __global__ __launch_bounds__(64 * kLptWaves) void lpt_packed_kernel(const int64_
     }
 }
 
+// ================================================================================ rows shape (N <= 16)
+// Four instances per wavefront, one per row of 16 lanes, each in the sorted form of lpt_core.h: a row's first N lanes hold
+// its instance's keys in ascending order (as complements), the greedy step is "head plus weight, re-inserted by a median
+// of three", five instructions for the four instances (weight to its row through DPP, subtract from the head through DPP,
+// neighbour through DPP, v_med3_u32, and a DPP row shift that files the decision) with two of them on the chain - against
+// eight and an LDS swizzle with five on the chain for eight instances in the packed shape.  Per instance that is a tenth
+// more issue slots and less than half the latency: the shape for batches that the wide shape would crowd and that leave the
+// packed one short of wavefronts.  Weights of a period sit four per lane (chunk c*16 + r in register c of lane r), as in
+// the packed shape with groups of 16, whose exact 64-bit path (exact_steps) and queue this kernel shares.
+template <int T>
+__device__ __forceinline__ unsigned row_lane(unsigned v)           // lane T of this lane's row
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x150 + T, 0xF, 0xF, true);
+}
+__device__ __forceinline__ unsigned row_shift_in(unsigned reg, unsigned v)   // every lane takes the next lane's reg, the row's last lane v
+{
+    return (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)reg, 0x101, 0xF, 0xF, false);
+}
+// the 16 steps whose weights (shifted past the rail bits) sit in wS, one per lane of the row
+template <int T>
+__device__ __forceinline__ void rows_steps(unsigned &t, unsigned &won, unsigned wS)
+{
+    if constexpr (T < 16) {
+        const unsigned w = row_lane<T>(wS);
+        const unsigned y = list_head<true>(t) - w;
+        const unsigned nb = list_next<true>(t);
+        won = row_shift_in(won, y);
+        t = umed3(t, nb, y);
+        rows_steps<T + 1>(t, won, wS);
+    }
+}
+
+template <int GW, bool RUNS, bool QUEUE>
+__global__ __launch_bounds__(64 * kLptWaves) void lpt_rows_kernel(const int64_t *__restrict__ chunk_off,
+                                                                  const uint32_t *__restrict__ chunk_w, int n_inst, int N,
+                                                                  uint8_t *__restrict__ rail, int64_t *__restrict__ S_out,
+                                                                  int64_t capacity, const uint32_t *__restrict__ order,
+                                                                  unsigned *next_group)
+{
+    static_assert(GW <= 16, "an instance's rails fit a row of 16 lanes");
+    constexpr int S = GroupBits<GW>::S;             // rail bits of a key (the packing limit follows from them)
+    constexpr unsigned MASK = (unsigned)GW - 1u;
+    constexpr int LW = 16, IPW = 64 / LW, STEP = kBatch, REGS = STEP / LW;
+    constexpr unsigned W_LIMIT = (unsigned)((0xFFFFFFFFu >> S) / (unsigned)(STEP + 2)) - 1u;
+
+    const int lane = threadIdx.x & 63;
+    const unsigned r = (unsigned)lane & 15u;
+    const int row_base = lane & ~15;
+    const int wave = (int)((blockIdx.x * (unsigned)kLptWaves) + (threadIdx.x >> 6));
+    if (chunk_off[n_inst] > capacity) {             // more chunks than the record arrays hold: touch none, mark the loads
+        const int64_t n = (int64_t)n_inst * N, stride = (int64_t)gridDim.x * blockDim.x;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) S_out[i] = -1;
+        return;
+    }
+    const int n_groups = (n_inst + IPW - 1) / IPW;
+    auto next = [&]() {
+        unsigned g = 0;
+        if (lane == 0) g = atomicAdd(next_group, 1u);
+        return (int)__builtin_amdgcn_readfirstlane((int)g);
+    };
+    const int64_t mean_len = chunk_off[n_inst] / n_inst;
+    if constexpr (QUEUE) {
+        const unsigned n_alone = next_group[2];
+        while (true) {
+            unsigned i = 0;
+            if (lane == 0) i = atomicAdd(next_group + 1, 1u);
+            i = (unsigned)__builtin_amdgcn_readfirstlane((int)i);
+            if (i >= n_alone) break;                // every wavefront gets here: the counter only grows
+            wide_instance<GW, RUNS>((int)order[i], chunk_off, chunk_w, n_inst, N, rail, S_out);
+        }
+    }
+    const unsigned per_rank = (unsigned)(STEP / N), extra = (unsigned)(STEP % N);
+    const int after_closed = row_base | (int)((r + extra) % (unsigned)N);       // lane whose entry moves here when a list rotates by `extra`
+    int place_of_chunk[REGS];                                                   // lane whose entry names the rail of chunk c*16 + r of a closed period
+#pragma unroll
+    for (int c = 0; c < REGS; ++c) place_of_chunk[c] = row_base | (int)(((unsigned)(c * LW) + r) % (unsigned)N);
+
+    for (int group = QUEUE ? next() : wave; group < n_groups; group = QUEUE ? next() : n_groups) {
+    const int slot = group * IPW + lane / LW;
+    const bool has_inst = slot < n_inst;
+    const int inst = has_inst ? (QUEUE ? (int)order[slot] : slot) : 0;
+    const bool in_list = has_inst && (int)r < N;
+    int64_t beg = has_inst ? chunk_off[inst] : 0;
+    int64_t len = has_inst ? chunk_off[inst + 1] - beg : 0;
+    unsigned long long base = 0;
+    if (RUNS && len > 0) {
+        // skip the leading run (already assigned round robin): start behind it with equal loads
+        const unsigned w0 = chunk_w[beg];
+        int64_t r0 = S_out[(int64_t)inst * N];
+        r0 = r0 < len ? r0 : len;
+        if (w0 != 0u && w0 <= W_LIMIT) {
+            const int64_t skip = r0 - r0 % N;
+            base = (unsigned long long)w0 * (unsigned long long)(skip / N);
+            beg += skip; len -= skip;
+        }
+    }
+    int64_t max_len = len;                          // the wave runs as long as its longest instance
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) { const int64_t o = __shfl_xor(max_len, d); max_len = o > max_len ? o : max_len; }
+    if (!RUNS) prioritise_long_chain(max_len, mean_len);
+
+    unsigned t = in_list ? ~r : 0u;                 // all deltas 0: ascending rail index
+    unsigned long long load = in_list ? 0ull : ~0ull;   // exact path: loads by rail, lane r of the row
+    bool exact = false;                             // wave-uniform
+
+    // weights: as in the packed shape (requests two periods ahead, no branch around the loads)
+    const uint32_t *const spare = reinterpret_cast<const uint32_t *>(chunk_off);
+    unsigned in_period[REGS];
+#pragma unroll
+    for (int c = 0; c < REGS; ++c) in_period[c] = (unsigned)(c * LW) + r;
+    auto left_at = [&](int64_t i0) {
+        const int64_t d = len - i0;
+        return (unsigned)(d < 0 ? 0 : d > (int64_t)(1 << 30) ? (int64_t)(1 << 30) : d);
+    };
+    auto request = [&](int64_t i0, unsigned left, unsigned (&wv)[REGS]) {
+        const uint32_t *from = left ? chunk_w + beg + i0 : spare;
+        const unsigned last = left ? left - 1u : 0u;
+#pragma unroll
+        for (int c = 0; c < REGS; ++c) wv[c] = from[in_period[c] < last ? in_period[c] : last];
+    };
+    auto take_in = [&](unsigned left, unsigned (&wv)[REGS]) {
+#pragma unroll
+        for (int c = 0; c < REGS; ++c) {
+            asm volatile("" : "+v"(wv[c]) : : "memory");    // nothing below (the stores least of all) moves above the wait
+            wv[c] = in_period[c] < left ? wv[c] : 0u;
+        }
+    };
+    unsigned wv_cur[REGS], wv_nxt[REGS];
+    unsigned left = left_at(0), left_nxt = left_at(STEP);
+    request(0, left, wv_cur);
+    request(STEP, left_nxt, wv_nxt);
+    take_in(left, wv_cur);
+    take_in(left_nxt, wv_nxt);
+
+    for (int64_t i0 = 0; i0 < max_len; i0 += STEP) {
+        unsigned wv_far[REGS], won[REGS];
+        const unsigned left_far = left_at(i0 + 2 * STEP);
+        request(i0 + 2 * STEP, left_far, wv_far);
+#pragma unroll
+        for (int c = 0; c < REGS; ++c) won[c] = 0;
+        if (!exact) {
+            unsigned big = 0;
+#pragma unroll
+            for (int c = 0; c < REGS; ++c) big |= (wv_cur[c] > W_LIMIT) ? 1u : 0u;
+            if (__ballot(big != 0) != 0ull) {       // leave the packed keys for good: lane r takes the entry of rail r
+                exact = true;
+                for (int place = 0; place < N; ++place) {
+                    const unsigned key = ~(unsigned)__shfl((int)t, row_base | place);
+                    if (in_list && (key & MASK) == r) load = base + (unsigned long long)(key >> S);
+                }
+            }
+        }
+        bool closed = false;                        // wave-uniform
+        unsigned w0 = 0;
+        if (RUNS && !exact) {
+            const bool done = left == 0u;           // this row's instance is already finished
+            w0 = row_lane<0>(wv_cur[0]);
+            bool same = true;
+#pragma unroll
+            for (int c = 0; c < REGS; ++c) same = same && (wv_cur[c] == w0);
+            const unsigned dmin = (~list_head<true>(t)) >> S;
+            const unsigned dmax = (~(unsigned)__shfl((int)t, row_base | (N - 1))) >> S;
+            const bool ok = done || (same && w0 != 0u && left >= (unsigned)STEP && (dmax - dmin) < w0);
+            closed = __ballot(!ok) == 0ull;
+            if (closed && !done) {
+                // equal weights from loads within one weight of each other: the list is visited front to back, round after
+                // round, and afterwards the places that took one chunk fewer come first: the list rotated by STEP mod N
+#pragma unroll
+                for (int c = 0; c < REGS; ++c) won[c] = (~(unsigned)__shfl((int)t, place_of_chunk[c])) & MASK;
+                const unsigned grown = t - ((w0 * (per_rank + (r < extra ? 1u : 0u))) << S);
+                const unsigned moved = (unsigned)__shfl((int)grown, after_closed);
+                t = in_list ? moved : 0u;
+            }
+        }
+        if (closed) {
+        } else if (!exact) {
+#pragma unroll
+            for (int c = 0; c < REGS; ++c) {
+                rows_steps<0>(t, won[c], wv_cur[c] << S);
+                won[c] = ~won[c] & MASK;
+            }
+        } else {
+            exact_steps<LW, STEP>(load, wv_cur, won, r);
+        }
+        if (!exact) {
+            // the emptiest rail's delta moves into the base, so deltas stay below the packing limit
+            const unsigned adv = (~list_head<true>(t)) >> S;
+            if (in_list) { t += adv << S; base += adv; }
+        }
+        take_in(left_far, wv_far);
+        uint8_t *const to = rail + beg + i0 + r;
+#pragma unroll
+        for (int c = 0; c < REGS; ++c)
+            if (in_period[c] < left) to[c * LW] = (uint8_t)won[c];
+#pragma unroll
+        for (int c = 0; c < REGS; ++c) { wv_cur[c] = wv_nxt[c]; wv_nxt[c] = wv_far[c]; }
+        left = left_nxt; left_nxt = left_far;
+    }
+    if (in_list) {
+        if (exact) {
+            S_out[(int64_t)inst * N + r] = (int64_t)load;
+        } else {
+            const unsigned key = ~t;
+            S_out[(int64_t)inst * N + (key & MASK)] = (int64_t)(base + (unsigned long long)(key >> S));
+        }
+    }
+    if (!RUNS) __builtin_amdgcn_s_setprio(0);
+    }
+}
+
 // Instances in descending order of chain length, to within the resolution of 512 buckets (a sixteenth of the length): counting
 // sort by one workgroup.  RUNS: S[inst*N] holds the length of the instance's leading run, which the serial kernel skips.
 // Also sets the counters of the queue: next_group[0] = first group the packed wavefronts take, [1] = 0 (next instance to run
@@ -553,11 +763,38 @@ static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, 
                              int64_t *S, int64_t capacity, void *ws, hipStream_t st)
 {
     constexpr int IPW = 64 / GW;
-    // Wide while the instances make at most three wavefronts per SIMD (256 CUs x 4 SIMDs): a wide chain takes 16 ns per
-    // step alone on its SIMD, 25 with a second wavefront, 35 with a third, 46 with a fourth, and a packed wavefront
-    // 34-38 ns per step however few there are (measured, N = 4, 8, 16).  N = 32: 22, 28, 42, 53, 75 (six) against
-    // 64-74 packed, so up to five.
-    const bool packed = IPW > 1 && n_inst > (int64_t)(GW <= 16 ? 3 : 5) * 1024;
+    // Three shapes (ns per greedy step and instance-carrying wavefront, measured on batches of equal chains, N = 4, 8, 16):
+    //   wide   one instance per wavefront:      16 alone on a SIMD, 25 / 35 / 46 with two / three / four wavefronts on it
+    //   rows   four per wavefront (N <= 16):    17-20 up to one wavefront per SIMD, 26 with two, 46 with four
+    //   packed 64/GW per wavefront:             34-39 however few, 41 at 16 384 instances (N = 16: 72)
+    // so: wide up to one wavefront per SIMD (256 CUs x 4 SIMDs), then rows up to 16 384 instances (always for groups of 16
+    // lanes, which pack no denser than rows do), then packed.  N = 32 has no rows shape: wide takes 22 / 28 / 42 / 53 / 75
+    // with one to six wavefronts on a SIMD against 64-74 packed, so wide up to five.
+    constexpr int64_t kWideMax = GW <= 16 ? 1024 : 5 * 1024;
+    constexpr int64_t kRowsMax = GW == 16 ? INT64_MAX : 16384;
+    const bool packed = IPW > 1 && n_inst > kWideMax;
+    if constexpr (GW <= 16) {
+        if (packed && n_inst <= kRowsMax) {
+            constexpr int RPW = 4;
+            const int64_t waves = (n_inst + RPW - 1) / RPW;
+            int64_t blocks = (waves + kLptWaves - 1) / kLptWaves;
+            if (ws && !RUNS) {
+                // heavy-tailed batches: longest first from a queue, two resident wavefronts per SIMD (four: a fifth slower at 12 288 instances)
+                uint32_t *order = static_cast<uint32_t *>(ws);
+                unsigned *counter = reinterpret_cast<unsigned *>(static_cast<char *>(ws) + align_up(sizeof(uint32_t) * (size_t)n_inst, 256));
+                hipLaunchKernelGGL((lpt_order_kernel<RUNS>), dim3(1), dim3(1024), 0, st, chunk_off, S, (int)n_inst, N, RPW, order, counter);
+                if (int rc = launch_status()) return rc;
+                const int64_t resident = 256 * 4 * 2 / kLptWaves;
+                if (blocks > resident) blocks = resident;
+                hipLaunchKernelGGL((lpt_rows_kernel<GW, RUNS, true>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
+                                   chunk_w, (int)n_inst, N, rail, S, capacity, order, counter);
+            } else {
+                hipLaunchKernelGGL((lpt_rows_kernel<GW, RUNS, false>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
+                                   chunk_w, (int)n_inst, N, rail, S, capacity, nullptr, nullptr);
+            }
+            return launch_status();
+        }
+    }
     if (packed && ws && !RUNS) {                    // behind the closed forms the chains are a few hundred tails each: nothing to order
         // Three resident wavefronts per SIMD: with the longest chains alone on a wavefront each (and at a raised issue
         // priority) a fourth only slows those chains, which the launch waits for, and with two the SIMDs idle between
