@@ -24,7 +24,8 @@
 // all chunks of all instances at once (lpt_prefix_kernel), which also finds, per instance, where the
 // run ends.  The serial kernels then start behind it with the closed-form loads.
 //
-// Two launch shapes.  "Packed": 64/GW instances share a wavefront, one per lane group, so one
+// Three launch shapes (the third, "rows", four instances per wavefront in the sorted form, sits between the two
+// described here and has its own comment further down).  "Packed": 64/GW instances share a wavefront, one per lane group, so one
 // instruction stream advances several schedulers - the shape for tens of thousands of instances,
 // where issue slots are the limit.  "Wide": one instance per wavefront, its state replicated in
 // every row of lanes, all 64 lanes streaming weights and writing rails - the shape for few instances,
