@@ -482,10 +482,10 @@ def _lpt_case(weights_per_inst, M, N, batch=1):
     topo = rs.Topo(M, N, 1 << 20)
     wt = torch.from_numpy(w.view(np.int32).copy()).to(DEV) if w.size else torch.zeros(1, dtype=torch.int32, device=DEV)
     rail_c, S_c = oracle.lpt_batch(off, w, batch, M, N)
-    for chunkwise in (False, True):
-        rail, S = rs.lpt_spray(torch.from_numpy(off).to(DEV), wt, batch, topo, chunkwise=chunkwise)
-        assert np.array_equal(rail.cpu().numpy()[:w.size], rail_c), f"rail, chunkwise={chunkwise}"
-        assert np.array_equal(S.cpu().numpy(), S_c), f"S, chunkwise={chunkwise}"
+    for chunkwise, ws in ((False, "auto"), (True, "auto"), (True, None)):      # with the optional workspace and without
+        rail, S = rs.lpt_spray(torch.from_numpy(off).to(DEV), wt, batch, topo, chunkwise=chunkwise, ws=ws)
+        assert np.array_equal(rail.cpu().numpy()[:w.size], rail_c), f"rail, chunkwise={chunkwise}, ws={ws}"
+        assert np.array_equal(S.cpu().numpy(), S_c), f"S, chunkwise={chunkwise}, ws={ws}"
 
 
 @pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 8, 11, 16, 24, 32, 40, 64])
@@ -572,12 +572,12 @@ def test_lpt_chunk_lists_from_stage3_shapes():
     _lpt_case(insts, 8, 8, batch=5)
 
 
-@pytest.mark.parametrize("N", [1, 2, 3, 4, 7, 8, 13, 16, 20, 32])
-def test_lpt_packed_shape_many_instances(N):
-    # enough instances that several share a wavefront (one per lane group): ragged lengths, runs, mixed weights
+def _many_instances_case(N, n_inst, per_wave, period, seed):
+    """Ragged lengths, runs, mixed weights, one instance that drags its wavefront onto the exact path, and weights at, one
+    above and around the packing limit (periods of `period` chunks), in wavefronts of their own (`per_wave` instances each),
+    with loads that pass 2^32."""
     gw = 4 if N <= 4 else 8 if N <= 8 else 16 if N <= 16 else 32
-    n_inst = 2048 * (64 // gw) + 37
-    rng = np.random.default_rng(900 + N)
+    rng = np.random.default_rng(seed)
     lens = rng.integers(0, 120, size=n_inst)
     lens[rng.random(n_inst) < 0.02] = 0
     lens[:50] = rng.integers(300, 900, size=50)
@@ -594,15 +594,28 @@ def test_lpt_packed_shape_many_instances(N):
             w = rng.integers(0, 1 << 20, size=n)
         insts.append(w)
     insts[7] = np.concatenate([[5_000_000_00], rng.integers(0, 1 << 30, size=40)])   # drags its wavefront onto the exact path
-    # weights at, one above and around the packing limit of this shape (periods of 64 chunks, 32 for groups of 4 lanes),
-    # in wavefronts of their own, with loads that pass 2^32
-    lim = ((0xFFFFFFFF >> (gw.bit_length() - 1)) // ((32 if gw == 4 else 64) + 2)) - 1
-    per_wave = 64 // gw
+    lim = ((0xFFFFFFFF >> (gw.bit_length() - 1)) // (period + 2)) - 1
     insts[20 * per_wave] = np.full(700, lim)
     insts[30 * per_wave + 1] = np.full(700, lim + 1)
     insts[40 * per_wave] = np.concatenate([np.full(300, lim), np.arange(300, 0, -1)])
-    insts[50 * per_wave] = np.concatenate([np.full(130, lim), [lim + 1], np.full(130, lim - 1)])   # leaves the packed form mid-way
+    insts[50 * per_wave] = np.concatenate([np.full(130, lim), [lim + 1], np.full(130, lim - 1)])   # leaves the packed keys mid-way
+    insts[60 * per_wave + 2] = np.concatenate([np.full(1000, 4096), np.full(333, 4095), np.full(200, 7)])   # long closed-form runs
     _lpt_case(insts, 1, N, batch=n_inst)                      # one node per matrix, n_inst matrices
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 7, 8, 20, 32])
+def test_lpt_packed_shape_many_instances(N):
+    # enough instances that the packed shape is taken: several share a wavefront, one per lane group
+    gw = 4 if N <= 4 else 8 if N <= 8 else 32
+    n_inst = (2048 * (64 // gw) if gw < 32 else 5200) + 37
+    _many_instances_case(N, n_inst, 64 // gw, 32 if gw == 4 else 64, 900 + N)
+
+
+@pytest.mark.parametrize("N,n_inst", [(1, 1100), (3, 4133), (4, 2500), (5, 4133), (8, 4133), (8, 16000), (11, 1400), (13, 8229), (16, 8229),
+                                      (16, 20000)])
+def test_lpt_rows_shape_many_instances(N, n_inst):
+    # four instances per wavefront, one per row of 16 lanes: the shape between the wide and the packed one (N <= 16)
+    _many_instances_case(N, n_inst, 4, 64, 1900 + N)
 
 
 def test_lpt_many_instances():
