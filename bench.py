@@ -144,7 +144,10 @@ def write_probe(torch, plan, total, reps=5):
     cut = lambda n: n - n % (1 << 20)
     arrs = [a[:cut(total)] for a in (plan.chunk_w, plan.chunk_flow, plan.perm) if a is not None]
     arrs.append(plan.rail[:4 * cut(total // 4)].view(torch.int32))
+    arrs = [a for a in arrs if a.numel()]
     nbytes = sum(a.numel() * a.element_size() for a in arrs)
+    if nbytes == 0:
+        return None
     ts = []
     for _ in range(reps):
         e0 = _event(torch)
