@@ -889,12 +889,18 @@ def _cpu_model():
 
 
 def _name_the_cpu(rec, model):
-    """Every cpu_baseline object says which CPU the oracle ran on."""
+    """Every cpu_baseline object says which CPU the oracle ran on and how the record's GPU rate compares (same unit)."""
     if isinstance(rec, dict):
         for k, v in rec.items():
             if k == "cpu_baseline" and isinstance(v, dict):
                 v["cpu_model"] = model
                 v["host_cpus"] = os.cpu_count()
+                gpu = rec.get("value") if rec.get("unit") == v.get("unit") else None
+                if gpu and v.get("value"):
+                    v["gpu_over_cpu"] = gpu / v["value"]
+                    one = v.get("single_thread")
+                    if isinstance(one, dict) and one.get("value") and one.get("unit") == v.get("unit"):
+                        one["gpu_over_cpu"] = gpu / one["value"]
             else:
                 _name_the_cpu(v, model)
 
