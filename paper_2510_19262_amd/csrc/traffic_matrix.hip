@@ -14,7 +14,8 @@
 
 namespace rs {
 
-constexpr int kTmThreads = 256;
+constexpr int kTmThreads = 256;    // a slice's workgroup
+constexpr int kTmThreadsWhole = 1024;   // the workgroup that takes a whole (matrix, source GPU) pair
 constexpr int kTmTableMax = 8192;   // placement entries staged in LDS (32 KiB)
 
 struct TmArgs {
@@ -46,8 +47,8 @@ __device__ __forceinline__ void tm_count(const TmArgs &a, const int32_t *table, 
 
 constexpr int kTmUnroll = 4;        // 16-byte index loads in flight per thread
 
-template <bool FAST, bool TABLE_LDS>
-__global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
+template <bool FAST, bool TABLE_LDS, int THREADS>
+__global__ __launch_bounds__(THREADS) void traffic_matrix_kernel(TmArgs a)
 {
     extern __shared__ unsigned tm_lds[];
     // [copies][G] counters.  Lanes whose tokens share a replica index rho - every lanes_per_period-th
@@ -64,11 +65,11 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
     const int32_t *src = a.topk_idx + pair * a.slots_per_gpu;
     const bool aligned = (reinterpret_cast<uintptr_t>(src) % 16) == 0;
     const int64_t qfull = aligned ? (a.slots_per_gpu / 4 < qhi ? a.slots_per_gpu / 4 : qhi) : qlo;   // whole, aligned quads
-    constexpr int64_t kStep = (int64_t)kTmUnroll * kTmThreads;
-    auto whole_step = [&](int64_t q) { return q + (int64_t)(kTmUnroll - 1) * kTmThreads < qfull; };
+    constexpr int64_t kStep = (int64_t)kTmUnroll * THREADS;
+    auto whole_step = [&](int64_t q) { return q + (int64_t)(kTmUnroll - 1) * THREADS < qfull; };
     auto request = [&](int64_t q, int4 (&e)[kTmUnroll]) {
 #pragma unroll
-        for (int u = 0; u < kTmUnroll; ++u) e[u] = *reinterpret_cast<const int4 *>(src + (q + (int64_t)u * kTmThreads) * 4);
+        for (int u = 0; u < kTmUnroll; ++u) e[u] = *reinterpret_cast<const int4 *>(src + (q + (int64_t)u * THREADS) * 4);
     };
     // the first step's indices are requested before the histogram is cleared and the table staged, every later step's
     // before the step in hand is counted: the loads of a short-lived workgroup are in flight from its first instruction on
@@ -77,9 +78,9 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
     bool have = whole_step(qd);
     if (have) request(qd, cur);
 
-    for (int i = threadIdx.x; i < a.bin_stride * a.copies; i += kTmThreads) all_bins[i] = 0;
+    for (int i = threadIdx.x; i < a.bin_stride * a.copies; i += THREADS) all_bins[i] = 0;
     if (TABLE_LDS)
-        for (int i = threadIdx.x; i < a.E * a.R; i += kTmThreads) lds_table[i] = a.expert_gpu[i];
+        for (int i = threadIdx.x; i < a.E * a.R; i += THREADS) lds_table[i] = a.expert_gpu[i];
     __syncthreads();
     // one definite kind of memory per instantiation: through a pointer that may be LDS or global every lookup is a
     // flat load, which waits for all of the wavefront's memory traffic
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
         if (more) request(qd + kStep, nxt);
 #pragma unroll
         for (int u = 0; u < kTmUnroll; ++u) {
-            const int64_t s0 = (qd + (int64_t)u * kTmThreads) * 4;
+            const int64_t s0 = (qd + (int64_t)u * THREADS) * 4;
             tm_count<FAST>(a, table, bins, s0 + 0, cur[u].x);
             tm_count<FAST>(a, table, bins, s0 + 1, cur[u].y);
             tm_count<FAST>(a, table, bins, s0 + 2, cur[u].z);
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
             for (int u = 0; u < kTmUnroll; ++u) cur[u] = nxt[u];
         }
     }
-    for (; qd < qhi; qd += kTmThreads) {
+    for (; qd < qhi; qd += THREADS) {
         const int64_t s0 = qd * 4;
         for (int j = 0; j < 4; ++j)
             if (s0 + j < a.slots_per_gpu) tm_count<FAST>(a, table, bins, s0 + j, src[s0 + j]);
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(kTmThreads) void traffic_matrix_kernel(TmArgs a)
     __syncthreads();
 
     int64_t *dst = a.D1 + pair * a.G;
-    for (int i = threadIdx.x; i < a.G; i += kTmThreads) {
+    for (int i = threadIdx.x; i < a.G; i += THREADS) {
         unsigned cnt = 0;
         for (int c = 0; c < a.copies; ++c) cnt += all_bins[(size_t)c * a.bin_stride + i];
         if (a.splits == 1) dst[i] = (int64_t)cnt * a.payload;           // sole owner of the pair
@@ -128,6 +129,10 @@ namespace rs {
 // its index bytes
 static int64_t tm_splits(int64_t slots_per_gpu, int64_t G, int64_t pairs)
 {
+    // Enough pairs to fill the chip twice over and few enough slots each: one workgroup of 1024 threads takes the whole pair
+    // and writes its D1 row itself - no slice counts, no second kernel (a DeepSeek-V3-shaped layer: 512 pairs of 65 536 slots,
+    // 0.038 -> 0.03 ms).
+    if (pairs >= 512 && slots_per_gpu <= (int64_t)kTmThreadsWhole * 4 * 32) return 1;
     const int64_t unit = (int64_t)kTmThreads * kTmUnroll * 4;            // slots one workgroup covers per step
     int64_t slice = unit;
     while (slice < 32 * G) slice += unit;
@@ -170,19 +175,22 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
     a.k = k; a.kshift = is_pow2(k) ? ilog2(k) : -1;
     a.E = E; a.R = R; a.rmask = is_pow2(R) ? R - 1 : -1;
     a.G = (int32_t)G;
+    const int64_t pairs = (int64_t)batch * G;
+    const int64_t splits = tm_splits(a.slots_per_gpu, G, pairs);
+    if (pairs * splits > 0x7FFFFFFFll) return RAILSCHED_ERR_UNSUPPORTED;
+    const bool whole = splits == 1 && pairs >= 512 && a.slots_per_gpu > (int64_t)kTmThreads * 4;   // see tm_splits
     a.copies = 1;
-    // as many copies as keep a workgroup's LDS (bins + table) within 20 KiB: eight workgroups, all the wavefronts a CU takes
+    // as many copies as keep a workgroup's LDS (bins + table) within 20 KiB: eight workgroups of 256, all the wavefronts a CU
+    // takes (two workgroups of 1024 have 80 KiB each, which the 8192-word bound keeps them far from)
     const int64_t table_words = (int64_t)E * R <= kTmTableMax ? (int64_t)E * R : 0;     // a larger table stays in global memory
-    while (a.copies < 8 && (int64_t)a.copies * 2 * (G | 1) <= 8192 && 4 * ((int64_t)a.copies * 2 * (G | 1) + table_words) <= 20 * 1024)
+    while (a.copies < 8 && (int64_t)a.copies * 2 * (G | 1) <= 8192 &&
+           (whole || 4 * ((int64_t)a.copies * 2 * (G | 1) + table_words) <= 20 * 1024))
         a.copies *= 2;
     // a lane holds 4 consecutive slots, so rho repeats every R*k/4 lanes when that is a whole number
     a.lanes_per_period = ((int64_t)R * k % 4 == 0 && (int64_t)R * k / 4 <= 64) ? (int32_t)((int64_t)R * k / 4) : 1;
     a.bin_stride = (int32_t)(a.copies > 1 ? (G | 1) : G);
     a.table_in_lds = ((int64_t)E * R <= kTmTableMax && 4 * (a.copies * (int64_t)a.bin_stride + (int64_t)E * R) <= 64 * 1024) ? 1 : 0;
 
-    const int64_t pairs = (int64_t)batch * G;
-    const int64_t splits = tm_splits(a.slots_per_gpu, G, pairs);
-    if (pairs * splits > 0x7FFFFFFFll) return RAILSCHED_ERR_UNSUPPORTED;
     a.splits = (int32_t)splits;
     a.partial = static_cast<uint32_t *>(ws);
     if (splits > 1) {
@@ -192,10 +200,19 @@ extern "C" int railsched_traffic_matrix(const int32_t *topk_idx, int32_t batch, 
     const size_t lds = sizeof(unsigned) * (size_t)a.bin_stride * a.copies + (a.table_in_lds ? sizeof(int32_t) * (size_t)E * R : 0);
     const dim3 grid((unsigned)(pairs * splits));
     const bool fast = a.kshift >= 0 && a.rmask >= 0;
-    if (fast && a.table_in_lds) hipLaunchKernelGGL((traffic_matrix_kernel<true, true>), grid, dim3(kTmThreads), lds, st, a);
-    else if (fast) hipLaunchKernelGGL((traffic_matrix_kernel<true, false>), grid, dim3(kTmThreads), lds, st, a);
-    else if (a.table_in_lds) hipLaunchKernelGGL((traffic_matrix_kernel<false, true>), grid, dim3(kTmThreads), lds, st, a);
-    else hipLaunchKernelGGL((traffic_matrix_kernel<false, false>), grid, dim3(kTmThreads), lds, st, a);
+    if (whole) {
+        constexpr int T = kTmThreadsWhole;
+        if (fast && a.table_in_lds) hipLaunchKernelGGL((traffic_matrix_kernel<true, true, T>), grid, dim3(T), lds, st, a);
+        else if (fast) hipLaunchKernelGGL((traffic_matrix_kernel<true, false, T>), grid, dim3(T), lds, st, a);
+        else if (a.table_in_lds) hipLaunchKernelGGL((traffic_matrix_kernel<false, true, T>), grid, dim3(T), lds, st, a);
+        else hipLaunchKernelGGL((traffic_matrix_kernel<false, false, T>), grid, dim3(T), lds, st, a);
+    } else {
+        constexpr int T = kTmThreads;
+        if (fast && a.table_in_lds) hipLaunchKernelGGL((traffic_matrix_kernel<true, true, T>), grid, dim3(T), lds, st, a);
+        else if (fast) hipLaunchKernelGGL((traffic_matrix_kernel<true, false, T>), grid, dim3(T), lds, st, a);
+        else if (a.table_in_lds) hipLaunchKernelGGL((traffic_matrix_kernel<false, true, T>), grid, dim3(T), lds, st, a);
+        else hipLaunchKernelGGL((traffic_matrix_kernel<false, false, T>), grid, dim3(T), lds, st, a);
+    }
     if (int rc = launch_status()) return rc;
     if (splits > 1) return launch_count_reduce(a.partial, D1, pairs * G, (int)G, (int)splits, payload_bytes, st);
     return RAILSCHED_OK;
