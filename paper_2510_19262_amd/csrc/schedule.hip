@@ -187,7 +187,7 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
                 uint32_t nxt = st_fs[j + 1];
                 uint32_t base = st_cs[j] - st_fs[j];                     // canonical position = base + p
                 uint32_t fl[4], pm[4], rr = 0;
-                uint32_t r = p % (uint32_t)N;
+                uint32_t r = x.nshift >= 0 ? (p & ((1u << x.nshift) - 1u)) : p % (uint32_t)N;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     while (p + e >= nxt) { ++j; nxt = st_fs[j + 1]; base = st_cs[j] - st_fs[j]; }
@@ -233,7 +233,8 @@ __global__ __launch_bounds__(kSsThreads) void ss_instance_kernel(CsArgs a, SsArg
             const int node = ss_dst_node(a, x, (uint32_t)f);
             for (int n = 0; n < N; ++n) {
                 // positions i < v with i mod N == n number (v + N - 1 - n) / N
-                const uint32_t c = (e + (uint32_t)(N - 1 - n)) / (uint32_t)N - (s + (uint32_t)(N - 1 - n)) / (uint32_t)N;
+                const uint32_t up = (uint32_t)(N - 1 - n);
+                const uint32_t c = x.nshift >= 0 ? ((e + up) >> x.nshift) - ((s + up) >> x.nshift) : (e + up) / (uint32_t)N - (s + up) / (uint32_t)N;
                 if (c) atomicAdd(&bins[node * N + n], (unsigned long long)c * (unsigned long long)cw);
             }
         }
@@ -273,7 +274,8 @@ __global__ __launch_bounds__(kSlThreads) void sl_recv_kernel(CsArgs a, SsArgs x)
         const int node = ss_dst_node(a, x, (uint32_t)f);
         for (int n = 0; n < N; ++n) {
             // positions i < v with i mod N == n number (v + N - 1 - n) / N
-            const uint32_t c = (e + (uint32_t)(N - 1 - n)) / (uint32_t)N - (s + (uint32_t)(N - 1 - n)) / (uint32_t)N;
+            const uint32_t up = (uint32_t)(N - 1 - n);
+            const uint32_t c = x.nshift >= 0 ? ((e + up) >> x.nshift) - ((s + up) >> x.nshift) : (e + up) / (uint32_t)N - (s + up) / (uint32_t)N;
             if (c) atomicAdd(&sl_bins[node * N + n], (unsigned long long)c * (unsigned long long)cw);
         }
     }
