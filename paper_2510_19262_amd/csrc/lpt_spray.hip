@@ -796,6 +796,8 @@ static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, 
             return launch_status();
         }
     }
+    constexpr bool kHasPacked = IPW > 1 && GW != 16;   // groups of 16 lanes always take the rows shape
+    if constexpr (kHasPacked) {
     if (packed && ws && !RUNS) {                    // behind the closed forms the chains are a few hundred tails each: nothing to order
         // Three resident wavefronts per SIMD: with the longest chains alone on a wavefront each (and at a raised issue
         // priority) a fourth only slows those chains, which the launch waits for, and with two the SIMDs idle between
@@ -810,16 +812,18 @@ static int launch_lpt_serial(const int64_t *chunk_off, const uint32_t *chunk_w, 
         if (blocks > resident) blocks = resident;
         hipLaunchKernelGGL((lpt_packed_kernel<GW, RUNS, true>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
                            chunk_w, (int)n_inst, N, rail, S, capacity, order, counter);
+        return launch_status();
     } else if (packed) {
         const int64_t waves = (n_inst + IPW - 1) / IPW;
         const int64_t blocks = (waves + kLptWaves - 1) / kLptWaves;
         hipLaunchKernelGGL((lpt_packed_kernel<GW, RUNS, false>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
                            chunk_w, (int)n_inst, N, rail, S, capacity, nullptr, nullptr);
-    } else {
-        const int64_t blocks = (n_inst + kLptWaves - 1) / kLptWaves;
-        hipLaunchKernelGGL((lpt_wide_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
-                           chunk_w, (int)n_inst, N, rail, S, capacity);
+        return launch_status();
     }
+    }
+    const int64_t blocks = (n_inst + kLptWaves - 1) / kLptWaves;
+    hipLaunchKernelGGL((lpt_wide_kernel<GW, RUNS>), dim3((unsigned)blocks), dim3(64 * kLptWaves), 0, st, chunk_off,
+                       chunk_w, (int)n_inst, N, rail, S, capacity);
     return launch_status();
 }
 
