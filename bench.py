@@ -134,6 +134,28 @@ def measure_streams(torch, dev, reps=7):
     return res
 
 
+def profiled_kernel_us(kernel, workload):
+    """Average duration (us) of `kernel` in the rocprofv3 --kernel-trace --stats run summarised under profiles/ for `workload`
+    (first table of the summary; the average runs over every call of the kernel in that run), or None."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    for name in sorted(os.listdir(pdir)):
+        if not name.startswith(workload + "_") or not name.endswith((".md", ".txt")):
+            continue
+        in_table = False
+        for line in open(os.path.join(pdir, name)):
+            if line.startswith("## "):
+                in_table = line.startswith("## Kernel durations")
+            elif in_table and line.startswith("| " + kernel):
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                try:
+                    return float(cells[2])
+                except (IndexError, ValueError):
+                    return None
+    return None
+
+
 def write_probe(torch, plan, total, reps=5):
     """Plain fills of the record arrays a schedule call writes (weights, flows, the permutation if kept, rails), `total`
     records each: the same bytes written by a kernel that does nothing else (torch's fill, one launch per array; the rail
@@ -170,6 +192,10 @@ def hbm_roofline(kernel, workload, algorithmic_bytes, ms, note=None, counted=Non
          "avg_launch_ms": ms}
     if MEASURED.get("copy_GBps"):
         r["frac_of_measured_copy"] = gbps / MEASURED["copy_GBps"]
+    us = profiled_kernel_us(kernel.split(" ")[0], workload)
+    if us:   # the dominant kernel alone, as the committed profile timed it (the call above also holds its small companions)
+        r["profiled_kernel_avg_us"] = us
+        r["frac_at_profiled_kernel_time"] = algorithmic_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS
     if note:
         r["note"] = note
     return r
